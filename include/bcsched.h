@@ -1,0 +1,139 @@
+/*
+ * bcsched.h -- C ABI of libbcsched: round-optimal n-block broadcast schedules
+ * on a p-processor circulant graph, constructed on one AMD MI355X (gfx950).
+ *
+ * Method: J. L. Traff, "(Poly)Logarithmic Time Construction of Round-optimal
+ * n-Block Broadcast Schedules for Broadcast and irregular Allgather in MPI"
+ * (arXiv 2205.10072), Section 2.  Citations below name that paper's sections,
+ * algorithms and tables.
+ *
+ * Vocabulary (Section 2): p ranks 0..p-1; q = ceil(log2 p); skips[0..q] with
+ * skips[q] = p and skips[k-1] = ceil(skips[k]/2) (Alg. 1); in slot k a rank r
+ * sends to (r + skips[k]) mod p and receives from (r - skips[k] + p) mod p.
+ * A rank's receive schedule recvsched[0..q-1] (Alg. 4) and send schedule
+ * sendsched[0..q-1] (Alg. 5) hold block numbers relative to the current phase
+ * of q rounds: one non-negative entry (the baseblock, Alg. 2) and negative
+ * entries b - q for blocks of the previous phase.
+ *
+ * Conventions of every call
+ *   - "device" pointers are HIP device memory on the current device, owned by
+ *     the caller, at least 4-byte aligned; "host" pointers are plain memory.
+ *   - All tables are int32, row-major, one row per rank.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Work is enqueued on it; no call waits for the device.
+ *   - Return value: BCS_OK (0) or a negative BCS_E* code.  On an error nothing
+ *     has been enqueued and no output is touched.  No call throws.
+ *   - No call allocates or frees its outputs.  bcs_sched* with a send table
+ *     over the full rank range need scratch memory: the *_ws variants take it
+ *     from the caller, the plain variants keep one allocation per device that
+ *     grows on demand and is released by bcs_release().  Calls that share that
+ *     allocation must be ordered on one stream.
+ */
+#ifndef BCSCHED_H
+#define BCSCHED_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define BCS_OK        0
+#define BCS_EINVAL  (-1)  /* an argument is outside its domain (see each call)        */
+#define BCS_EHIP    (-2)  /* a HIP call failed; bcs_last_hip_error() has its code      */
+#define BCS_ENOMEM  (-3)  /* scratch allocation failed, or the given workspace is small */
+
+#define BCS_MAX_Q         31           /* p <= 2^31 - 1                                */
+#define BCS_BATCH_STRIDE  32           /* ints per row of the batch tables             */
+#define BCS_BATCH_PAD     INT32_MIN    /* fills batch row entries k >= q               */
+#define BCS_NO_BLOCK      (-1)         /* expanded tables: nothing moves in this round */
+
+/* q = ceil(log2 p) (Section 2, first paragraph).  p = 1 gives 0.
+ * Returns BCS_EINVAL for p < 1. */
+int bcs_q(int32_t p);
+
+/* Alg. 1.  Writes skips[0..q] (q+1 values) to host memory `skips_host` and
+ * returns q.  BCS_EINVAL for p < 1 or a NULL pointer. */
+int bcs_skips(int32_t p, int32_t *skips_host);
+
+/* Number of rounds of the n-block broadcast, n - 1 + q (Section 1; Alg. 6).
+ * Returns BCS_EINVAL (as int64) for p < 1 or n < 1. */
+int64_t bcs_rounds(int32_t p, int32_t n);
+
+/* Receive and send schedules (Alg. 4; Alg. 5 / first loops of Alg. 9) of the
+ * ranks r0 <= r < r1 for a broadcast rooted at rank 0.
+ *   recv_out, send_out: device, (r1-r0) x q int32, entry [(r-r0)*q + k].
+ *   Either may be NULL (that table is not produced); both NULL is an error.
+ * When the call covers all ranks (r0 = 0, r1 = p) send rows are read off the
+ * receive rows of the to-neighbours (Alg. 9, second loop); otherwise each send
+ * entry is recomputed from the neighbour's receive schedule (Alg. 5).  Both
+ * give the same values.
+ * p = 1: q = 0, rows are empty, nothing is enqueued, BCS_OK.
+ * BCS_EINVAL: p < 1, r0 < 0, r0 > r1, r1 > p, both outputs NULL. */
+int bcs_sched(int32_t p, int32_t r0, int32_t r1,
+              int32_t *recv_out, int32_t *send_out, void *stream);
+
+/* As bcs_sched for an arbitrary root: the row of rank r is the schedule of
+ * the virtual rank (r - root + p) mod p (Section 2, paragraph after Alg. 2;
+ * Section 2.5 uses this for every root at once).  Neighbours are unchanged:
+ * rank r still sends to (r + skips[k]) mod p.
+ * Also BCS_EINVAL for root outside [0, p). */
+int bcs_sched_rooted(int32_t p, int32_t root, int32_t r0, int32_t r1,
+                     int32_t *recv_out, int32_t *send_out, void *stream);
+
+/* Scratch bytes bcs_sched_rooted_ws needs for these arguments (0 when none).
+ * Negative: BCS_EINVAL. */
+int64_t bcs_sched_workspace_bytes(int32_t p, int32_t r0, int32_t r1, int want_send);
+
+/* bcs_sched_rooted with caller-provided scratch.  `workspace` is device
+ * memory, 256-byte aligned, of at least bcs_sched_workspace_bytes(...) bytes;
+ * its contents are undefined afterwards.  BCS_ENOMEM if it is too small or
+ * NULL while scratch is needed.  Performs no allocation. */
+int bcs_sched_rooted_ws(int32_t p, int32_t root, int32_t r0, int32_t r1,
+                        int32_t *recv_out, int32_t *send_out,
+                        void *workspace, size_t workspace_bytes, void *stream);
+
+/* `count` unrelated problems: problem i is rank r[i] of a p[i]-rank graph with
+ * broadcast root root[i].  p, r, root: device arrays of `count` int32.
+ *   recv_out, send_out: device, count x BCS_BATCH_STRIDE int32; row i holds
+ *   q_i = ceil(log2 p[i]) entries, the rest BCS_BATCH_PAD.  Either may be NULL.
+ *   q_out: device, count int32, may be NULL.
+ * Send rows are recomputed per Alg. 5 (no other rank of that graph is there).
+ * Triples are validated on the device: a row with p < 1 or r, root outside
+ * [0, p) gets q_out = -1 and all-PAD rows; host-side errors are BCS_EINVAL for
+ * count < 0, a NULL input array, or all outputs NULL. */
+int bcs_sched_batch(int64_t count, const int32_t *p, const int32_t *r, const int32_t *root,
+                    int32_t *recv_out, int32_t *send_out, int32_t *q_out, void *stream);
+
+/* The (rank, round) -> block tables of the n-block broadcast (index arithmetic
+ * of Alg. 6: x = (q - (n-1+q) mod q) mod q dummy rounds, entries shifted by -x,
+ * slot k = (x+j) mod q in real round j, +q per phase; caption of Alg. 6: a
+ * negative block means nothing is sent / received, a block above n-1 is n-1).
+ *   recv, send: device, (r1-r0) x q, as produced by bcs_sched*; either may be
+ *   NULL together with its output.
+ *   recv_blocks, send_blocks: device, (r1-r0) x R int32, R = n-1+q, entry
+ *   [(r-r0)*R + j] = block moved in round j, or BCS_NO_BLOCK.
+ * p = 1: q = 0, the input tables have empty rows and are ignored (may be
+ * NULL); each output given gets R = n-1 columns, all BCS_NO_BLOCK.
+ * BCS_EINVAL: p < 1, n < 1, bad range, a table given without its output (or
+ * the reverse), nothing to do. */
+int bcs_expand(int32_t p, int32_t n, int32_t r0, int32_t r1,
+               const int32_t *recv, const int32_t *send,
+               int32_t *recv_blocks, int32_t *send_blocks, void *stream);
+
+/* Frees the per-device scratch kept by the plain bcs_sched* calls on the
+ * current device (after synchronising that device).  Safe to call anytime. */
+int bcs_release(void);
+
+/* Text for a BCS_* code; never NULL. */
+const char *bcs_strerror(int code);
+
+/* hipError_t (as int) of the last failed HIP call made by this library in the
+ * calling thread; 0 if none. */
+int bcs_last_hip_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BCSCHED_H */

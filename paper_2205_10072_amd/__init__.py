@@ -1,0 +1,149 @@
+"""Python binding of libbcsched (round-optimal broadcast schedules on MI355X).
+
+Argument marshalling only: every function here hands device pointers and a
+stream to the C ABI declared in ``include/bcsched.h`` and returns.  PyTorch is
+used for device memory and streams, nothing else.  There is no CPU fallback:
+if ``libbcsched.so`` is not built, importing the library functions raises.
+
+Method: J. L. Traff, arXiv 2205.10072, Section 2.
+"""
+import ctypes
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libbcsched.so")
+
+OK, EINVAL, EHIP, ENOMEM = 0, -1, -2, -3
+MAX_Q = 31
+BATCH_STRIDE = 32
+BATCH_PAD = -(2 ** 31)
+NO_BLOCK = -1
+
+# every symbol include/bcsched.h declares
+SYMBOLS = (
+    "bcs_q", "bcs_skips", "bcs_rounds", "bcs_sched", "bcs_sched_rooted", "bcs_sched_workspace_bytes",
+    "bcs_sched_rooted_ws", "bcs_sched_batch", "bcs_expand", "bcs_release", "bcs_strerror",
+    "bcs_last_hip_error",
+)
+
+_lib = None
+
+
+class BcsError(RuntimeError):
+    def __init__(self, code, what):
+        self.code = code
+        msg = "%s: %s (code %d)" % (what, _strerror(code), code)
+        if code == EHIP and _lib is not None:
+            msg += ", hipError %d" % _lib.bcs_last_hip_error()
+        super().__init__(msg)
+
+
+def lib():
+    """The loaded C library; raises if it has not been built (no fallback exists)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise ImportError("libbcsched.so is not built: run `python -m paper_2205_10072_amd.build` "
+                          "(or __graft_entry__.build()); there is no fallback path")
+    L = ctypes.CDLL(LIB_PATH)
+    i32, i64, vp, sz = ctypes.c_int32, ctypes.c_int64, ctypes.c_void_p, ctypes.c_size_t
+    L.bcs_q.argtypes = [i32]
+    L.bcs_skips.argtypes = [i32, vp]
+    L.bcs_rounds.argtypes = [i32, i32]
+    L.bcs_rounds.restype = i64
+    L.bcs_sched.argtypes = [i32, i32, i32, vp, vp, vp]
+    L.bcs_sched_rooted.argtypes = [i32, i32, i32, i32, vp, vp, vp]
+    L.bcs_sched_workspace_bytes.argtypes = [i32, i32, i32, ctypes.c_int]
+    L.bcs_sched_workspace_bytes.restype = i64
+    L.bcs_sched_rooted_ws.argtypes = [i32, i32, i32, i32, vp, vp, vp, sz, vp]
+    L.bcs_sched_batch.argtypes = [i64, vp, vp, vp, vp, vp, vp, vp]
+    L.bcs_expand.argtypes = [i32, i32, i32, i32, vp, vp, vp, vp, vp]
+    L.bcs_release.argtypes = []
+    L.bcs_strerror.argtypes = [ctypes.c_int]
+    L.bcs_strerror.restype = ctypes.c_char_p
+    L.bcs_last_hip_error.argtypes = []
+    _lib = L
+    return L
+
+
+def _strerror(code):
+    try:
+        return lib().bcs_strerror(code).decode()
+    except Exception:  # library missing: still produce a message
+        return "bcsched error"
+
+
+def _check(code, what):
+    if code < 0:
+        raise BcsError(int(code), what)
+    return code
+
+
+def _ptr(t):
+    """Device pointer of an int32, contiguous CUDA/HIP tensor (None -> NULL)."""
+    if t is None:
+        return None
+    import torch
+    if not (isinstance(t, torch.Tensor) and t.is_cuda and t.dtype == torch.int32 and t.is_contiguous()):
+        raise TypeError("expected a contiguous int32 tensor in device memory")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(stream):
+    import torch
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+def bcs_q(p):
+    return _check(lib().bcs_q(p), "bcs_q")
+
+
+def bcs_skips(p):
+    """Alg. 1: list of the q+1 skips."""
+    q = bcs_q(p)
+    buf = (ctypes.c_int32 * (q + 1))()
+    _check(lib().bcs_skips(p, ctypes.cast(buf, ctypes.c_void_p)), "bcs_skips")
+    return list(buf)
+
+
+def bcs_rounds(p, n):
+    return _check(lib().bcs_rounds(p, n), "bcs_rounds")
+
+
+def bcs_sched(p, r0, r1, recv_out, send_out, stream=None):
+    _check(lib().bcs_sched(p, r0, r1, _ptr(recv_out), _ptr(send_out), _stream(stream)), "bcs_sched")
+
+
+def bcs_sched_rooted(p, root, r0, r1, recv_out, send_out, stream=None):
+    _check(lib().bcs_sched_rooted(p, root, r0, r1, _ptr(recv_out), _ptr(send_out), _stream(stream)),
+           "bcs_sched_rooted")
+
+
+def bcs_sched_workspace_bytes(p, r0, r1, want_send=True):
+    return _check(lib().bcs_sched_workspace_bytes(p, r0, r1, 1 if want_send else 0), "bcs_sched_workspace_bytes")
+
+
+def bcs_sched_rooted_ws(p, root, r0, r1, recv_out, send_out, workspace, stream=None):
+    """`workspace`: a device tensor of any dtype (or None when no scratch is needed)."""
+    wp = ctypes.c_void_p(workspace.data_ptr()) if workspace is not None else None
+    wb = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    _check(lib().bcs_sched_rooted_ws(p, root, r0, r1, _ptr(recv_out), _ptr(send_out), wp, wb, _stream(stream)),
+           "bcs_sched_rooted_ws")
+
+
+def bcs_sched_batch(p, r, root, recv_out, send_out, q_out, stream=None):
+    count = p.numel()
+    _check(lib().bcs_sched_batch(count, _ptr(p), _ptr(r), _ptr(root), _ptr(recv_out), _ptr(send_out),
+                                 _ptr(q_out), _stream(stream)), "bcs_sched_batch")
+
+
+def bcs_expand(p, n, r0, r1, recv, send, recv_blocks, send_blocks, stream=None):
+    _check(lib().bcs_expand(p, n, r0, r1, _ptr(recv), _ptr(send), _ptr(recv_blocks), _ptr(send_blocks),
+                            _stream(stream)), "bcs_expand")
+
+
+def bcs_release():
+    _check(lib().bcs_release(), "bcs_release")

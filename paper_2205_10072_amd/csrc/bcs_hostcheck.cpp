@@ -1,0 +1,97 @@
+// Host build of the per-rank construction in bcs_core.h, one "lane" at a time, so that CPU tests can
+// compare the code the GPU lanes run with the oracle.  Test support; not part of libbcsched.
+#include <stdint.h>
+
+#include "bcs_core.h"
+
+using namespace bcs;
+
+namespace {
+
+int host_q(int32_t p) {
+    int q = 0;
+    while (((int64_t)1 << q) < (int64_t)p) ++q;
+    return q;
+}
+
+void fill_skips(int32_t p, SkipTab &t) {
+    const int q = host_q(p);
+    for (int k = 0; k <= q; ++k) t.s[k] = (((uint32_t)p - 1u) >> (q - k)) + 1u;
+    for (int k = q + 1; k < kMaxQ + 2; ++k) t.s[k] = (uint32_t)p;
+}
+
+template <int Q>
+void row_uniform(const SkipTab &t, uint32_t v, int last, int32_t *out) {
+    Uniform<Q> pol;
+    for (int k = 0; k <= Q; ++k) pol.S[k] = t.s[k];
+    pol.tab = &t;
+    recv_row(pol, v, last, [&](int i, int val) { out[i] = val; });
+}
+
+template <int Q>
+uint32_t range_uniform(const SkipTab &t, uint32_t a, uint32_t b) {
+    Uniform<Q> pol;
+    for (int k = 0; k <= Q; ++k) pol.S[k] = t.s[k];
+    pol.tab = &t;
+    return range_blocks(pol, a, b);
+}
+
+typedef void (*RowFn)(const SkipTab &, uint32_t, int, int32_t *);
+typedef uint32_t (*RangeFn)(const SkipTab &, uint32_t, uint32_t);
+
+template <int Q>
+struct Fill {
+    static void go(RowFn *r, RangeFn *g) {
+        r[Q] = &row_uniform<Q>;
+        g[Q] = &range_uniform<Q>;
+        Fill<Q - 1>::go(r, g);
+    }
+};
+template <>
+struct Fill<0> {
+    static void go(RowFn *, RangeFn *) {}
+};
+
+RowFn g_row[kMaxQ + 1];
+RangeFn g_range[kMaxQ + 1];
+bool g_ready = false;
+void ready() {
+    if (!g_ready) {
+        Fill<kMaxQ>::go(g_row, g_range);
+        g_ready = true;
+    }
+}
+
+}  // namespace
+
+extern "C" {
+
+// entries 0..last of the receive row of virtual rank v, uniform-p code path
+int hc_recv_row(int32_t p, int32_t v, int last, int32_t *out) {
+    if (p < 2 || v < 0 || v >= p) return -1;
+    ready();
+    SkipTab t;
+    fill_skips(p, t);
+    g_row[host_q(p)](t, (uint32_t)v, last, out);
+    return 0;
+}
+
+// the same through the per-lane-p code path; wave_q >= q plays the largest q of the wave
+int hc_recv_row_perlane(int32_t p, int32_t v, int last, int wave_q, int32_t *out) {
+    if (p < 1 || v < 0 || v >= p) return -1;
+    PerLane pol;
+    pol.pm1 = (uint32_t)p - 1u;
+    pol.ql = host_q(p);
+    pol.wave_top = wave_q - 1;
+    recv_row(pol, (uint32_t)v, last, [&](int i, int val) { out[i] = val; });
+    return 0;
+}
+
+// mask of baseblocks of ranks a..b (1 <= a, b < p), uniform-p code path
+uint32_t hc_range_blocks(int32_t p, uint32_t a, uint32_t b) {
+    ready();
+    SkipTab t;
+    fill_skips(p, t);
+    return g_range[host_q(p)](t, a, b);
+}
+}

@@ -1,0 +1,49 @@
+"""ctypes door onto the host build of the GPU lanes' construction code (bcs_core.h)."""
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+SRC = os.path.join(ROOT, "paper_2205_10072_amd", "csrc", "bcs_hostcheck.cpp")
+CORE = os.path.join(ROOT, "paper_2205_10072_amd", "csrc", "bcs_core.h")
+LIB = os.path.join(ROOT, "paper_2205_10072_amd", "libbcs_hostcheck.so")
+
+_lib = None
+
+
+def load():
+    global _lib
+    if _lib is None:
+        stale = (not os.path.exists(LIB)
+                 or os.path.getmtime(LIB) < max(os.path.getmtime(SRC), os.path.getmtime(CORE)))
+        if stale:
+            subprocess.run(["g++", "-O2", "-std=c++17", "-fPIC", "-shared", "-Wno-unknown-pragmas",
+                            "-o", LIB, SRC], check=True)
+        L = ctypes.CDLL(LIB)
+        i32p = ctypes.POINTER(ctypes.c_int32)
+        L.hc_recv_row.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int, i32p]
+        L.hc_recv_row_perlane.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int, ctypes.c_int, i32p]
+        L.hc_range_blocks.argtypes = [ctypes.c_int32, ctypes.c_uint32, ctypes.c_uint32]
+        L.hc_range_blocks.restype = ctypes.c_uint32
+        _lib = L
+    return _lib
+
+
+def recv_row(p, v, last=None, perlane=False, wave_q=None):
+    q = (p - 1).bit_length()
+    if last is None:
+        last = q - 1
+    out = np.full(32, 12345, dtype=np.int32)
+    ptr = out.ctypes.data_as(ctypes.POINTER(ctypes.c_int32))
+    if perlane:
+        rc = load().hc_recv_row_perlane(p, v, last, q if wave_q is None else wave_q, ptr)
+    else:
+        rc = load().hc_recv_row(p, v, last, ptr)
+    assert rc == 0
+    return out
+
+
+def range_blocks(p, a, b):
+    return int(load().hc_range_blocks(p, a, b))

@@ -1,0 +1,218 @@
+"""Parity of the HIP library (through its C ABI) with the CPU oracle, bit for bit, on an MI355X."""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+@pytest.fixture(scope="module")
+def bcs():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_2205_10072_amd as lib
+    lib.lib()                                  # raises if libbcsched.so is missing: no fallback
+    return lib
+
+
+def dev_tables(rows, cols, fill=777):
+    return (torch.full((rows, cols), fill, dtype=torch.int32, device="cuda"),
+            torch.full((rows, cols), fill, dtype=torch.int32, device="cuda"))
+
+
+def gpu_sched(bcs, p, root=0, r0=0, r1=None, want_recv=True, want_send=True):
+    r1 = p if r1 is None else r1
+    q = bcs.bcs_q(p)
+    recv, send = dev_tables(r1 - r0, q)
+    bcs.bcs_sched_rooted(p, root, r0, r1, recv if want_recv else None, send if want_send else None)
+    torch.cuda.synchronize()
+    return recv.cpu().numpy(), send.cpu().numpy()
+
+
+def test_sweep_every_p_to_1024(bcs, oracle):
+    """Config 1: every p in 2..1024, every rank, root 0; then the GPU's own tables are replayed."""
+    from bcast_sim import simulate
+    for p in range(2, 1025):
+        recv, send = gpu_sched(bcs, p)
+        orecv, osend = oracle.sched_range(p)
+        assert np.array_equal(recv, orecv), p
+        assert np.array_equal(send, osend), p
+        for n in ((1, 2, 3, 4, 5, 6, 7, 8) if p % 16 == 0 or p < 70 else (1 + p % 8,)):
+            simulate(p, n, recv, send)
+
+
+def test_sweep_as_one_batch(bcs, oracle):
+    """Config 1 again as a single batch call (per-lane p, mixed q in one wave)."""
+    ps = np.concatenate([np.full(p, p, dtype=np.int32) for p in range(1, 1025)])
+    rs = np.concatenate([np.arange(p, dtype=np.int32) for p in range(1, 1025)])
+    roots = np.zeros_like(ps)
+    count = ps.shape[0]
+    recv, send = dev_tables(count, bcs.BATCH_STRIDE)
+    qv = torch.full((count,), 99, dtype=torch.int32, device="cuda")
+    bcs.bcs_sched_batch(torch.from_numpy(ps).cuda(), torch.from_numpy(rs).cuda(), torch.from_numpy(roots).cuda(),
+                        recv, send, qv)
+    torch.cuda.synchronize()
+    orecv, osend, oq = oracle.sched_batch(ps, rs, roots, threads=8)
+    assert np.array_equal(qv.cpu().numpy(), oq)
+    assert np.array_equal(recv.cpu().numpy(), orecv)
+    assert np.array_equal(send.cpu().numpy(), osend)
+
+
+def test_one_million_and_one_ranks(bcs, oracle):
+    """Config 2: p = 2^20 + 1, all ranks, root 0."""
+    p = (1 << 20) + 1
+    recv, send = gpu_sched(bcs, p)
+    orecv, osend = oracle.sched_range(p, threads=16)
+    assert np.array_equal(recv, orecv)
+    assert np.array_equal(send, osend)
+
+
+def test_sub_ranges_roots_and_single_tables(bcs, oracle):
+    """Ragged ranges that start and end inside a tile, other roots, one table only, caller workspace."""
+    for p, root in [(2, 0), (2, 1), (3, 2), (9, 4), (20, 19), (33, 1), (1000, 123), (4097, 4096), (65537, 40000),
+                    (1048577, 77)]:
+        q = bcs.bcs_q(p)
+        orecv, osend = oracle.sched_range(p, root=root, threads=8)
+        recv, send = gpu_sched(bcs, p, root=root)
+        assert np.array_equal(recv, orecv) and np.array_equal(send, osend), (p, root)
+        recv, _ = gpu_sched(bcs, p, root=root, want_send=False)
+        assert np.array_equal(recv, orecv)
+        _, send = gpu_sched(bcs, p, root=root, want_recv=False)
+        assert np.array_equal(send, osend)
+        # caller-provided workspace
+        ws = torch.empty(bcs.bcs_sched_workspace_bytes(p, 0, p) + 256, dtype=torch.uint8, device="cuda")
+        recv_d, send_d = dev_tables(p, q)
+        bcs.bcs_sched_rooted_ws(p, root, 0, p, recv_d, send_d, ws)
+        torch.cuda.synchronize()
+        assert np.array_equal(recv_d.cpu().numpy(), orecv) and np.array_equal(send_d.cpu().numpy(), osend)
+        # partial ranges: send rows are recomputed (Alg. 5) and must equal the looked-up ones
+        for r0, r1 in [(0, min(p, 1)), (p - 1, p), (p // 3, min(p, p // 3 + 300)), (max(0, p - 259), p), (1, p)]:
+            if p > 70000 and r1 - r0 > 1000:
+                continue
+            recv, send = gpu_sched(bcs, p, root=root, r0=r0, r1=r1)
+            assert np.array_equal(recv, orecv[r0:r1]), (p, root, r0, r1)
+            assert np.array_equal(send, osend[r0:r1]), (p, root, r0, r1)
+    # an empty range and p = 1 succeed and leave the outputs untouched
+    recv, send = dev_tables(3, 4)
+    bcs.bcs_sched(9, 4, 4, recv, send)
+    bcs.bcs_sched(1, 0, 1, recv, send)
+    torch.cuda.synchronize()
+    assert bool((recv == 777).all()) and bool((send == 777).all())
+
+
+def test_largest_p_sampled_chunks(bcs, oracle):
+    """Config 3 (p = 2^27 - 1, q = 27): chunks at both ends and inside, and p = 2^31 - 1."""
+    for p in (134217727, 2**31 - 1):
+        q = bcs.bcs_q(p)
+        for r0 in (0, p // 2 - 1000, 87654321, p - 3001):
+            r1 = r0 + 3001
+            recv, send = gpu_sched(bcs, p, r0=r0, r1=r1)
+            orecv, osend = oracle.sched_range(p, r0=r0, r1=r1, threads=16)
+            assert np.array_equal(recv, orecv), (p, r0)
+            assert np.array_equal(send, osend), (p, r0)
+
+
+def test_largest_p_all_ranks_sampled_rows(bcs, oracle):
+    """Config 3 in the all-ranks launch configuration (send by look-up): rows sampled against the oracle,
+    every row checked for the structure any size must have."""
+    p = 134217727
+    q = 27
+    recv = torch.empty((p, q), dtype=torch.int32, device="cuda")
+    send = torch.empty((p, q), dtype=torch.int32, device="cuda")
+    bcs.bcs_sched(p, 0, p, recv, send)
+    torch.cuda.synchronize()
+    # any size: a non-root receive row holds exactly one non-negative entry b and the other q-1 blocks
+    # as c - q, so it sums to -q(q-1)/2 whatever b is; the root's row sums to -q(q+1)/2
+    nonneg = (recv >= 0).sum(dim=1)
+    assert int(nonneg[0]) == 0 and bool((nonneg[1:] == 1).all())
+    rowsum = recv.sum(dim=1, dtype=torch.int64)
+    assert bool((rowsum[1:] == -(q * (q - 1)) // 2).all())
+    assert int(rowsum[0]) == -(q * (q + 1)) // 2
+    del nonneg, rowsum
+    rng = np.random.default_rng(21)
+    starts = [0, p - 4096] + [int(v) for v in rng.integers(0, p - 4096, 6)]
+    for r0 in starts:
+        orecv, _ = oracle.sched_range(p, r0=r0, r1=r0 + 4096, want_send=False, threads=16)
+        assert np.array_equal(recv[r0:r0 + 4096].cpu().numpy(), orecv), r0
+    skips = bcs.bcs_skips(p)
+    rows = torch.from_numpy(rng.integers(0, p, 200000)).cuda()
+    for k in range(q):                       # the look-up itself, against the GPU's own receive table
+        t = (rows + skips[k]) % p
+        assert bool((send[rows, k] == recv[t, k]).all()), k
+    del recv, send
+    bcs.bcs_release()
+    torch.cuda.empty_cache()
+
+
+def test_expand_p65537_n4096(bcs, oracle):
+    """Config 4: 2 x 65 537 x 4112 int32."""
+    p, n = 65537, 4096
+    q = bcs.bcs_q(p)
+    R = bcs.bcs_rounds(p, n)
+    orecv, osend = oracle.sched_range(p, threads=16)
+    recv, send = dev_tables(p, q)
+    bcs.bcs_sched(p, 0, p, recv, send)
+    rb = torch.full((p, R), 12345, dtype=torch.int32, device="cuda")
+    sb = torch.full((p, R), 12345, dtype=torch.int32, device="cuda")
+    bcs.bcs_expand(p, n, 0, p, recv, send, rb, sb)
+    torch.cuda.synchronize()
+    assert np.array_equal(recv.cpu().numpy(), orecv)
+    assert np.array_equal(rb.cpu().numpy(), oracle.expand(p, n, orecv))
+    assert np.array_equal(sb.cpu().numpy(), oracle.expand(p, n, osend))
+
+
+def test_expand_small_and_ragged(bcs, oracle):
+    for p, n in [(1, 1), (1, 5), (2, 1), (2, 7), (3, 2), (9, 4), (20, 1), (20, 6), (33, 12), (33, 300), (1000, 37),
+                 (4097, 1), (4097, 521)]:
+        q = bcs.bcs_q(p)
+        R = bcs.bcs_rounds(p, n)
+        orecv, osend = oracle.sched_range(p)
+        if R == 0:                       # p = 1, n = 1: no rounds, empty rows, nothing to hand over
+            continue
+        for r0, r1 in [(0, p), (p // 2, p), (0, max(1, p // 3))]:
+            recv = torch.from_numpy(orecv[r0:r1].copy()).cuda()
+            send = torch.from_numpy(osend[r0:r1].copy()).cuda()
+            rb, sb = dev_tables(r1 - r0, R, fill=4242)
+            bcs.bcs_expand(p, n, r0, r1, recv, send, rb, sb)
+            bcs.bcs_expand(p, n, r0, r1, recv, None, rb, None)       # one table only
+            torch.cuda.synchronize()
+            assert np.array_equal(rb.cpu().numpy(), oracle.expand(p, n, orecv[r0:r1])), (p, n, r0, r1)
+            assert np.array_equal(sb.cpu().numpy(), oracle.expand(p, n, osend[r0:r1])), (p, n, r0, r1)
+
+
+def test_irregular_batch(bcs, oracle):
+    """Config 5: 2^20 seeded (p, r, root) triples, p log-uniform up to 2^31 - 1."""
+    from paper_2205_10072_amd import synth
+    count = 1 << 20
+    p, r, root = synth.batch_triples(count)
+    recv, send = dev_tables(count, bcs.BATCH_STRIDE)
+    qv = torch.full((count,), 99, dtype=torch.int32, device="cuda")
+    bcs.bcs_sched_batch(torch.from_numpy(p).cuda(), torch.from_numpy(r).cuda(), torch.from_numpy(root).cuda(),
+                        recv, send, qv)
+    torch.cuda.synchronize()
+    orecv, osend, oq = oracle.sched_batch(p, r, root, threads=16)
+    assert np.array_equal(qv.cpu().numpy(), oq)
+    assert np.array_equal(recv.cpu().numpy(), orecv)
+    assert np.array_equal(send.cpu().numpy(), osend)
+
+
+def test_batch_edge_rows(bcs, oracle):
+    """Invalid triples are flagged on the device; a ragged count; single outputs."""
+    p = np.array([1, 2, 2, 0, 5, 5, 2**31 - 1, 7, -3, 9], dtype=np.int32)
+    r = np.array([0, 1, 0, 0, 5, 2, 2**31 - 2, -1, 0, 3], dtype=np.int32)
+    root = np.array([0, 0, 1, 0, 0, 6, 5, 0, 0, 8], dtype=np.int32)
+    ok = np.array([1, 1, 1, 0, 0, 0, 1, 0, 0, 1], dtype=bool)
+    recv, send = dev_tables(len(p), bcs.BATCH_STRIDE)
+    qv = torch.full((len(p),), 99, dtype=torch.int32, device="cuda")
+    args = [torch.from_numpy(a).cuda() for a in (p, r, root)]
+    bcs.bcs_sched_batch(*args, recv, send, qv)
+    torch.cuda.synchronize()
+    orecv, osend, oq = oracle.sched_batch(p[ok], r[ok], root[ok])
+    assert np.array_equal(qv.cpu().numpy()[ok], oq) and (qv.cpu().numpy()[~ok] == -1).all()
+    assert np.array_equal(recv.cpu().numpy()[ok], orecv) and np.array_equal(send.cpu().numpy()[ok], osend)
+    assert (recv.cpu().numpy()[~ok] == bcs.BATCH_PAD).all() and (send.cpu().numpy()[~ok] == bcs.BATCH_PAD).all()
+    recv2, _ = dev_tables(len(p), bcs.BATCH_STRIDE)
+    bcs.bcs_sched_batch(*args, recv2, None, None)
+    torch.cuda.synchronize()
+    assert torch.equal(recv2, recv)

@@ -1,0 +1,108 @@
+"""CPU tests of the product's host-side logic: the C ABI's symbols and argument checks (no GPU work is
+enqueued), and the GPU lanes' construction code compiled for the host, against the oracle."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import hostcheck
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    import paper_2205_10072_amd as bcs
+    header = open(os.path.join(ROOT, "include", "bcsched.h")).read()
+    declared = set(re.findall(r"\b(bcs_[a-z_0-9]+)\s*\(", header))
+    assert declared == set(bcs.SYMBOLS)
+    L = bcs.lib()
+    for name in declared:
+        assert hasattr(L, name), name
+
+
+def test_host_helpers_and_argument_checks(oracle):
+    import paper_2205_10072_amd as bcs
+    L = bcs.lib()
+    for p in [1, 2, 3, 20, 31, 32, 33, 1000, 1048577, 134217727, 2**31 - 1]:
+        assert bcs.bcs_q(p) == oracle.q_of(p)
+        assert bcs.bcs_skips(p) == oracle.skips(p).tolist()
+    assert bcs.bcs_rounds(65537, 4096) == 4112
+    assert L.bcs_q(0) == bcs.EINVAL and L.bcs_rounds(5, 0) == bcs.EINVAL
+    assert L.bcs_skips(0, None) == bcs.EINVAL and L.bcs_skips(5, None) == bcs.EINVAL
+    fake = ctypes.c_void_p(256)                 # never dereferenced: every call below must fail first
+    bad = [(0, 0, 0, 0), (5, 5, 0, 5), (5, -1, 0, 5), (5, 0, -1, 5), (5, 0, 3, 2), (5, 0, 0, 6)]
+    for p, root, r0, r1 in bad:
+        assert L.bcs_sched_rooted(p, root, r0, r1, fake, fake, None) == bcs.EINVAL
+        assert L.bcs_sched_rooted_ws(p, root, r0, r1, fake, fake, None, 0, None) == bcs.EINVAL
+    assert L.bcs_sched(5, 0, 5, None, None, None) == bcs.EINVAL
+    assert L.bcs_sched_rooted_ws(5, 0, 0, 5, fake, fake, None, 0, None) == bcs.ENOMEM
+    assert L.bcs_sched_workspace_bytes(5, 0, 5, 1) == 3 * 64 * 4
+    assert L.bcs_sched_workspace_bytes(5, 0, 4, 1) == 0 and L.bcs_sched_workspace_bytes(5, 0, 5, 0) == 0
+    assert L.bcs_sched_workspace_bytes(5, 0, 6, 1) == bcs.EINVAL
+    assert L.bcs_sched_batch(-1, fake, fake, fake, fake, fake, fake, None) == bcs.EINVAL
+    assert L.bcs_sched_batch(4, None, fake, fake, fake, fake, fake, None) == bcs.EINVAL
+    assert L.bcs_sched_batch(4, fake, fake, fake, None, None, None, None) == bcs.EINVAL
+    assert L.bcs_expand(5, 0, 0, 5, fake, fake, fake, fake, None) == bcs.EINVAL
+    assert L.bcs_expand(5, 3, 0, 5, fake, None, None, fake, None) == bcs.EINVAL
+    assert L.bcs_expand(5, 3, 0, 5, None, None, None, None, None) == bcs.EINVAL
+    # p = 1 and empty ranges succeed without touching the device
+    assert L.bcs_sched(1, 0, 1, fake, fake, None) == bcs.OK
+    assert L.bcs_sched(9, 4, 4, fake, fake, None) == bcs.OK
+    assert L.bcs_sched_batch(0, fake, fake, fake, fake, fake, fake, None) == bcs.OK
+    assert L.bcs_strerror(bcs.EINVAL) == b"invalid argument"
+    assert L.bcs_strerror(-99) is not None
+
+
+def test_binding_refuses_host_tensors():
+    import torch
+    import paper_2205_10072_amd as bcs
+    t = torch.zeros(10, dtype=torch.int32)
+    with pytest.raises(TypeError):
+        bcs.bcs_sched(2, 0, 2, t, t)
+
+
+def test_lane_code_range_blocks_equals_scan(oracle):
+    rng = np.random.default_rng(11)
+    for p in list(range(2, 80)) + [127, 128, 129, 255, 257, 1000, 1023, 1025]:
+        bb = oracle.baseblocks_linear(p)
+        if p < 40:
+            pairs = [(a, b) for a in range(1, p) for b in range(1, p)]
+        else:
+            pairs = [(int(a), int(b)) for a, b in rng.integers(1, p, (600, 2))]
+        for a, b in pairs:
+            want = oracle.rangeblocks_scan(p, bb, a, b) if a <= b else 0
+            assert hostcheck.range_blocks(p, a, b) == want, (p, a, b)
+
+
+def test_lane_code_rows_equal_oracle_small_p(oracle):
+    for p in list(range(2, 600)) + [1000, 1023, 1024, 1025, 2047, 2049, 4097]:
+        recv, _ = oracle.sched_range(p)
+        q = recv.shape[1]
+        for v in range(p):
+            assert (hostcheck.recv_row(p, v)[:q] == recv[v]).all(), (p, v)
+
+
+def test_lane_code_rows_equal_oracle_large_p(oracle):
+    rng = np.random.default_rng(12)
+    ps = [65537, 1048577, 134217727, 2**31 - 1, 2**30, 2**30 + 1, 1500000001] + \
+         [int(v) for v in rng.integers(2, 2**31 - 1, 60)]
+    for p in ps:
+        q = oracle.q_of(p)
+        for v in [0, 1, 2, p - 1, p - 2, p // 2] + [int(x) for x in rng.integers(0, p, 120)]:
+            want = oracle.recvsched(p, v)
+            assert (hostcheck.recv_row(p, v)[:q] == want).all(), (p, v)
+            assert (hostcheck.recv_row(p, v, perlane=True, wave_q=31)[:q] == want).all(), (p, v)
+            k = int(rng.integers(0, q))          # a prefix, as Alg. 5 asks for
+            assert (hostcheck.recv_row(p, v, last=k)[:k + 1] == want[:k + 1]).all()
+
+
+def test_lane_code_perlane_small_p_and_padding_lanes(oracle):
+    """Per-lane path: a lane whose q is below the wave's bound must leave entries >= q alone."""
+    for p in [1, 2, 3, 5, 9, 20, 33, 100, 1000]:
+        q = oracle.q_of(p)
+        for v in range(p):
+            got = hostcheck.recv_row(p, v, last=30, perlane=True, wave_q=31)
+            assert (got[:q] == oracle.recvsched(p, v)).all() if q else True
+            assert (got[q:] == 12345).all()
