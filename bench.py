@@ -1,0 +1,149 @@
+#!/usr/bin/env python3
+"""Benchmark of the schedule-construction hot path on one MI355X.
+
+One step = one pass of the whole path over one batch: receive and send schedules of all
+p = 2^20 + 1 ranks (skips, baseblocks, range search, Alg. 4, send by neighbour look-up,
+root rotation) followed by their expansion into (rank, round) -> block tables for n = 256
+blocks (Alg. 6 index arithmetic).  Inputs are just (p, root, n): synthetic by construction.
+Outputs are preallocated; nothing crosses PCIe inside the timed region.
+
+Prints ONE JSON line: rank-schedules per second over the whole step, the roofline of the
+kernel that takes most of the step (plus one entry per kernel), the expansion's write rate,
+and the CPU oracle timed on the host cores next to it (a baseline, not a target).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+P = (1 << 20) + 1          # BASELINE config 2: non-power-of-two, q = 21
+ROOT_RANK = 0
+N_BLOCKS = 256             # expansion of the same tables; R = 276 rounds, x = 18 dummy rounds
+
+HBM_PEAK_GBS = 8000.0                       # MI355X HBM3E
+INT_VALU_PEAK_GOPS = 256 * 4 * 16 * 2.4     # CUs x SIMDs x lanes x GHz = 39 321.6 G lane-ops/s (32-bit, full rate)
+
+
+def valu_ops_per_rank(q, kernel):
+    """Vector-ALU lane-operations one rank costs on the non-divergent path, counted from the ISA of the
+    kernels ('algorithmic work')."""
+    if kernel == "k_recv_uniform":
+        return q * (q * OPS_PER_LEVEL + OPS_PER_ROUND) + q * OPS_BASEBLOCK_LEVEL
+    raise KeyError(kernel)
+
+
+OPS_PER_LEVEL = 25         # one level of the range walk (compare, select, prefix mask) in k_recv_uniform
+OPS_PER_ROUND = 24         # per-round set-up and choice of the largest new block
+OPS_BASEBLOCK_LEVEL = 5    # one level of the baseblock walk
+
+
+def cpu_baseline(budget_s=12.0):
+    """The oracle, as it stands, on the host cores: whole steps of the same workload until the budget is spent."""
+    import oracle
+    threads = min(16, os.cpu_count() or 1)
+    done = 0
+    t0 = time.perf_counter()
+    while True:
+        recv, send = oracle.sched_range(P, root=ROOT_RANK, threads=threads)
+        oracle.expand(P, N_BLOCKS, recv, threads=threads)
+        oracle.expand(P, N_BLOCKS, send, threads=threads)
+        done += 1
+        el = time.perf_counter() - t0
+        if el >= budget_s or done >= 50:
+            break
+    return {"value": done * P / el, "unit": "rank-schedules/s", "cores": threads, "kind": "oracle",
+            "sample": "%d whole steps (all %d ranks: recv by Alg. 4, send by look-up, expansion n=%d), %.1f s"
+                      % (done, P, N_BLOCKS, el)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU; --gpus %d is not supported (ranks shard trivially "
+                 "over [r0, r1), see DESIGN.md)" % args.gpus)
+    import torch
+    import paper_2205_10072_amd as bcs
+    bcs.lib()
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    torch.cuda.set_device(0)
+    q = bcs.bcs_q(P)
+    R = bcs.bcs_rounds(P, N_BLOCKS)
+    recv = torch.empty((P, q), dtype=torch.int32, device="cuda")
+    send = torch.empty((P, q), dtype=torch.int32, device="cuda")
+    rb = torch.empty((P, R), dtype=torch.int32, device="cuda")
+    sb = torch.empty((P, R), dtype=torch.int32, device="cuda")
+    ws = torch.empty(bcs.bcs_sched_workspace_bytes(P, 0, P), dtype=torch.uint8, device="cuda")
+
+    def step():
+        bcs.bcs_sched_rooted_ws(P, ROOT_RANK, 0, P, recv, send, ws)
+        bcs.bcs_expand(P, N_BLOCKS, 0, P, recv, send, rb, sb)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    steps = max(1, min(args.steps, 1000))
+    bcs.bcs_timing_begin()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    timing = bcs.bcs_timing_end()
+    ms_per_step = (t1 - t0) * 1e3 / steps
+
+    # per-kernel rooflines from the device-side durations of the timed region
+    kernels = {}
+    for name, (ms, cnt) in timing.items():
+        avg_ms = ms / cnt
+        ent = {"launches_per_step": cnt / steps, "avg_ms": avg_ms, "ms_per_step": ms / steps}
+        if name == "k_expand":
+            nbytes = P * R * 4                                  # one table per launch, written once
+            ent.update(bound="hbm", achieved=nbytes / avg_ms / 1e6, peak=HBM_PEAK_GBS, unit="GB/s")
+        elif name == "k_send_lookup":
+            nbytes = 2 * P * q * 4                              # read one table, write one table
+            ent.update(bound="hbm", achieved=nbytes / avg_ms / 1e6, peak=HBM_PEAK_GBS, unit="GB/s")
+        elif name == "k_recv_uniform":
+            ops = valu_ops_per_rank(q, name) * P
+            ent.update(bound="alu", achieved=ops / avg_ms / 1e6, peak=INT_VALU_PEAK_GOPS, unit="Gop/s")
+        else:
+            continue
+        ent["frac"] = ent["achieved"] / ent["peak"]
+        ent["traffic"] = None
+        kernels[name] = ent
+    dominant = max(kernels, key=lambda k: kernels[k]["ms_per_step"])
+    roofline = dict(kernels[dominant], kernel=dominant)
+
+    out = {
+        "metric": "rank-schedules constructed/s (int32, bit-exact) + expand GB/s vs HBM peak",
+        "value": P / (ms_per_step * 1e-3),
+        "unit": "rank-schedules/s",
+        "n_gpus": 1, "steps": steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "int32", "data": "synthetic",
+        "config": {"workload": "p=2^20+1 (q=21), all ranks, root 0: recv+send schedules, then expansion n=%d "
+                               "(R=%d rounds)" % (N_BLOCKS, R), "p": P, "q": q, "n": N_BLOCKS, "rounds": R},
+        "expand_gbs": kernels["k_expand"]["achieved"],
+        "construct_rank_schedules_per_s": P / ((kernels["k_recv_uniform"]["ms_per_step"]
+                                                 + kernels["k_send_lookup"]["ms_per_step"]) * 1e-3),
+        "roofline": roofline,
+        "kernels": kernels,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline()
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -48,6 +48,7 @@ extern "C" {
 #define BCS_BATCH_STRIDE  32           /* ints per row of the batch tables             */
 #define BCS_BATCH_PAD     INT32_MIN    /* fills batch row entries k >= q               */
 #define BCS_NO_BLOCK      (-1)         /* expanded tables: nothing moves in this round */
+#define BCS_MAX_N         (INT32_MAX - 64) /* bcs_expand: rounds and blocks stay in int32 */
 
 /* q = ceil(log2 p) (Section 2, first paragraph).  p = 1 gives 0.
  * Returns BCS_EINVAL for p < 1. */
@@ -116,8 +117,9 @@ int bcs_sched_batch(int64_t count, const int32_t *p, const int32_t *r, const int
  *   [(r-r0)*R + j] = block moved in round j, or BCS_NO_BLOCK.
  * p = 1: q = 0, the input tables have empty rows and are ignored (may be
  * NULL); each output given gets R = n-1 columns, all BCS_NO_BLOCK.
- * BCS_EINVAL: p < 1, n < 1, bad range, a table given without its output (or
- * the reverse), nothing to do. */
+ * Outputs that are 16-byte aligned are written with 16-byte stores.
+ * BCS_EINVAL: p < 1, n < 1, n > BCS_MAX_N, bad range, a table given without
+ * its output (or the reverse), nothing to do. */
 int bcs_expand(int32_t p, int32_t n, int32_t r0, int32_t r1,
                const int32_t *recv, const int32_t *send,
                int32_t *recv_blocks, int32_t *send_blocks, void *stream);
@@ -125,6 +127,21 @@ int bcs_expand(int32_t p, int32_t n, int32_t r0, int32_t r1,
 /* Frees the per-device scratch kept by the plain bcs_sched* calls on the
  * current device (after synchronising that device).  Safe to call anytime. */
 int bcs_release(void);
+
+/* Device-side duration of each kernel, for measurements.  Between
+ * bcs_timing_begin() and bcs_timing_end() every kernel this library launches
+ * (from the calling process, any stream) carries its own start/stop event
+ * pair from a pool of BCS_TIMING_MAX_LAUNCHES; later launches run untimed.
+ * bcs_timing_end waits for the timed launches and writes, per kernel id
+ * 0..BCS_KERNEL_COUNT-1, the summed duration in milliseconds and the number
+ * of timed launches into host arrays of BCS_KERNEL_COUNT entries.  Not
+ * thread-safe; meant for one measuring thread. */
+#define BCS_KERNEL_COUNT         6
+#define BCS_TIMING_MAX_LAUNCHES  4096
+int bcs_timing_begin(void);
+int bcs_timing_end(double *ms_sum_host, int64_t *launches_host);
+/* Name of kernel `id` as a profiler shows it (without template arguments). */
+const char *bcs_kernel_name(int id);
 
 /* Text for a BCS_* code; never NULL. */
 const char *bcs_strerror(int code);

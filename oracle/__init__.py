@@ -50,7 +50,7 @@ def _load():
     lib.orc_sched_range.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32,
                                     i32p, i32p, ctypes.c_int]
     lib.orc_sched_batch.argtypes = [ctypes.c_int64, i32p, i32p, i32p, i32p, i32p, i32p, ctypes.c_int]
-    lib.orc_expand.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int64, i32p, i32p]
+    lib.orc_expand.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int64, i32p, i32p, ctypes.c_int]
     _lib = lib
     return lib
 
@@ -153,12 +153,12 @@ def sched_batch(p, r, root, want_send=True, threads=1):
     return recv, send, qv
 
 
-def expand(p, n, table):
+def expand(p, n, table, threads=1):
     """Alg. 6 index arithmetic: table[rows][q] -> blocks[rows][n-1+q] (-1 = nothing)."""
     q = q_of(p)
     table = np.ascontiguousarray(table, dtype=np.int32).reshape(-1, q) if q > 0 \
         else np.zeros((np.asarray(table).shape[0], 0), dtype=np.int32)
     rows = table.shape[0]
     out = np.zeros((rows, n - 1 + q), dtype=np.int32)
-    _check(_load().orc_expand(p, n, rows, _ptr(table), _ptr(out)), "expand")
+    _check(_load().orc_expand(p, n, rows, _ptr(table), _ptr(out), threads), "expand")
     return out

@@ -413,10 +413,12 @@ int orc_sched_batch(int64_t count, const int32_t *p, const int32_t *r, const int
  * k = i mod q and adds q to it afterwards.  A negative block means "nothing
  * this round" and is written as -1; a block above n-1 is block n-1 (caption
  * of Alg. 6).  One call expands one table: in[(r-r0)*q + k] ->
- * out[(r-r0)*R + j], R = n-1+q, j counts real rounds from 0. */
-int orc_expand(int32_t p, int32_t n, int64_t rows, const int32_t *in, int32_t *out)
+ * out[(r-r0)*R + j], R = n-1+q, j counts real rounds from 0.  `threads` splits
+ * the row loop; rows are independent. */
+int orc_expand(int32_t p, int32_t n, int64_t rows, const int32_t *in, int32_t *out, int threads)
 {
     if (p < 1 || n < 1 || rows < 0) return ORC_EINVAL;
+    if (threads < 1) threads = 1;
     int q = orc_q(p);
     int64_t R = (int64_t)n - 1 + q;
     if (q == 0) {
@@ -424,6 +426,7 @@ int orc_expand(int32_t p, int32_t n, int64_t rows, const int32_t *in, int32_t *o
         return 0;
     }
     int64_t x = (q - (n - 1 + q) % q) % q;
+    #pragma omp parallel for schedule(static) num_threads(threads)
     for (int64_t row = 0; row < rows; row++) {
         int64_t sched[ORC_MAXQ + 1];
         for (int i = 0; i < q; i++) {

@@ -23,8 +23,9 @@ NO_BLOCK = -1
 SYMBOLS = (
     "bcs_q", "bcs_skips", "bcs_rounds", "bcs_sched", "bcs_sched_rooted", "bcs_sched_workspace_bytes",
     "bcs_sched_rooted_ws", "bcs_sched_batch", "bcs_expand", "bcs_release", "bcs_strerror",
-    "bcs_last_hip_error",
+    "bcs_last_hip_error", "bcs_timing_begin", "bcs_timing_end", "bcs_kernel_name",
 )
+KERNEL_COUNT = 6
 
 _lib = None
 
@@ -63,6 +64,10 @@ def lib():
     L.bcs_strerror.argtypes = [ctypes.c_int]
     L.bcs_strerror.restype = ctypes.c_char_p
     L.bcs_last_hip_error.argtypes = []
+    L.bcs_timing_begin.argtypes = []
+    L.bcs_timing_end.argtypes = [vp, vp]
+    L.bcs_kernel_name.argtypes = [ctypes.c_int]
+    L.bcs_kernel_name.restype = ctypes.c_char_p
     _lib = L
     return L
 
@@ -147,3 +152,16 @@ def bcs_expand(p, n, r0, r1, recv, send, recv_blocks, send_blocks, stream=None):
 
 def bcs_release():
     _check(lib().bcs_release(), "bcs_release")
+
+
+def bcs_timing_begin():
+    _check(lib().bcs_timing_begin(), "bcs_timing_begin")
+
+
+def bcs_timing_end():
+    """{kernel name: (summed milliseconds, timed launches)} since bcs_timing_begin()."""
+    ms = (ctypes.c_double * KERNEL_COUNT)()
+    cnt = (ctypes.c_int64 * KERNEL_COUNT)()
+    _check(lib().bcs_timing_end(ctypes.cast(ms, ctypes.c_void_p), ctypes.cast(cnt, ctypes.c_void_p)),
+           "bcs_timing_end")
+    return {lib().bcs_kernel_name(i).decode(): (ms[i], cnt[i]) for i in range(KERNEL_COUNT) if cnt[i]}

@@ -6,6 +6,7 @@
 //
 // The per-rank construction is in bcs_core.h; this file holds the kernels and the C ABI.
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdint.h>
 #include <utility>
 
@@ -23,6 +24,48 @@ thread_local int g_last_hip = 0;
 inline int hip_fail(hipError_t e) {
     g_last_hip = (int)e;
     return BCS_EHIP;
+}
+
+// Optional per-kernel device timing (bcs_timing_begin / bcs_timing_end): while it is on, a launch is
+// given a start and a stop event from a fixed pool, so its duration is the device's own.
+enum KernelId { kRecv = 0, kSendLookup, kSendRecompute, kBatch, kExpand, kFill, kKernelCount };
+static_assert(kKernelCount == BCS_KERNEL_COUNT, "header and kernel list disagree");
+const char *const kKernelNames[kKernelCount] = {"k_recv_uniform", "k_send_lookup", "k_send_recompute",
+                                                "k_batch",        "k_expand",      "k_fill"};
+struct Timing {
+    bool on = false;
+    int used = 0;
+    int created = 0;
+    hipEvent_t start[BCS_TIMING_MAX_LAUNCHES];
+    hipEvent_t stop[BCS_TIMING_MAX_LAUNCHES];
+    int kid[BCS_TIMING_MAX_LAUNCHES];
+};
+Timing g_timing;
+
+template <class... KArgs, class... Args>
+void launch_lds(int kid, void (*kernel)(KArgs...), dim3 grid, dim3 block, unsigned lds_bytes, hipStream_t st,
+                Args... args) {
+    Timing &t = g_timing;
+    if (t.on && t.used < BCS_TIMING_MAX_LAUNCHES) {
+        if (t.used == t.created) {
+            if (hipEventCreate(&t.start[t.created]) == hipSuccess) {
+                if (hipEventCreate(&t.stop[t.created]) == hipSuccess) ++t.created;
+                else (void)hipEventDestroy(t.start[t.created]);
+            }
+        }
+        if (t.used < t.created) {
+            const int slot = t.used++;
+            t.kid[slot] = kid;
+            hipExtLaunchKernelGGL(kernel, grid, block, lds_bytes, st, t.start[slot], t.stop[slot], 0, args...);
+            return;
+        }
+    }
+    hipLaunchKernelGGL(kernel, grid, block, lds_bytes, st, args...);
+}
+
+template <class... KArgs, class... Args>
+void launch(int kid, void (*kernel)(KArgs...), dim3 grid, dim3 block, hipStream_t st, Args... args) {
+    launch_lds(kid, kernel, grid, block, 0u, st, args...);
 }
 
 // ----------------------------------------------------------------------------------------------
@@ -191,43 +234,213 @@ __global__ __launch_bounds__(kBlock) void k_batch(int64_t count, const int32_t *
 }
 
 // ----------------------------------------------------------------------------------------------
-// K4: expansion (Alg. 6 index arithmetic).  Real round j uses slot k = (x+j) mod q and the value
-// sched[k] + q*floor((x+j)/q) - x: slots below x were advanced once by the x dummy rounds, which
-// the floor term already counts.  Negative -> BCS_NO_BLOCK, above n-1 -> n-1.  A workgroup owns a
-// panel of kExpCols rounds and walks down the rows; lanes are consecutive rounds, so stores are
-// contiguous and each lane keeps its slot and offset in registers for the whole walk.
+// K4: expansion (Alg. 6 index arithmetic).  Real round j uses slot k = (x+j) mod q; by then the slot
+// has been advanced floor((x+j)/q) times by q and shifted by -x, and q*floor((x+j)/q) = x+j-k, so
+// the block is sched[k] + j - k.  Negative -> BCS_NO_BLOCK, above n-1 -> n-1 (caption of Alg. 6).
+//
+// The output is one contiguous int32 stream of rows*R entries and the kernels treat it as such: a
+// workgroup owns kExpChunk consecutive entries (16 KiB), a lane writes 16 bytes per 4 KiB piece.
+// The schedule rows the chunk touches are staged in LDS as T[k] = sched[k] - k, so an entry is
+// T[k] + j, clamped.  Wave-uniform steps come precomputed from the host.
+//
+// k_expand (R >= 16, q >= 3): a lane's four consecutive entries use four consecutive slots.  So that
+// they are four consecutive LDS words whatever happens in between, a staged row of q+9 words holds
+//   T[0..q-1] | T[0..2] | T[q-3..q-1] | T'[x..x+2] - R      (T' = next row's T, slots mod q)
+// A row always ends on slot q-1 (x + R is a multiple of q).  A lane that stays inside its row starts at
+// word k and may run into the second group (slot wraps to 0, round keeps counting); a lane whose
+// piece crosses into the next row starts 6 words further and runs into the fourth group, whose
+// "- R" makes T + (j + c) come out as the next row's T + (c - entries left).  One select per lane,
+// none per entry.  Small divisions use exact multiply-high reciprocals.
+// k_expand_small: the same stream for tiny R or q = 1, advancing slot and round entry by entry.
 // ----------------------------------------------------------------------------------------------
-constexpr int kExpCols = kBlock;          // rounds per panel (one per lane)
-constexpr int kExpRows = 64;              // rows staged in LDS per step
+constexpr int kExpIter = 4;                         // 16-byte pieces per lane (measured best of 1..16)
+constexpr int kExpChunk = kExpIter * kBlock * 4;    // entries per workgroup
+constexpr int kExpSmallLds = kExpChunk + 2 * (kMaxQ + 1);
+constexpr uint32_t kExpMinR = 16;
+constexpr uint32_t kExpMinQ = 3;
+constexpr uint64_t kExpNtMaxR = 640;                // rows up to this length use streaming stores
+constexpr uint32_t kExpPad = 9;                      // extra words per staged row
 
-__global__ __launch_bounds__(kBlock) void k_expand(int q, uint32_t x, int32_t nm1, uint64_t rows, uint64_t R,
-                                                   uint32_t rows_per_block,
-                                                   const int32_t *__restrict__ in, int32_t *__restrict__ out) {
-    __shared__ int32_t tile[kExpRows * (kMaxQ + 1)];
-    const uint64_t j = (uint64_t)blockIdx.x * kExpCols + threadIdx.x;
-    const bool col_live = j < R;
-    const uint64_t i = (uint64_t)x + j;
-    const uint32_t phase = (uint32_t)(i / (uint32_t)q);
-    const int k = (int)(i - (uint64_t)phase * q);
-    const int64_t off64 = (int64_t)phase * q - (int64_t)x;
-    const uint64_t row_begin = (uint64_t)blockIdx.y * rows_per_block;
-    uint64_t row_end = row_begin + rows_per_block;
-    if (row_end > rows) row_end = rows;
-    for (uint64_t rb = row_begin; rb < row_end; rb += kExpRows) {
-        const uint32_t nr = (uint32_t)((row_end - rb) < (uint64_t)kExpRows ? (row_end - rb) : (uint64_t)kExpRows);
-        const uint32_t cnt = nr * (uint32_t)q;
-        __syncthreads();
-        const int32_t *src = in + rb * (uint64_t)q;
-        for (uint32_t e = threadIdx.x; e < cnt; e += kBlock) tile[e] = src[e];
-        __syncthreads();
-        if (col_live) {
-            int32_t *dst = out + rb * R + j;
-            for (uint32_t rr = 0; rr < nr; ++rr) {
-                int64_t val = (int64_t)tile[rr * (uint32_t)q + k] + off64;
-                val = val < 0 ? -1 : (val > nm1 ? nm1 : val);
-                dst[(uint64_t)rr * R] = (int32_t)val;
-            }
+struct ExpandArgs {
+    uint64_t total;                       // rows * R
+    uint64_t rows;
+    uint32_t R;
+    uint32_t step_rows;                   // (kBlock*4) / R
+    uint32_t step_j;                      // (kBlock*4) % R
+    uint32_t step_k;                      // step_j % q
+    uint32_t wrap_k;                      // q - R % q
+    uint32_t q;
+    uint32_t x;
+    int32_t nm1;                          // n - 1
+    int aligned;                          // output is 16-byte aligned
+    uint32_t magic_R;                     // floor(2^32 / R) + 1       (dividends below 2^14, R < 8192)
+    uint32_t magic_q;                     // floor(2^32 / q) + 1       (dividends below 2^16)
+    uint32_t magic_w;                     // floor(2^32 / (q+9)) + 1   (dividends below 2^14)
+};
+
+__device__ __forceinline__ void expand_store(int32_t *__restrict__ out, uint64_t e, const int32_t (&v)[4],
+                                             bool vec, bool full, uint64_t total) {
+    if (vec && (full || e + 4 <= total)) {
+        *reinterpret_cast<int4 *>(out + e) = make_int4(v[0], v[1], v[2], v[3]);
+    } else {
+#pragma unroll
+        for (int c = 0; c < 4; ++c)
+            if (full || e + c < total) out[e + c] = v[c];
+    }
+}
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+
+// NT: streaming (non-temporal) stores.  Measured on MI355X they win while the schedule reads are a
+// visible share of the traffic (short rows) and lose to plain stores for long rows.
+template <bool NT>
+__global__ __launch_bounds__(kBlock) void k_expand(const ExpandArgs a, const int32_t *__restrict__ in,
+                                                   int32_t *__restrict__ out) {
+    extern __shared__ int32_t tile[];     // (rows touched + 1) x (q + 9)
+    const uint32_t q = a.q, R = a.R, w = q + kExpPad;
+    const uint64_t e0 = (uint64_t)blockIdx.x * kExpChunk;          // first entry of this workgroup
+    uint64_t row0;
+    uint32_t j0;
+    if ((a.total >> 32) == 0) {
+        const uint32_t e32 = (uint32_t)e0, r32 = e32 / R;
+        row0 = r32;
+        j0 = e32 - r32 * R;
+    } else {
+        row0 = e0 / R;
+        j0 = (uint32_t)(e0 - row0 * R);
+    }
+    uint32_t nrows = (j0 + (uint32_t)kExpChunk - 1u) / R + 1u;
+    if (row0 + nrows > a.rows) nrows = (uint32_t)(a.rows - row0);
+    const bool has_next = row0 + nrows < a.rows;                    // a row after the last touched one
+    const uint32_t staged = nrows * w;
+    const int32_t *src = in + row0 * q;
+    const uint32_t last_row = has_next ? nrows : nrows - 1u;        // highest row index that may be read
+    // loads of a group are issued together (indices clamped, no branch) so their latencies overlap
+    constexpr int kGroup = 4;
+    for (uint32_t base = 0; base < staged; base += kGroup * kBlock) {
+        int32_t got[kGroup];
+#pragma unroll
+        for (int u = 0; u < kGroup; ++u) {
+            uint32_t i = base + u * kBlock + threadIdx.x;
+            i = i < staged ? i : staged - 1u;
+            const uint32_t rr = __umulhi(i, a.magic_w);
+            const uint32_t pos = i - rr * w;
+            // which slot of which row this word mirrors
+            const bool g1 = pos >= q, g2 = pos >= q + 3u, g3 = pos >= q + 6u;
+            uint32_t slot = g3 ? pos - (q + 6u) + a.x : (g2 ? pos - 6u : (g1 ? pos - q : pos));
+            slot = slot >= q ? slot - q : slot;
+            uint32_t row = g3 ? rr + 1u : rr;
+            row = row > last_row ? last_row : row;
+            const int32_t shift = g3 ? (int32_t)(slot + R) : (int32_t)slot;
+            got[u] = src[row * q + slot] - shift;
         }
+#pragma unroll
+        for (int u = 0; u < kGroup; ++u) {
+            const uint32_t i = base + u * kBlock + threadIdx.x;
+            if (i < staged) tile[i] = got[u];
+        }
+    }
+    __syncthreads();
+
+    // this lane's first entry: chunk-relative t = j0 + 4*lane lies in row row0 + t / R
+    const uint32_t t = j0 + threadIdx.x * 4u;
+    uint32_t rd = R >= 8192u ? (t >= R ? 1u : 0u) : __umulhi(t, a.magic_R);
+    uint32_t j = t - rd * R;
+    const uint32_t kb = (a.x + j0) % q;
+    const uint32_t kv = kb + threadIdx.x * 4u + rd * a.wrap_k;     // congruent to x + j mod q
+    uint32_t k = kv - q * __umulhi(kv, a.magic_q);
+    const bool full = e0 + kExpChunk <= a.total;
+    const bool vec = a.aligned != 0;
+    uint64_t e = e0 + threadIdx.x * 4u;
+    const int32_t lo = -1, hi = a.nm1;
+    const unsigned char *lds = reinterpret_cast<const unsigned char *>(tile);
+#pragma unroll 1
+    for (int it = 0; it < kExpIter; ++it) {
+        if (!full && e >= a.total) break;
+        const uint32_t left = R - j;                                // entries left in this row
+        const uint32_t word = rd * w + k + (left < 4u ? 6u : 0u);
+        const int32_t *wp = reinterpret_cast<const int32_t *>(lds + word * 4u);
+        int32_t v[4];
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const int32_t raw = wp[c] + (int32_t)(j + c);
+            const int32_t m = raw > lo ? raw : lo;
+            v[c] = m < hi ? m : hi;
+        }
+        if (vec && (full || e + 4 <= a.total)) {
+            v4i pack = {v[0], v[1], v[2], v[3]};
+            if constexpr (NT) __builtin_nontemporal_store(pack, reinterpret_cast<v4i *>(out + e));
+            else *reinterpret_cast<v4i *>(out + e) = pack;
+        } else {
+#pragma unroll
+            for (int c = 0; c < 4; ++c)
+                if (full || e + c < a.total) out[e + c] = v[c];
+        }
+        e += (uint64_t)kBlock * 4u;
+        rd += a.step_rows;
+        j += a.step_j;
+        k += a.step_k;
+        if (j >= R) {
+            j -= R;
+            ++rd;
+            k += a.wrap_k;
+        }
+        k = k >= q ? k - q : k;
+        k = k >= q ? k - q : k;
+    }
+}
+
+__global__ __launch_bounds__(kBlock) void k_expand_small(const ExpandArgs a, const int32_t *__restrict__ in,
+                                                         int32_t *__restrict__ out) {
+    __shared__ int32_t tile[kExpSmallLds];
+    const uint32_t q = a.q, R = a.R;
+    const uint64_t e0 = (uint64_t)blockIdx.x * kExpChunk;
+    const uint64_t row0 = e0 / R;
+    const uint32_t j0 = (uint32_t)(e0 - row0 * R);
+    uint64_t row_last = (e0 + kExpChunk - 1) / R;
+    if (row_last >= a.rows) row_last = a.rows - 1;
+    const uint32_t staged = (uint32_t)(row_last - row0 + 1) * q;   // <= kExpSmallLds since q <= R
+    const int32_t *src = in + row0 * q;
+    for (uint32_t i = threadIdx.x; i < staged; i += kBlock) tile[i] = src[i] - (int32_t)(i % q);
+    __syncthreads();
+    const uint32_t t = j0 + threadIdx.x * 4u;
+    uint32_t rd = t / R;
+    uint32_t j = t - rd * R;
+    uint32_t k = (a.x + j) % q;
+    const bool full = e0 + kExpChunk <= a.total;
+    const bool vec = a.aligned != 0;
+    uint64_t e = e0 + threadIdx.x * 4u;
+#pragma unroll 1
+    for (int it = 0; it < kExpIter; ++it) {
+        if (!full && e >= a.total) break;
+        uint32_t ro = rd * q, jj = j, kk = k;
+        int32_t v[4];
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            uint32_t idx = ro + kk;
+            idx = idx < staged ? idx : 0u;            // past the table's end; such entries are never stored
+            const int32_t raw = tile[idx] + (int32_t)jj;
+            v[c] = raw < 0 ? -1 : (raw > a.nm1 ? a.nm1 : raw);
+            ++kk;
+            ++jj;
+            kk = kk == q ? 0u : kk;
+            const bool wj = jj == R;                  // next row: round 0, slot x
+            jj = wj ? 0u : jj;
+            kk = wj ? a.x : kk;
+            ro = wj ? ro + q : ro;
+        }
+        expand_store(out, e, v, vec, full, a.total);
+        e += (uint64_t)kBlock * 4u;
+        rd += a.step_rows;
+        j += a.step_j;
+        k += a.step_k;
+        if (j >= R) {
+            j -= R;
+            ++rd;
+            k += a.wrap_k;
+        }
+        k = k >= q ? k - q : k;
+        k = k >= q ? k - q : k;
     }
 }
 
@@ -304,15 +517,15 @@ int launch_sched(const SkipTab &tab, uint32_t root, uint32_t r0, uint32_t r1, in
     const unsigned blocks = (unsigned)((count + kBlock - 1) / kBlock);
     const bool full = (r0 == 0 && r1 == tab.s[Q]);
     if (recv_out || (send_out && full)) {
-        hipLaunchKernelGGL(k_recv_uniform<Q>, dim3(blocks), dim3(kBlock), 0, st, tab, root, r0, r1, recv_out,
+        launch(kRecv, k_recv_uniform<Q>, dim3(blocks), dim3(kBlock), st, tab, root, r0, r1, recv_out,
                            (send_out && full) ? recvT : (int32_t *)nullptr, ldT);
     }
     if (send_out) {
         if (full) {
-            hipLaunchKernelGGL(k_send_lookup<Q>, dim3(blocks), dim3(kBlock), 0, st, tab, (const int32_t *)recvT, ldT,
+            launch(kSendLookup, k_send_lookup<Q>, dim3(blocks), dim3(kBlock), st, tab, (const int32_t *)recvT, ldT,
                                send_out);
         } else {
-            hipLaunchKernelGGL(k_send_recompute<Q>, dim3(blocks), dim3(kBlock), 0, st, tab, root, r0, r1, send_out);
+            launch(kSendRecompute, k_send_recompute<Q>, dim3(blocks), dim3(kBlock), st, tab, root, r0, r1, send_out);
         }
     }
     hipError_t e = hipGetLastError();
@@ -410,7 +623,7 @@ int bcs_sched_batch(int64_t count, const int32_t *p, const int32_t *r, const int
     if (count == 0) return BCS_OK;
     const uint64_t blocks = ((uint64_t)count + kBlock - 1) / kBlock;
     if (blocks > 0x7fffffffull) return BCS_EINVAL;
-    hipLaunchKernelGGL(k_batch, dim3((unsigned)blocks), dim3(kBlock), 0, (hipStream_t)stream, count, p, r, root,
+    launch(kBatch, k_batch, dim3((unsigned)blocks), dim3(kBlock), (hipStream_t)stream, count, p, r, root,
                        recv_out, send_out, q_out);
     hipError_t e = hipGetLastError();
     return e == hipSuccess ? BCS_OK : hip_fail(e);
@@ -418,7 +631,7 @@ int bcs_sched_batch(int64_t count, const int32_t *p, const int32_t *r, const int
 
 int bcs_expand(int32_t p, int32_t n, int32_t r0, int32_t r1, const int32_t *recv, const int32_t *send,
                int32_t *recv_blocks, int32_t *send_blocks, void *stream) {
-    if (check_range(p, 0, r0, r1) != BCS_OK || n < 1) return BCS_EINVAL;
+    if (check_range(p, 0, r0, r1) != BCS_OK || n < 1 || n > BCS_MAX_N) return BCS_EINVAL;
     const int q = host_q(p);
     if (q == 0) {                      // rows of the input tables are empty: only the outputs count
         recv = recv_blocks;
@@ -436,23 +649,39 @@ int bcs_expand(int32_t p, int32_t n, int32_t r0, int32_t r1, const int32_t *recv
     for (int t = 0; t < 2; ++t) {
         if (!ins[t]) continue;
         if (q == 0) {
-            hipLaunchKernelGGL(k_fill, dim3(1024), dim3(kBlock), 0, st, outs[t], rows * R, (int32_t)BCS_NO_BLOCK);
+            launch(kFill, k_fill, dim3(1024), dim3(kBlock), st, outs[t], rows * R, (int32_t)BCS_NO_BLOCK);
             continue;
         }
-        const uint32_t x = (uint32_t)((q - (int)(R % (uint64_t)q)) % q);
-        const uint64_t panels = (R + kExpCols - 1) / kExpCols;
-        // enough workgroups to fill 256 CUs several times over, rows split in multiples of the LDS step
-        uint64_t want_y = (8192 + panels - 1) / panels;
-        uint64_t rpb = (rows + want_y - 1) / want_y;
-        rpb = round_up(rpb < 1 ? 1 : rpb, kExpRows);
-        const uint64_t gy = (rows + rpb - 1) / rpb;
-        if (panels > 0x7fffffffull || gy > 65535ull) {
-            // fall back to fewer, taller workgroups
-            rpb = round_up((rows + 65534ull) / 65535ull, kExpRows);
+        ExpandArgs ea;
+        ea.total = rows * R;
+        ea.rows = rows;
+        ea.R = (uint32_t)R;
+        ea.q = (uint32_t)q;
+        ea.x = (uint32_t)((q - (int)(R % (uint64_t)q)) % q);
+        ea.nm1 = n - 1;
+        ea.step_rows = (uint32_t)((kBlock * 4u) / R);
+        ea.step_j = (uint32_t)((kBlock * 4u) % R);
+        ea.step_k = ea.step_j % (uint32_t)q;
+        ea.wrap_k = (uint32_t)q - (uint32_t)(R % (uint64_t)q);
+        ea.aligned = (((uintptr_t)outs[t]) & 15u) == 0 ? 1 : 0;
+        ea.magic_R = (uint32_t)((1ull << 32) / R + 1ull);
+        ea.magic_q = q >= 2 ? (uint32_t)((1ull << 32) / (uint64_t)q + 1ull) : 0u;
+        ea.magic_w = (uint32_t)((1ull << 32) / (uint64_t)(q + kExpPad) + 1ull);
+        const uint64_t blocks = (ea.total + kExpChunk - 1) / kExpChunk;
+        if (blocks > 0x7fffffffull) return BCS_EINVAL;
+        if (R >= kExpMinR && (uint32_t)q >= kExpMinQ) {
+            // rows a chunk can touch, plus one that a lane past the end may address but never uses
+            const uint64_t max_rows = (R - 1 + kExpChunk - 1) / R + 2;
+            const unsigned lds_bytes = (unsigned)(max_rows * (uint64_t)(q + kExpPad) * sizeof(int32_t));
+            if (R <= kExpNtMaxR)
+                launch_lds(kExpand, k_expand<true>, dim3((unsigned)blocks), dim3(kBlock), lds_bytes, st, ea, ins[t],
+                           outs[t]);
+            else
+                launch_lds(kExpand, k_expand<false>, dim3((unsigned)blocks), dim3(kBlock), lds_bytes, st, ea, ins[t],
+                           outs[t]);
+        } else {
+            launch(kExpand, k_expand_small, dim3((unsigned)blocks), dim3(kBlock), st, ea, ins[t], outs[t]);
         }
-        const uint64_t gy2 = (rows + rpb - 1) / rpb;
-        hipLaunchKernelGGL(k_expand, dim3((unsigned)panels, (unsigned)gy2), dim3(kBlock), 0, st, q, x, (int32_t)(n - 1),
-                           rows, R, (uint32_t)rpb, ins[t], outs[t]);
     }
     hipError_t e = hipGetLastError();
     return e == hipSuccess ? BCS_OK : hip_fail(e);
@@ -474,6 +703,35 @@ int bcs_release(void) {
     }
     return BCS_OK;
 }
+
+int bcs_timing_begin(void) {
+    g_timing.used = 0;
+    g_timing.on = true;
+    return BCS_OK;
+}
+
+int bcs_timing_end(double *ms_sum, int64_t *launches) {
+    Timing &t = g_timing;
+    t.on = false;
+    if (!ms_sum || !launches) return BCS_EINVAL;
+    for (int k = 0; k < kKernelCount; ++k) {
+        ms_sum[k] = 0.0;
+        launches[k] = 0;
+    }
+    for (int i = 0; i < t.used; ++i) {
+        hipError_t e = hipEventSynchronize(t.stop[i]);
+        if (e != hipSuccess) return hip_fail(e);
+        float ms = 0.f;
+        e = hipEventElapsedTime(&ms, t.start[i], t.stop[i]);
+        if (e != hipSuccess) return hip_fail(e);
+        ms_sum[t.kid[i]] += (double)ms;
+        launches[t.kid[i]] += 1;
+    }
+    t.used = 0;
+    return BCS_OK;
+}
+
+const char *bcs_kernel_name(int id) { return (id >= 0 && id < kKernelCount) ? kKernelNames[id] : "?"; }
 
 const char *bcs_strerror(int code) {
     switch (code) {
