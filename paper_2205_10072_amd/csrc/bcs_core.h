@@ -3,27 +3,47 @@
 //
 // Method: J. L. Traff, arXiv 2205.10072, Section 2 (Alg. 1, 2, 4).  Block sets are 32-bit masks.
 //
-// How a lane finds the baseblocks of a rank range [a, b] (what the paper's Alg. 3 is for) is this
-// library's own routine.  It rests on the self-similarity stated after Alg. 2: rank skips[k] has
+// Two routines answer "which baseblocks do the ranks a..b hold" (what the paper's Alg. 3 is for).
+// Both are this library's own and rest on the self-similarity stated after Alg. 2: rank skips[k] has
 // baseblock k, and ranks skips[k]+1 .. skips[k+1]-1 repeat the baseblocks of ranks
-// 1 .. skips[k+1]-skips[k]-1.  Walking the levels k = q-1 .. 0 once:
+// 1 .. skips[k+1]-skips[k]-1.
+//
+// (1) The level walk (range_blocks), exact for any range, 25 vector ops a level.  For k = q-1 .. 0:
 //   b <  skips[k]            nothing at this level;
 //   a >  skips[k] (<= b)     the range lies in the upper copy: move it down by skips[k];
 //   a <= skips[k] <= b       block k is in; so are the blocks of ranks 1 .. b-skips[k], which are
 //                            exactly 0 .. (largest level whose skip is <= b-skips[k]); what is left
 //                            is [a, skips[k]-1], handled by the remaining levels.
-// The walk is branch-free (compare / select), so the lanes of a wave never diverge in it.
+// It builds the small table below and serves as the reference in the host tests.
+//
+// (2) The digit form (digits + window_blocks), which Alg. 4 runs on.  Write a rank as the greedy sum
+// of skips, largest first (the walk of Alg. 2); its digit mask D(y) has bit k set when skips[k] was
+// taken, and the baseblock is the lowest set bit.  D is order preserving, so for a window (y1, y2]:
+//   - the first level k (from the top) where D(y1) and D(y2) differ holds a rank with baseblock k,
+//     the largest block of the window;
+//   - the ranks above that node are a prefix of the level-k pattern: blocks 0 .. (highest digit of
+//     D(y2) below k);
+//   - the ranks below it are a tail of the pattern: blocks 0 .. l1 with l1 the highest clear digit of
+//     D(y1) below k -- provided l1 >= 7.  Each copy of the pattern in the upper half of its parent
+//     lacks its last rank when the parent skip is odd, and below level 7 these missing ranks can be
+//     the only holders of a block; there the answer is read from a table indexed by the number of
+//     odd levels passed and the seven low digits.  The table depends on skips[7] only (64 shapes;
+//     another 64 for p <= 64) and is filled by the level walk.
+// The windows of Alg. 4 share their end points (round i ends where round i+1 begins), so a row costs
+// q+1 digit masks (3 vector ops a level) and a few bit operations per round.
+// All of it is branch-free apart from the wave-uniform test for Alg. 4's rare second range.
 #ifndef BCS_CORE_H
 #define BCS_CORE_H
 
+#include <stddef.h>
 #include <stdint.h>
 
 #if defined(__HIP_DEVICE_COMPILE__)
-#define BCS_HD __device__ __forceinline__
+#define BCS_HD __host__ __device__ __forceinline__
 #define BCS_WAVE_ANY(x) __any(x)
 #define BCS_CLZ(x) __clz((int)(x))
 #elif defined(__HIPCC__)
-#define BCS_HD __device__ __forceinline__
+#define BCS_HD __host__ __device__ __forceinline__
 #define BCS_WAVE_ANY(x) (x)
 #define BCS_CLZ(x) ((x) ? __builtin_clz(x) : 32)
 #else
@@ -36,8 +56,31 @@ namespace bcs {
 
 constexpr int kMaxQ = 31;
 
+// Low-level table: kLowShapes shapes x kLowRows rows x 128 digit patterns, one byte (a 7-bit block
+// mask) each.  Shape: skips[7] - 65 when q >= 7, else 63 + p.  Row d < 25: tail of the level-7 pattern
+// cut short by d ranks; row 25 + k: tail of the level-k pattern, k <= 7.
+constexpr int kLowLevels = 7;
+constexpr int kLowShapes = 128;
+constexpr int kLowRows = 25 + kLowLevels + 1;
+constexpr int kLowShapeBytes = kLowRows * 128;
+constexpr int kLowTableBytes = kLowShapes * kLowShapeBytes;
+
+BCS_HD int ceil_log2(uint32_t p) { return p > 1u ? 32 - BCS_CLZ(p - 1u) : 0; }
+BCS_HD int low_shape(uint32_t p, int q) { return q >= kLowLevels ? (int)(((p - 1u) >> (q - kLowLevels)) + 1u) - 65 : 63 + (int)p; }
+// bit k set when skips[k+1] is odd, i.e. 2*skips[k] - skips[k+1] = 1: bit q-1-k of p-1 is clear
+BCS_HD uint32_t odd_levels(uint32_t p, int q) {
+#if defined(__HIP_DEVICE_COMPILE__)
+    return q ? __brev(~(p - 1u) & (0xffffffffu >> (32 - q))) >> (32 - q) : 0u;
+#else
+    uint32_t m = 0;
+    for (int k = 0; k < q; ++k) m |= ((~(p - 1u) >> (q - 1 - k)) & 1u) << k;
+    return m;
+#endif
+}
+
 struct SkipTab {
     uint32_t s[kMaxQ + 2];               // s[0..q]; entries above q repeat p
+    uint32_t odd;                        // odd_levels(p, q)
 };
 
 // ----------------------------------------------------------------------------------------------
@@ -49,6 +92,9 @@ template <int Q>
 struct Uniform {
     uint32_t S[Q + 1];
     const SkipTab *tab;                  // same values, for wave-uniform dynamic indices
+    const uint8_t *low;                  // this p's shape of the low-level table
+    BCS_HD uint32_t odd_mask() const { return tab->odd; }
+    BCS_HD const uint8_t *lowtab() const { return low; }
     BCS_HD int q() const { return Q; }
     BCS_HD int top() const { return Q - 1; }
     BCS_HD uint32_t p() const { return S[Q]; }
@@ -62,6 +108,10 @@ struct PerLane {
     uint32_t pm1;                        // p - 1
     int ql;                              // this lane's q
     int wave_top;                        // largest q in the wave, minus 1 (uniform loop bound)
+    uint32_t odd;                        // odd_levels(p, q)
+    const uint8_t *low;                  // this lane's shape of the low-level table
+    BCS_HD uint32_t odd_mask() const { return odd; }
+    BCS_HD const uint8_t *lowtab() const { return low; }
     BCS_HD int q() const { return ql; }
     BCS_HD int top() const { return wave_top; }
     BCS_HD uint32_t p() const { return pm1 + 1u; }
@@ -104,72 +154,122 @@ BCS_HD uint32_t range_blocks(const Pol &pol, uint32_t a, uint32_t b) {
     return m;
 }
 
-// Alg. 2 as a level walk (largest skip first, subtract while it fits): returns the baseblock of
-// v > 0 and, in `home`, the level h with skips[h] <= v < skips[h+1] (-1 for the root).
+// One entry of the low-level table, by the level walk on the small system p' that the shape names.
+BCS_HD uint32_t low_table_entry(int shape, int row, int low) {
+    const uint32_t pp = shape < 64 ? (uint32_t)shape + 65u : (uint32_t)shape - 63u;
+    const int qq = ceil_log2(pp);
+    PerLane pol;
+    pol.pm1 = pp - 1u;
+    pol.ql = qq;
+    pol.wave_top = kLowLevels - 1;
+    pol.odd = 0;
+    pol.low = nullptr;
+    int k;
+    uint32_t cut;
+    if (row < 25) {
+        if (qq < kLowLevels) return 0u;
+        k = kLowLevels;
+        cut = (uint32_t)row;
+    } else {
+        k = row - 25;
+        cut = 0u;
+        if (k > qq) return 0u;
+    }
+    uint32_t a = 1u;                                     // first rank after the one the digits name
+    for (int j = 0; j < k; ++j)
+        if ((low >> j) & 1) a += pol.s(j);
+    const uint32_t top = pol.s(k);                       // k = qq gives p'
+    if (top < 2u + cut) return 0u;
+    const uint32_t b = top - 1u - cut;
+    return a <= b ? range_blocks(pol, a, b) : 0u;
+}
+
+// Alg. 2's walk, keeping which skips were taken: bit k of the result is set when skips[k] is part of
+// the greedy sum of y (0 <= y < p).  The lowest set bit is the baseblock, the highest the home level.
 template <class Pol>
-BCS_HD int baseblock_and_home(const Pol &pol, uint32_t v, int &home) {
-    int own = 0, h = -1;
-    uint32_t y = v;
+BCS_HD uint32_t digits(const Pol &pol, uint32_t y) {
+    uint32_t d = 0;
 #pragma unroll
     for (int k = pol.top(); k >= 0; --k) {
         const uint32_t s = pol.s(k);
-        const bool fits = s <= y;
-        h = (fits && h < 0) ? k : h;
-        own = fits ? k : own;
-        y = fits ? y - s : y;
+        const bool take = y >= s;
+        y = take ? y - s : y;
+        d = (d << 1) | (take ? 1u : 0u);
     }
-    home = h;
-    return own;
+    return d;
+}
+
+// Baseblocks of the ranks after the one with digits d_lo up to the one with digits d_hi (d_lo < d_hi
+// as integers; both may carry one more digit above level q-1 that counts laps around the ring, in
+// which case the result has that bit set for rank 0 and the caller drops it).  0 when d_lo == d_hi.
+template <class Pol>
+BCS_HD uint32_t window_blocks(const Pol &pol, uint32_t d_lo, uint32_t d_hi) {
+    const uint32_t diff = d_lo ^ d_hi;
+    const int k = 31 - BCS_CLZ(diff);
+    const uint32_t node = 1u << (k & 31);
+    const uint32_t below = node - 1u;
+    const uint32_t up = d_hi & below;                          // ranks above the node: a prefix
+    const uint32_t pre = up ? (0xffffffffu >> BCS_CLZ(up)) : 0u;
+    const uint32_t low = d_lo & below;                         // ranks below it: a tail
+    const uint32_t clear = ~low & below;
+    const uint32_t tail = clear ? (0xffffffffu >> BCS_CLZ(clear)) : 0u;
+    const uint32_t run = below & ~127u;                        // levels 7..k-1
+    const int passed = __builtin_popcount(pol.odd_mask() & run);
+    const int row = k > kLowLevels ? passed : 25 + k;
+    const uint32_t small = pol.lowtab()[row * 128 + (int)(low & 127u)];
+    const uint32_t suf = (clear >> kLowLevels) ? tail : small;
+    return diff ? (node | pre | suf) : 0u;
 }
 
 // Alg. 4: entries 0..last of the receive schedule of virtual rank v; emit(i, value) per entry.
 // The rank's own baseblock starts the set B of blocks it already has.  Round i looks for the largest
 // new block among ranks v-skips[i+1]+1 .. v-skips[i]; if there is none, among ranks
-// v-sum_{j<=i}skips[j] .. v-skips[i+1].  Ranks are mod p and rank 0 owns no baseblock.  The i = 0 and
-// i = q-1 special cases printed in Alg. 4 are instances of this rule.
+// v-sum_{j<=i}skips[j] .. v-skips[i+1], which are the last c ranks before the first range, c being the
+// number of odd levels up to i (because skips[i+1] = 1 + sum_{j<=i}(skips[j] - odd_j)).  Ranks are
+// mod p and rank 0 owns no baseblock.  The i = 0 and i = q-1 special cases printed in Alg. 4 are
+// instances of this rule.  End points are kept as v + p - skips[i] in [0, 2p): digits of the rank plus
+// a lap digit at level q, so that every window is an increasing pair.
 template <class Pol, class Emit>
 BCS_HD void recv_row(const Pol &pol, uint32_t v, int last, Emit emit) {
     const uint32_t p = pol.p();
     const int q = pol.q();
-    int home;
-    const int own = baseblock_and_home(pol, v, home);
+    const uint32_t lap = 1u << (q & 31);
+    const uint32_t dv = digits(pol, v);
+    const int home = 31 - BCS_CLZ(dv);                    // -1 for the root
+    const int own = dv ? __builtin_ctz(dv) : 0;
     uint32_t B = v ? (1u << own) : 0u;
-    const uint32_t all = (q >= 32) ? 0xffffffffu : ((1u << q) - 1u);
-    uint32_t psum = 0;
+    const uint32_t odd = pol.odd_mask();
     uint32_t s_i = pol.sdyn(0);
+    uint32_t d_hi = digits(pol, v >= s_i ? v - s_i : v + p - s_i) | (v >= s_i ? lap : 0u);
+    uint32_t c = 0;
 #pragma unroll 1
     for (int i = 0; i <= last; ++i) {
         const uint32_t s_n = pol.sdyn(i + 1);
-        psum += s_i;
-        const bool active = i < q;                       // per-lane q may be below the wave's bound
+        const bool active = i < q;                        // per-lane q may be below the wave's bound
         const bool is_home = (i == home);
-        // first range; for i > home it wraps below rank 0 and is taken p higher
-        const uint32_t base = (v >= s_n) ? v : v + p;
-        uint32_t a = base - s_n + 1u, b = base - s_i;
-        if (is_home || !active) { a = 1u; b = 0u; }
-        uint32_t U = range_blocks(pol, a, b) & ~B;
+        const bool ahead = v >= s_n;
+        const uint32_t y = ahead ? v - s_n : v + p - s_n;
+        const uint32_t d_lo = digits(pol, y) | (ahead ? lap : 0u);
+        c += (odd >> i) & 1u;
+        uint32_t U = window_blocks(pol, d_lo, d_hi) & ~lap & ~B;
         const bool need2 = active && !is_home && U == 0u;
         if (BCS_WAVE_ANY(need2)) {
-            // second range, possibly cut in two by rank 0
-            int64_t lo = (int64_t)v - (int64_t)psum, hi = (int64_t)v - (int64_t)s_n;
-            const bool whole = (hi - lo + 1) >= (int64_t)p;
-            if (hi < 0) { lo += p; hi += p; }
-            uint32_t a1, b1, a2 = 1u, b2 = 0u;
-            if (lo >= 1) { a1 = (uint32_t)lo; b1 = (uint32_t)hi; }
-            else { a1 = (uint32_t)(lo + p); b1 = p - 1u; a2 = 1u; b2 = (uint32_t)hi; if (lo == 0) { a1 = 1u; b1 = 0u; } }
-            if (!need2 || whole) { a1 = 1u; b1 = 0u; a2 = 1u; b2 = 0u; }
-            uint32_t U2 = whole ? all : 0u;
-#pragma unroll 1
-            for (int piece = 0; piece < 2; ++piece) {
-                U2 |= range_blocks(pol, piece ? a2 : a1, piece ? b2 : b1);
-            }
-            U = need2 ? (U2 & ~B) : U;
+            // the c ranks that end where the first range begins; one more lap if that runs below 0
+            const uint32_t Y = v + p - s_n;
+            const bool under = Y < c;
+            const uint32_t Z = under ? Y + p - c : Y - c;
+            const uint32_t hi2 = under ? (d_lo | lap) : d_lo;
+            const bool zlap = Z >= p;
+            const uint32_t lo2 = digits(pol, zlap ? Z - p : Z) | (zlap ? lap : 0u);
+            const uint32_t U2 = window_blocks(pol, lo2, hi2) & ~lap & ~B;
+            U = need2 ? U2 : U;
         }
-        const int blk = 31 - BCS_CLZ(U);             // largest candidate
+        const int blk = 31 - BCS_CLZ(U);                  // largest candidate
         if (active) {
             if (is_home) emit(i, own);
             else { B |= 1u << (blk & 31); emit(i, blk - q); }
         }
+        d_hi = d_lo;
         s_i = s_n;
     }
 }

@@ -1,5 +1,6 @@
 // Host build of the per-rank construction in bcs_core.h, one "lane" at a time, so that CPU tests can
 // compare the code the GPU lanes run with the oracle.  Test support; not part of libbcsched.
+#include <stddef.h>
 #include <stdint.h>
 
 #include "bcs_core.h"
@@ -18,6 +19,21 @@ void fill_skips(int32_t p, SkipTab &t) {
     const int q = host_q(p);
     for (int k = 0; k <= q; ++k) t.s[k] = (((uint32_t)p - 1u) >> (q - k)) + 1u;
     for (int k = q + 1; k < kMaxQ + 2; ++k) t.s[k] = (uint32_t)p;
+    t.odd = odd_levels((uint32_t)p, q);
+}
+
+// the low-level table, filled on the host by the same entry function the GPU's fill kernel runs
+uint8_t g_low[kLowTableBytes];
+bool g_low_ready = false;
+const uint8_t *low_for(int32_t p) {
+    if (!g_low_ready) {
+        for (int e = 0; e < kLowTableBytes; ++e) {
+            const int shape = e / kLowShapeBytes, rest = e - shape * kLowShapeBytes;
+            g_low[e] = (uint8_t)low_table_entry(shape, rest >> 7, rest & 127);
+        }
+        g_low_ready = true;
+    }
+    return g_low + (size_t)low_shape((uint32_t)p, host_q(p)) * kLowShapeBytes;
 }
 
 template <int Q>
@@ -25,6 +41,7 @@ void row_uniform(const SkipTab &t, uint32_t v, int last, int32_t *out) {
     Uniform<Q> pol;
     for (int k = 0; k <= Q; ++k) pol.S[k] = t.s[k];
     pol.tab = &t;
+    pol.low = low_for((int32_t)t.s[Q]);
     recv_row(pol, v, last, [&](int i, int val) { out[i] = val; });
 }
 
@@ -33,6 +50,7 @@ uint32_t range_uniform(const SkipTab &t, uint32_t a, uint32_t b) {
     Uniform<Q> pol;
     for (int k = 0; k <= Q; ++k) pol.S[k] = t.s[k];
     pol.tab = &t;
+    pol.low = nullptr;
     return range_blocks(pol, a, b);
 }
 
@@ -83,6 +101,8 @@ int hc_recv_row_perlane(int32_t p, int32_t v, int last, int wave_q, int32_t *out
     pol.pm1 = (uint32_t)p - 1u;
     pol.ql = host_q(p);
     pol.wave_top = wave_q - 1;
+    pol.odd = odd_levels((uint32_t)p, pol.ql);
+    pol.low = low_for(p);
     recv_row(pol, (uint32_t)v, last, [&](int i, int val) { out[i] = val; });
     return 0;
 }

@@ -8,6 +8,7 @@
 #include <hip/hip_runtime.h>
 #include <hip/hip_ext.h>
 #include <stdint.h>
+#include <mutex>
 #include <utility>
 
 #include "bcsched.h"
@@ -69,6 +70,26 @@ void launch(int kid, void (*kernel)(KArgs...), dim3 grid, dim3 block, hipStream_
 }
 
 // ----------------------------------------------------------------------------------------------
+// The low-level table of bcs_core.h lives in the code object; k_build_lowtab fills it once per device
+// and process (one thread per entry, by the level walk).
+// ----------------------------------------------------------------------------------------------
+__device__ uint8_t g_lowtab[kLowTableBytes];
+
+__global__ __launch_bounds__(kBlock) void k_build_lowtab() {
+    const int e = blockIdx.x * kBlock + threadIdx.x;
+    if (e >= kLowTableBytes) return;
+    const int shape = e / kLowShapeBytes;
+    const int rest = e - shape * kLowShapeBytes;
+    g_lowtab[e] = (uint8_t)low_table_entry(shape, rest >> 7, rest & 127);
+}
+
+// copies one shape of the table (kLowShapeBytes, a multiple of 4) into LDS; callers synchronise
+__device__ __forceinline__ void stage_lowtab(uint32_t *dst, int shape) {
+    const uint32_t *src = reinterpret_cast<const uint32_t *>(g_lowtab + (size_t)shape * kLowShapeBytes);
+    for (int i = threadIdx.x; i < kLowShapeBytes / 4; i += kBlock) dst[i] = src[i];
+}
+
+// ----------------------------------------------------------------------------------------------
 // K1: receive rows of ranks [r0, r1), uniform p.  Lane = rank.  Rows are staged in LDS (odd stride,
 // conflict-free) and leave as contiguous dwords; optionally each entry is also stored slot-major
 // (recvT[k][r - r0]) for the send look-up that follows.
@@ -79,11 +100,15 @@ __global__ __launch_bounds__(kBlock) void k_recv_uniform(const SkipTab tab, uint
                                                          int32_t *__restrict__ recvT, uint64_t ldT) {
     constexpr int kStride = Q | 1;
     __shared__ int32_t tile[kBlock * kStride];
+    __shared__ uint32_t lowtab[kLowShapeBytes / 4];
     Uniform<Q> pol;
 #pragma unroll
     for (int k = 0; k <= Q; ++k) pol.S[k] = tab.s[k];
     pol.tab = &tab;
+    pol.low = reinterpret_cast<const uint8_t *>(lowtab);
     const uint32_t p = pol.p();
+    stage_lowtab(lowtab, low_shape(p, Q));
+    __syncthreads();
     const uint64_t first = (uint64_t)blockIdx.x * kBlock;       // offset of this tile inside [r0, r1)
     const uint64_t idx = first + threadIdx.x;
     const uint64_t count = (uint64_t)r1 - r0;
@@ -143,11 +168,15 @@ __global__ __launch_bounds__(kBlock) void k_send_recompute(const SkipTab tab, ui
                                                            int32_t *__restrict__ send_out) {
     constexpr int kStride = Q | 1;
     __shared__ int32_t tile[kBlock * kStride];
+    __shared__ uint32_t lowtab[kLowShapeBytes / 4];
     Uniform<Q> pol;
 #pragma unroll
     for (int k = 0; k <= Q; ++k) pol.S[k] = tab.s[k];
     pol.tab = &tab;
+    pol.low = reinterpret_cast<const uint8_t *>(lowtab);
     const uint32_t p = pol.p();
+    stage_lowtab(lowtab, low_shape(p, Q));
+    __syncthreads();
     const uint64_t first = (uint64_t)blockIdx.x * kBlock;
     const uint64_t idx = first + threadIdx.x;
     const uint64_t count = (uint64_t)r1 - r0;
@@ -200,6 +229,8 @@ __global__ __launch_bounds__(kBlock) void k_batch(int64_t count, const int32_t *
     pol.pm1 = p - 1u;
     pol.ql = q;
     pol.wave_top = qmax - 1;
+    pol.odd = odd_levels(p, q);
+    pol.low = g_lowtab + (size_t)low_shape(p, q) * kLowShapeBytes;
     const uint32_t v = (uint32_t)ri >= (uint32_t)rooti ? (uint32_t)(ri - rooti) : (uint32_t)ri + p - (uint32_t)rooti;
     int32_t *my = tile + threadIdx.x * kStride;
     const int64_t rows = (count - first) < (int64_t)kBlock ? (count - first) : (int64_t)kBlock;
@@ -470,14 +501,58 @@ int host_skips(int32_t p, SkipTab &t) {
     }
     t.s[k] = v;
     for (int j = q + 1; j < kMaxQ + 2; ++j) t.s[j] = (uint32_t)p;
+    t.odd = odd_levels((uint32_t)p, q);
     return q;
+}
+
+// Fills g_lowtab on first use per device.  The fill is enqueued on the first caller's stream; until
+// it has finished, callers on other streams are made to wait for it on the device.
+struct LowTabState {
+    bool launched = false;
+    bool done = false;
+    hipStream_t stream = nullptr;
+    hipEvent_t ready = nullptr;
+};
+constexpr int kMaxDevices = 64;
+LowTabState g_lowtab_state[kMaxDevices];
+std::mutex g_lowtab_mutex;
+
+int ensure_lowtab(hipStream_t st) {
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return hip_fail(e);
+    if (dev < 0 || dev >= kMaxDevices) return BCS_EINVAL;
+    std::lock_guard<std::mutex> lock(g_lowtab_mutex);
+    LowTabState &s = g_lowtab_state[dev];
+    if (s.done) return BCS_OK;
+    if (!s.launched) {
+        e = hipEventCreateWithFlags(&s.ready, hipEventDisableTiming);
+        if (e != hipSuccess) return hip_fail(e);
+        hipLaunchKernelGGL(k_build_lowtab, dim3((kLowTableBytes + kBlock - 1) / kBlock), dim3(kBlock), 0, st);
+        e = hipGetLastError();
+        if (e != hipSuccess) return hip_fail(e);
+        e = hipEventRecord(s.ready, st);
+        if (e != hipSuccess) return hip_fail(e);
+        s.launched = true;
+        s.stream = st;
+        return BCS_OK;
+    }
+    if (hipEventQuery(s.ready) == hipSuccess) {
+        s.done = true;
+        return BCS_OK;
+    }
+    (void)hipGetLastError();                       // hipErrorNotReady is not an error here
+    if (st != s.stream) {
+        e = hipStreamWaitEvent(st, s.ready, 0);
+        if (e != hipSuccess) return hip_fail(e);
+    }
+    return BCS_OK;
 }
 
 struct Scratch {
     void *ptr = nullptr;
     size_t bytes = 0;
 };
-constexpr int kMaxDevices = 64;
 Scratch g_scratch[kMaxDevices];
 
 int scratch_get(size_t bytes, void **out) {
@@ -593,6 +668,8 @@ int bcs_sched_rooted_ws(int32_t p, int32_t root, int32_t r0, int32_t r1, int32_t
     if (need > 0 && (!workspace || workspace_bytes < (size_t)need)) return BCS_ENOMEM;
     SkipTab tab;
     host_skips(p, tab);
+    rc = ensure_lowtab((hipStream_t)stream);
+    if (rc != BCS_OK) return rc;
     const uint64_t ld = round_up((uint64_t)p, 64);
     return launch_for_q(q)(tab, (uint32_t)root, (uint32_t)r0, (uint32_t)r1, recv_out, send_out,
                            need > 0 ? (int32_t *)workspace : nullptr, ld, (hipStream_t)stream);
@@ -623,6 +700,8 @@ int bcs_sched_batch(int64_t count, const int32_t *p, const int32_t *r, const int
     if (count == 0) return BCS_OK;
     const uint64_t blocks = ((uint64_t)count + kBlock - 1) / kBlock;
     if (blocks > 0x7fffffffull) return BCS_EINVAL;
+    const int rc = ensure_lowtab((hipStream_t)stream);
+    if (rc != BCS_OK) return rc;
     launch(kBatch, k_batch, dim3((unsigned)blocks), dim3(kBlock), (hipStream_t)stream, count, p, r, root,
                        recv_out, send_out, q_out);
     hipError_t e = hipGetLastError();
