@@ -90,6 +90,7 @@ struct SkipTab {
 // ----------------------------------------------------------------------------------------------
 template <int Q>
 struct Uniform {
+    static constexpr bool kScalarSkips = true;   // skips are wave-uniform (SGPR operands)
     uint32_t S[Q + 1];
     const SkipTab *tab;                  // same values, for wave-uniform dynamic indices
     const uint8_t *low;                  // this p's shape of the low-level table
@@ -105,6 +106,7 @@ struct Uniform {
 };
 
 struct PerLane {
+    static constexpr bool kScalarSkips = false;
     uint32_t pm1;                        // p - 1
     int ql;                              // this lane's q
     int wave_top;                        // largest q in the wave, minus 1 (uniform loop bound)
@@ -188,6 +190,39 @@ BCS_HD uint32_t low_table_entry(int shape, int row, int low) {
 // the greedy sum of y (0 <= y < p).  The lowest set bit is the baseblock, the highest the home level.
 template <class Pol>
 BCS_HD uint32_t digits(const Pol &pol, uint32_t y) {
+#if defined(__HIP_DEVICE_COMPILE__)
+    // three vector ops a level: subtract with borrow-out, keep the old value on borrow, shift the borrow
+    // into the (inverted) digit mask.  gfx950 wants two wait states between a vector op that writes
+    // vcc and one that reads it, hence the s_nop.
+    uint32_t inv = 0;
+    if constexpr (Pol::kScalarSkips) {
+#pragma unroll
+        for (int k = pol.top(); k >= 0; --k) {
+            uint32_t t;
+            asm("v_subrev_co_u32 %0, vcc, %3, %1\n\t"
+                "s_nop 1\n\t"
+                "v_cndmask_b32 %1, %0, %1, vcc\n\t"
+                "v_addc_co_u32 %2, vcc, %2, %2, vcc"
+                : "=&v"(t), "+v"(y), "+v"(inv)
+                : "s"(pol.s(k))
+                : "vcc");
+        }
+    } else {
+#pragma unroll 1
+        for (int k = pol.top(); k >= 0; --k) {
+            uint32_t t;
+            asm("v_subrev_co_u32 %0, vcc, %3, %1\n\t"
+                "s_nop 1\n\t"
+                "v_cndmask_b32 %1, %0, %1, vcc\n\t"
+                "v_addc_co_u32 %2, vcc, %2, %2, vcc"
+                : "=&v"(t), "+v"(y), "+v"(inv)
+                : "v"(pol.s(k))
+                : "vcc");
+        }
+    }
+    const int levels = pol.top() + 1;
+    return levels > 0 ? (~inv & (0xffffffffu >> (32 - levels))) : 0u;
+#else
     uint32_t d = 0;
 #pragma unroll
     for (int k = pol.top(); k >= 0; --k) {
@@ -197,6 +232,7 @@ BCS_HD uint32_t digits(const Pol &pol, uint32_t y) {
         d = (d << 1) | (take ? 1u : 0u);
     }
     return d;
+#endif
 }
 
 // Baseblocks of the ranks after the one with digits d_lo up to the one with digits d_hi (d_lo < d_hi

@@ -101,6 +101,29 @@ def test_sub_ranges_roots_and_single_tables(bcs, oracle):
     assert bool((recv == 777).all()) and bool((send == 777).all())
 
 
+def test_every_q_from_1_to_31(bcs, oracle):
+    """One kernel instance exists per q: each is run on two p of that bit length (one random, one 2^q or 2^(q-1)+1),
+    over all ranks when that is cheap and over ragged chunks otherwise, with both ways of making send rows."""
+    rng = np.random.default_rng(31)
+    for q in range(1, 32):
+        lo, hi = (1 << (q - 1)) + 1, min(1 << q, 2**31 - 1)
+        for p in {int(rng.integers(lo, hi + 1)), hi, lo}:
+            assert bcs.bcs_q(p) == q
+            root = int(rng.integers(0, p))
+            if p <= 300000:
+                recv, send = gpu_sched(bcs, p, root=root)
+                orecv, osend = oracle.sched_range(p, root=root, threads=16)
+                assert np.array_equal(recv, orecv), (p, root)
+                assert np.array_equal(send, osend), (p, root)
+            starts = [0, max(0, p - 700)] + [int(v) for v in rng.integers(0, max(1, p - 700), 2)]
+            for r0 in starts:
+                r1 = min(p, r0 + 700)
+                recv, send = gpu_sched(bcs, p, root=root, r0=r0, r1=r1)
+                orecv, osend = oracle.sched_range(p, root=root, r0=r0, r1=r1, threads=16)
+                assert np.array_equal(recv, orecv), (p, root, r0)
+                assert np.array_equal(send, osend), (p, root, r0)
+
+
 def test_largest_p_sampled_chunks(bcs, oracle):
     """Config 3 (p = 2^27 - 1, q = 27): chunks at both ends and inside, and p = 2^31 - 1."""
     for p in (134217727, 2**31 - 1):
