@@ -202,21 +202,59 @@ __global__ __launch_bounds__(kBlock) void k_send_recompute(const SkipTab tab, ui
     }
 }
 
-// K3: unrelated (p, r, root) triples, one per lane; rows of BCS_BATCH_STRIDE ints, padded.
-__global__ __launch_bounds__(kBlock) void k_batch(int64_t count, const int32_t *__restrict__ pv,
-                                                  const int32_t *__restrict__ rv, const int32_t *__restrict__ rootv,
-                                                  int32_t *__restrict__ recv_out, int32_t *__restrict__ send_out,
-                                                  int32_t *__restrict__ q_out) {
-    constexpr int kStride = BCS_BATCH_STRIDE + 1;
-    __shared__ int32_t tile[kBlock * kStride];
-    const int64_t first = (int64_t)blockIdx.x * kBlock;
-    const int64_t idx = first + threadIdx.x;
-    const bool live = idx < count;
-    int32_t pi = live ? pv[idx] : 1, ri = live ? rv[idx] : 0, rooti = live ? rootv[idx] : 0;
-    const bool valid = live && pi >= 1 && ri >= 0 && ri < pi && rooti >= 0 && rooti < pi;
-    if (!valid) { pi = 1; ri = 0; rooti = 0; }
-    const uint32_t p = (uint32_t)pi;
-    const int q = p > 1u ? 32 - __clz((int)(p - 1u)) : 0;
+// K3: unrelated (p, r, root) triples; rows of BCS_BATCH_STRIDE ints (one 128-byte line each), padded.
+// A workgroup takes kBatchBlock triples and first orders them by q in LDS (counting sort), because a
+// wave runs its level loops to the largest q among its lanes and the work grows like q^3: after the
+// sort a wave holds neighbouring q only.  Each lane then builds the rows of its triple and stores
+// them entry by entry into the triple's own line.
+constexpr int kBatchBlock = 1024;
+
+__global__ __launch_bounds__(kBatchBlock) void k_batch(int64_t count, const int32_t *__restrict__ pv,
+                                                       const int32_t *__restrict__ rv,
+                                                       const int32_t *__restrict__ rootv,
+                                                       int32_t *__restrict__ recv_out, int32_t *__restrict__ send_out,
+                                                       int32_t *__restrict__ q_out) {
+    __shared__ uint32_t bins[33];                 // bins[q] for valid triples, bins[32] for the rest
+    __shared__ uint32_t start[33];
+    __shared__ uint32_t s_p[kBatchBlock], s_v[kBatchBlock], s_slot[kBatchBlock];
+    const int64_t first = (int64_t)blockIdx.x * kBatchBlock;
+    {
+        const int64_t idx = first + threadIdx.x;
+        const bool live = idx < count;
+        const int32_t pi = live ? pv[idx] : 1, ri = live ? rv[idx] : 0, rooti = live ? rootv[idx] : 0;
+        const bool valid = live && pi >= 1 && ri >= 0 && ri < pi && rooti >= 0 && rooti < pi;
+        const uint32_t p = valid ? (uint32_t)pi : 1u;
+        const int q = ceil_log2(p);
+        const uint32_t v = !valid ? 0u
+                           : ((uint32_t)ri >= (uint32_t)rooti ? (uint32_t)(ri - rooti)
+                                                              : (uint32_t)ri + p - (uint32_t)rooti);
+        if (threadIdx.x < 33) bins[threadIdx.x] = 0u;
+        __syncthreads();
+        const int bin = valid ? q : 32;
+        const uint32_t rank_in_bin = atomicAdd(&bins[bin], 1u);
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            uint32_t acc = 0;
+            for (int k = 0; k < 33; ++k) {
+                start[k] = acc;
+                acc += bins[k];
+            }
+        }
+        __syncthreads();
+        const uint32_t pos = start[bin] + rank_in_bin;
+        s_p[pos] = p;
+        s_v[pos] = v;
+        s_slot[pos] = threadIdx.x | (valid ? 0u : 0x80000000u) | (live ? 0u : 0x40000000u);
+        __syncthreads();
+    }
+    // from here on this lane works on the triple that the sort put at its position
+    const uint32_t p = s_p[threadIdx.x];
+    const uint32_t v = s_v[threadIdx.x];
+    const uint32_t slot = s_slot[threadIdx.x];
+    const bool valid = (slot & 0x80000000u) == 0u;
+    const bool live = (slot & 0x40000000u) == 0u;
+    const int64_t idx = first + (slot & 0xffffu);
+    const int q = ceil_log2(p);
     if (live && q_out) q_out[idx] = valid ? q : -1;
     // largest q in this wave bounds the level loops of all its lanes
     int qmax = q;
@@ -231,36 +269,24 @@ __global__ __launch_bounds__(kBlock) void k_batch(int64_t count, const int32_t *
     pol.wave_top = qmax - 1;
     pol.odd = odd_levels(p, q);
     pol.low = g_lowtab + (size_t)low_shape(p, q) * kLowShapeBytes;
-    const uint32_t v = (uint32_t)ri >= (uint32_t)rooti ? (uint32_t)(ri - rooti) : (uint32_t)ri + p - (uint32_t)rooti;
-    int32_t *my = tile + threadIdx.x * kStride;
-    const int64_t rows = (count - first) < (int64_t)kBlock ? (count - first) : (int64_t)kBlock;
-    const uint32_t n = (uint32_t)rows * BCS_BATCH_STRIDE;
-
     if (recv_out) {
-#pragma unroll
-        for (int k = 0; k < BCS_BATCH_STRIDE; ++k) my[k] = BCS_BATCH_PAD;
-        recv_row(pol, v, qmax - 1, [&](int i, int val) { my[i] = val; });
-        __syncthreads();
-        int32_t *dst = recv_out + first * BCS_BATCH_STRIDE;
-        for (uint32_t e = threadIdx.x; e < n; e += kBlock)
-            dst[e] = tile[(e >> 5) * kStride + (e & 31u)];
-        __syncthreads();
+        int32_t *row = recv_out + idx * BCS_BATCH_STRIDE;
+        recv_row(pol, v, qmax - 1, [&](int i, int val) { if (live) row[i] = val; });
+        if (live)
+            for (int k = q; k < BCS_BATCH_STRIDE; ++k) row[k] = BCS_BATCH_PAD;
     }
     if (send_out) {
-#pragma unroll
-        for (int k = 0; k < BCS_BATCH_STRIDE; ++k) my[k] = BCS_BATCH_PAD;
+        int32_t *row = send_out + idx * BCS_BATCH_STRIDE;
 #pragma unroll 1
         for (int i = 0; i < qmax; ++i) {
             uint32_t t = v + (i < q ? pol.s(i) : 0u);
             t = t >= p ? t - p : t;
             int32_t keep = 0;
             recv_row(pol, t, i, [&](int j, int val) { keep = (j == i) ? val : keep; });
-            if (i < q) my[i] = keep;
+            if (live && i < q) row[i] = keep;
         }
-        __syncthreads();
-        int32_t *dst = send_out + first * BCS_BATCH_STRIDE;
-        for (uint32_t e = threadIdx.x; e < n; e += kBlock)
-            dst[e] = tile[(e >> 5) * kStride + (e & 31u)];
+        if (live)
+            for (int k = q; k < BCS_BATCH_STRIDE; ++k) row[k] = BCS_BATCH_PAD;
     }
 }
 
@@ -698,11 +724,11 @@ int bcs_sched_batch(int64_t count, const int32_t *p, const int32_t *r, const int
     if (count < 0 || !p || !r || !root) return BCS_EINVAL;
     if (!recv_out && !send_out && !q_out) return BCS_EINVAL;
     if (count == 0) return BCS_OK;
-    const uint64_t blocks = ((uint64_t)count + kBlock - 1) / kBlock;
+    const uint64_t blocks = ((uint64_t)count + kBatchBlock - 1) / kBatchBlock;
     if (blocks > 0x7fffffffull) return BCS_EINVAL;
     const int rc = ensure_lowtab((hipStream_t)stream);
     if (rc != BCS_OK) return rc;
-    launch(kBatch, k_batch, dim3((unsigned)blocks), dim3(kBlock), (hipStream_t)stream, count, p, r, root,
+    launch(kBatch, k_batch, dim3((unsigned)blocks), dim3(kBatchBlock), (hipStream_t)stream, count, p, r, root,
                        recv_out, send_out, q_out);
     hipError_t e = hipGetLastError();
     return e == hipSuccess ? BCS_OK : hip_fail(e);
