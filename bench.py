@@ -29,17 +29,11 @@ HBM_PEAK_GBS = 8000.0                       # MI355X HBM3E
 INT_VALU_PEAK_GOPS = 256 * 4 * 16 * 2.4     # CUs x SIMDs x lanes x GHz = 39 321.6 G lane-ops/s (32-bit, full rate)
 
 
-def valu_ops_per_rank(q, kernel):
-    """Vector-ALU lane-operations one rank costs on the non-divergent path, counted from the ISA of the
-    kernels ('algorithmic work')."""
-    if kernel == "k_recv_uniform":
-        return q * (q * OPS_PER_LEVEL + OPS_PER_ROUND) + q * OPS_BASEBLOCK_LEVEL
-    raise KeyError(kernel)
-
-
-OPS_PER_LEVEL = 25         # one level of the range walk (compare, select, prefix mask) in k_recv_uniform
-OPS_PER_ROUND = 24         # per-round set-up and choice of the largest new block
-OPS_BASEBLOCK_LEVEL = 5    # one level of the baseblock walk
+def valu_ops_per_rank(q):
+    """Vector-ALU lane-operations one receive row costs on the main path of k_recv_uniform, counted from its
+    ISA: q+2 digit walks of 3 ops a level, 55 ops of window logic and bookkeeping a round, 50 of set-up.
+    The wave-uniform branch for Alg. 4's second range is extra work and not counted."""
+    return 3 * q * (q + 2) + 55 * q + 50
 
 
 def cpu_baseline(budget_s=12.0):
@@ -125,7 +119,7 @@ def main():
             nbytes = 2 * P * q * 4                              # read one table, write one table
             ent.update(bound="hbm", achieved=nbytes / avg_ms / 1e6, peak=HBM_PEAK_GBS, unit="GB/s")
         elif name == "k_recv_uniform":
-            ops = valu_ops_per_rank(q, name) * P
+            ops = valu_ops_per_rank(q) * P
             ent.update(bound="alu", achieved=ops / avg_ms / 1e6, peak=INT_VALU_PEAK_GOPS, unit="Gop/s")
         else:
             continue
