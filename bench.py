@@ -36,23 +36,47 @@ def valu_ops_per_rank(q):
     return 3 * q * (q + 2) + 55 * q + 50
 
 
-def cpu_baseline(budget_s=12.0):
-    """The oracle, as it stands, on the host cores: whole steps of the same workload until the budget is spent."""
+def measure_valu_peak(torch, bcs):
+    """Integer vector-ALU rate this GPU reaches on independent full-rate ops (G lane-ops/s)."""
+    blocks, iters = 256 * 32, 4096
+    sink = torch.empty(blocks * 256, dtype=torch.int32, device="cuda")
+    bcs.bcs_valu_peak_launch(blocks, iters, sink)
+    torch.cuda.synchronize()
+    bcs.bcs_timing_begin()
+    for _ in range(5):
+        bcs.bcs_valu_peak_launch(blocks, iters, sink)
+    torch.cuda.synchronize()
+    ms, cnt = bcs.bcs_timing_end()["k_valu_peak"]
+    ops = blocks * 256 * iters * bcs.VALU_PEAK_OPS_PER_ITER
+    return ops / (ms / cnt) / 1e6
+
+
+def cpu_baseline(budget_s=10.0):
+    """The oracle, as it stands, on the host cores: whole steps of the same workload until the budget is spent;
+    then one more step on a single thread."""
     import oracle
+
+    def one_step(threads):
+        recv, send = oracle.sched_range(P, root=ROOT_RANK, threads=threads)
+        oracle.expand(P, N_BLOCKS, recv, threads=threads)
+        oracle.expand(P, N_BLOCKS, send, threads=threads)
+
     threads = min(16, os.cpu_count() or 1)
     done = 0
     t0 = time.perf_counter()
     while True:
-        recv, send = oracle.sched_range(P, root=ROOT_RANK, threads=threads)
-        oracle.expand(P, N_BLOCKS, recv, threads=threads)
-        oracle.expand(P, N_BLOCKS, send, threads=threads)
+        one_step(threads)
         done += 1
         el = time.perf_counter() - t0
         if el >= budget_s or done >= 50:
             break
+    t1 = time.perf_counter()
+    one_step(1)
+    single = time.perf_counter() - t1
     return {"value": done * P / el, "unit": "rank-schedules/s", "cores": threads, "kind": "oracle",
             "sample": "%d whole steps (all %d ranks: recv by Alg. 4, send by look-up, expansion n=%d), %.1f s"
-                      % (done, P, N_BLOCKS, el)}
+                      % (done, P, N_BLOCKS, el),
+            "single_thread_value": P / single}
 
 
 def main():
@@ -96,6 +120,7 @@ def main():
             b.copy_(a)
         torch.cuda.synchronize()
         del a, b
+    valu_peak_measured = measure_valu_peak(torch, bcs)
     steps = max(1, min(args.steps, 1000))
     bcs.bcs_timing_begin()
     torch.cuda.synchronize()
@@ -120,7 +145,8 @@ def main():
             ent.update(bound="hbm", achieved=nbytes / avg_ms / 1e6, peak=HBM_PEAK_GBS, unit="GB/s")
         elif name == "k_recv_uniform":
             ops = valu_ops_per_rank(q) * P
-            ent.update(bound="alu", achieved=ops / avg_ms / 1e6, peak=INT_VALU_PEAK_GOPS, unit="Gop/s")
+            ent.update(bound="alu", achieved=ops / avg_ms / 1e6, peak=INT_VALU_PEAK_GOPS, unit="Gop/s",
+                       peak_measured=valu_peak_measured, frac_of_measured=ops / avg_ms / 1e6 / valu_peak_measured)
         else:
             continue
         ent["frac"] = ent["achieved"] / ent["peak"]

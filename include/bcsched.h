@@ -136,12 +136,22 @@ int bcs_release(void);
  * 0..BCS_KERNEL_COUNT-1, the summed duration in milliseconds and the number
  * of timed launches into host arrays of BCS_KERNEL_COUNT entries.  Not
  * thread-safe; meant for one measuring thread. */
-#define BCS_KERNEL_COUNT         6
+#define BCS_KERNEL_COUNT         7
 #define BCS_TIMING_MAX_LAUNCHES  4096
 int bcs_timing_begin(void);
 int bcs_timing_end(double *ms_sum_host, int64_t *launches_host);
 /* Name of kernel `id` as a profiler shows it (without template arguments). */
 const char *bcs_kernel_name(int id);
+
+/* Measurement aid, not part of the method: launches a kernel of `blocks`
+ * workgroups of 256 lanes in which every lane executes
+ * iters * BCS_VALU_PEAK_OPS_PER_ITER independent
+ * full-rate 32-bit integer vector operations (add, xor, min, subtract) and then
+ * stores one word to sink[blocks * 256] (device).  Timed with
+ * bcs_timing_begin/end (kernel "k_valu_peak") it gives the integer-ALU rate
+ * this GPU reaches in practice.  BCS_EINVAL for a zero count or NULL sink. */
+#define BCS_VALU_PEAK_OPS_PER_ITER 32
+int bcs_valu_peak_launch(uint32_t blocks, uint32_t iters, uint32_t *sink, void *stream);
 
 /* Text for a BCS_* code; never NULL. */
 const char *bcs_strerror(int code);

@@ -23,9 +23,10 @@ NO_BLOCK = -1
 SYMBOLS = (
     "bcs_q", "bcs_skips", "bcs_rounds", "bcs_sched", "bcs_sched_rooted", "bcs_sched_workspace_bytes",
     "bcs_sched_rooted_ws", "bcs_sched_batch", "bcs_expand", "bcs_release", "bcs_strerror",
-    "bcs_last_hip_error", "bcs_timing_begin", "bcs_timing_end", "bcs_kernel_name",
+    "bcs_last_hip_error", "bcs_timing_begin", "bcs_timing_end", "bcs_kernel_name", "bcs_valu_peak_launch",
 )
-KERNEL_COUNT = 6
+KERNEL_COUNT = 7
+VALU_PEAK_OPS_PER_ITER = 32
 
 _lib = None
 
@@ -68,6 +69,7 @@ def lib():
     L.bcs_timing_end.argtypes = [vp, vp]
     L.bcs_kernel_name.argtypes = [ctypes.c_int]
     L.bcs_kernel_name.restype = ctypes.c_char_p
+    L.bcs_valu_peak_launch.argtypes = [ctypes.c_uint32, ctypes.c_uint32, vp, vp]
     _lib = L
     return L
 
@@ -165,3 +167,8 @@ def bcs_timing_end():
     _check(lib().bcs_timing_end(ctypes.cast(ms, ctypes.c_void_p), ctypes.cast(cnt, ctypes.c_void_p)),
            "bcs_timing_end")
     return {lib().bcs_kernel_name(i).decode(): (ms[i], cnt[i]) for i in range(KERNEL_COUNT) if cnt[i]}
+
+
+def bcs_valu_peak_launch(blocks, iters, sink, stream=None):
+    """`sink`: int32 device tensor of at least blocks * 256 entries."""
+    _check(lib().bcs_valu_peak_launch(blocks, iters, _ptr(sink), _stream(stream)), "bcs_valu_peak_launch")

@@ -29,10 +29,10 @@ inline int hip_fail(hipError_t e) {
 
 // Optional per-kernel device timing (bcs_timing_begin / bcs_timing_end): while it is on, a launch is
 // given a start and a stop event from a fixed pool, so its duration is the device's own.
-enum KernelId { kRecv = 0, kSendLookup, kSendRecompute, kBatch, kExpand, kFill, kKernelCount };
+enum KernelId { kRecv = 0, kSendLookup, kSendRecompute, kBatch, kExpand, kFill, kValuPeak, kKernelCount };
 static_assert(kKernelCount == BCS_KERNEL_COUNT, "header and kernel list disagree");
-const char *const kKernelNames[kKernelCount] = {"k_recv_uniform", "k_send_lookup", "k_send_recompute",
-                                                "k_batch",        "k_expand",      "k_fill"};
+const char *const kKernelNames[kKernelCount] = {"k_recv_uniform", "k_send_lookup", "k_send_recompute", "k_batch",
+                                                "k_expand",       "k_fill",        "k_valu_peak"};
 struct Timing {
     bool on = false;
     int used = 0;
@@ -501,6 +501,35 @@ __global__ __launch_bounds__(kBlock) void k_expand_small(const ExpandArgs a, con
     }
 }
 
+// Measurement aid: the practical ceiling the `alu` roofline is set against.  kValuChains independent chains of
+// full-rate 32-bit integer vector ops of the kinds the construction is made of (add, xor, min, subtract), written
+// as instructions so that the count is exact: `iters` rounds of 4 ops per chain and lane, no memory traffic
+// until one word per lane at the end.
+constexpr int kValuChains = 8;
+static_assert(4 * kValuChains == BCS_VALU_PEAK_OPS_PER_ITER, "header and calibration kernel disagree");
+
+__global__ __launch_bounds__(kBlock) void k_valu_peak(uint32_t iters, uint32_t seed, uint32_t *__restrict__ sink) {
+    uint32_t x[kValuChains];
+#pragma unroll
+    for (int c = 0; c < kValuChains; ++c) x[c] = seed + threadIdx.x * (2u * c + 1u) + blockIdx.x;
+    const uint32_t k1 = seed | 1u, k2 = seed ^ 0x9e3779b9u, k3 = 0xfffffff1u;
+#pragma unroll 1
+    for (uint32_t it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int c = 0; c < kValuChains; ++c) asm volatile("v_add_u32 %0, %1, %0" : "+v"(x[c]) : "s"(k1));
+#pragma unroll
+        for (int c = 0; c < kValuChains; ++c) asm volatile("v_xor_b32 %0, %1, %0" : "+v"(x[c]) : "s"(k2));
+#pragma unroll
+        for (int c = 0; c < kValuChains; ++c) asm volatile("v_min_u32 %0, %1, %0" : "+v"(x[c]) : "s"(k3));
+#pragma unroll
+        for (int c = 0; c < kValuChains; ++c) asm volatile("v_subrev_u32 %0, %1, %0" : "+v"(x[c]) : "s"(k1));
+    }
+    uint32_t acc = 0;
+#pragma unroll
+    for (int c = 0; c < kValuChains; ++c) acc ^= x[c];
+    sink[(size_t)blockIdx.x * kBlock + threadIdx.x] = acc;
+}
+
 __global__ void k_fill(int32_t *__restrict__ out, uint64_t n, int32_t value) {
     const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
     for (uint64_t e = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; e < n; e += stride) out[e] = value;
@@ -807,6 +836,13 @@ int bcs_release(void) {
         if (e != hipSuccess) return hip_fail(e);
     }
     return BCS_OK;
+}
+
+int bcs_valu_peak_launch(uint32_t blocks, uint32_t iters, uint32_t *sink, void *stream) {
+    if (blocks == 0 || iters == 0 || !sink) return BCS_EINVAL;
+    launch(kValuPeak, k_valu_peak, dim3(blocks), dim3(kBlock), (hipStream_t)stream, iters, 0x2205u, sink);
+    hipError_t e = hipGetLastError();
+    return e == hipSuccess ? BCS_OK : hip_fail(e);
 }
 
 int bcs_timing_begin(void) {
