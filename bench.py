@@ -29,6 +29,15 @@ HBM_PEAK_GBS = 8000.0                       # MI355X HBM3E
 INT_VALU_PEAK_GOPS = 256 * 4 * 16 * 2.4     # CUs x SIMDs x lanes x GHz = 39 321.6 G lane-ops/s (32-bit, full rate)
 
 
+# HBM bytes per launch at this workload, from the rocprofv3 counter runs summarised in
+# profiles/bench_c2_kernels.md (FETCH_SIZE scaled x2.0, WRITE_SIZE x1.0 by the 1 GiB copy calibration).
+PROFILED_TRAFFIC_BYTES = {
+    "k_expand": (2 * 53089 + 1130913) * 1024,
+    "k_recv_uniform": (2 * 55 + 172033) * 1024,
+    "k_send_lookup": (2 * 48172 + 86016) * 1024,
+}
+
+
 def valu_ops_per_rank(q):
     """Vector-ALU lane-operations one receive row costs on the main path of k_recv_uniform, counted from its
     ISA: q+2 digit walks of 3 ops a level, 55 ops of window logic and bookkeeping a round, 50 of set-up.
@@ -150,7 +159,7 @@ def main():
         else:
             continue
         ent["frac"] = ent["achieved"] / ent["peak"]
-        ent["traffic"] = None
+        ent["traffic"] = PROFILED_TRAFFIC_BYTES.get(name)
         kernels[name] = ent
     dominant = max(kernels, key=lambda k: kernels[k]["ms_per_step"])
     roofline = dict(kernels[dominant], kernel=dominant)
