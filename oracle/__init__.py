@@ -51,6 +51,7 @@ def _load():
                                     i32p, i32p, ctypes.c_int]
     lib.orc_sched_batch.argtypes = [ctypes.c_int64, i32p, i32p, i32p, i32p, i32p, i32p, ctypes.c_int]
     lib.orc_expand.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int64, i32p, i32p, ctypes.c_int]
+    lib.orc_allgather_tables.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, i32p, i32p]
     _lib = lib
     return lib
 
@@ -162,3 +163,13 @@ def expand(p, n, table, threads=1):
     out = np.zeros((rows, n - 1 + q), dtype=np.int32)
     _check(_load().orc_expand(p, n, rows, _ptr(table), _ptr(out), threads), "expand")
     return out
+
+
+def allgather_tables(p, n, r):
+    """Alg. 9 index arithmetic for process r: (pack[R][p], unpack[R][p]), -1 = nothing."""
+    q = q_of(p)
+    R = n - 1 + q
+    pack = np.zeros((R, p), dtype=np.int32)
+    unpack = np.zeros((R, p), dtype=np.int32)
+    _check(_load().orc_allgather_tables(p, n, r, _ptr(pack), _ptr(unpack)), "allgather_tables")
+    return pack, unpack

@@ -446,3 +446,69 @@ int orc_expand(int32_t p, int32_t n, int64_t rows, const int32_t *in, int32_t *o
     }
     return 0;
 }
+
+/* Alg. 9 (irregular allgather), its index arithmetic for ONE process r: which block of buffer[j] is packed
+ * for sending and which block of buffer[j] the received data is unpacked into, for every root j and every
+ * round.  Steps in the paper's order: the full receive schedule (first loop), the send schedule by look-up
+ * (second loop), x dummy rounds, then per round i (slot k = i mod q) and per j the virtual rank
+ * r' = (r - j + p) mod p, whose send / receive entry k names the block and is then advanced by q.
+ *
+ * Reading: Alg. 9 as printed starts its rounds at i = x but leaves out the adjustment of the schedules that
+ * Alg. 6 makes for the x dummy rounds (entries shifted by -x, slots below x advanced once); its caption speaks
+ * of the same negative / too-large blocks as Alg. 6's, so the adjustment is taken from Alg. 6.  Without it the
+ * allgather does not complete when x != 0 (the tests show this on a mutated copy).
+ *
+ * pack[(i - x) * p + j], unpack[(i - x) * p + j]: block number, -1 = nothing, clamped to n-1; R = n-1+q rows. */
+int orc_allgather_tables(int32_t p, int32_t n, int32_t r, int32_t *pack, int32_t *unpack)
+{
+    int32_t skips[ORC_MAXQ + 2];
+    if (p < 1 || n < 1 || r < 0 || r >= p) return ORC_EINVAL;
+    int q = orc_skips(p, skips);
+    int64_t R = (int64_t)n - 1 + q;
+    if (q == 0) {
+        for (int64_t i = 0; i < R; i++) { pack[i] = -1; unpack[i] = -1; }
+        return 0;
+    }
+    int64_t *recvsched = (int64_t *)malloc(sizeof(int64_t) * (size_t)p * q);
+    int64_t *sendsched = (int64_t *)malloc(sizeof(int64_t) * (size_t)p * q);
+    if (!recvsched || !sendsched) { free(recvsched); free(sendsched); return ORC_ENOMEM; }
+    int rc = 0;
+    for (int32_t j = 0; j < p && !rc; j++) {
+        int32_t row[ORC_MAXQ + 1];
+        rc = recvsched_core(skips, q, j, q - 1, NULL, 0, row);
+        for (int k = 0; k < q; k++) recvsched[(size_t)j * q + k] = row[k];
+    }
+    if (rc) { free(recvsched); free(sendsched); return rc; }
+    for (int32_t j = 0; j < p; j++)
+        for (int k = 0; k < q; k++) {
+            int32_t t = (int32_t)(((int64_t)j + skips[k]) % p);
+            sendsched[(size_t)j * q + k] = recvsched[(size_t)t * q + k];
+        }
+    int64_t x = (q - (n - 1 + q) % q) % q;
+    for (int32_t j = 0; j < p; j++)
+        for (int i = 0; i < q; i++) {
+            int64_t adj = (i < x) ? (q - x) : (-x);
+            recvsched[(size_t)j * q + i] += adj;
+            sendsched[(size_t)j * q + i] += adj;
+        }
+    int64_t i = x;
+    while (i < (int64_t)n + q - 1 + x) {
+        int k = (int)(i % q);
+        for (int32_t j = 0; j < p; j++) {                         /* pack */
+            int32_t rr = (int32_t)(((int64_t)r - j + p) % p);
+            int64_t blk = sendsched[(size_t)rr * q + k];
+            pack[(i - x) * p + j] = (int32_t)(blk < 0 ? -1 : (blk > n - 1 ? n - 1 : blk));
+            sendsched[(size_t)rr * q + k] += q;
+        }
+        for (int32_t j = 0; j < p; j++) {                         /* unpack */
+            int32_t rr = (int32_t)(((int64_t)r - j + p) % p);
+            int64_t blk = recvsched[(size_t)rr * q + k];
+            unpack[(i - x) * p + j] = (int32_t)(blk < 0 ? -1 : (blk > n - 1 ? n - 1 : blk));
+            recvsched[(size_t)rr * q + k] += q;
+        }
+        i = i + 1;
+    }
+    free(recvsched);
+    free(sendsched);
+    return 0;
+}

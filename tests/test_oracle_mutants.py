@@ -15,6 +15,7 @@ import pytest
 sys.path.insert(0, os.path.dirname(os.path.abspath(__file__)))
 from conftest import load_table                      # noqa: E402
 from bcast_sim import simulate, ScheduleError        # noqa: E402
+from allgather_sim import simulate_allgather, AllgatherError   # noqa: E402
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 SRC = os.path.join(os.path.dirname(HERE), "oracle", "bcs_oracle.c")
@@ -51,6 +52,9 @@ MUTANTS = [
     ("expand_no_phase_bump_for_early_slots", "if (i < x) sched[i] = (int64_t)in[row * q + i] - x + q;",
      "if (i < x) sched[i] = (int64_t)in[row * q + i] - x;"),
     ("expand_clamp_to_n", "else if (blk > n - 1) blk = n - 1;", "else if (blk > n) blk = n;"),
+    ("allgather_without_dummy_round_adjustment", "int64_t adj = (i < x) ? (q - x) : (-x);", "int64_t adj = 0;"),
+    ("allgather_wrong_rotation", "int32_t rr = (int32_t)(((int64_t)r - j + p) % p);\n            int64_t blk = sendsched",
+     "int32_t rr = (int32_t)(((int64_t)r + j) % p);\n            int64_t blk = sendsched"),
 ]
 
 
@@ -69,6 +73,7 @@ class Lib:
         L.orc_rangeblocks_scan.restype = ctypes.c_uint32
         L.orc_rangeblocks.argtypes = [ctypes.c_int32, ctypes.c_int64, ctypes.c_int64]
         L.orc_rangeblocks.restype = ctypes.c_uint32
+        L.orc_allgather_tables.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, i32p, i32p]
         self.L = L
 
     @staticmethod
@@ -90,6 +95,15 @@ class Lib:
         send = np.zeros((r1 - r0, q), np.int32)
         rc = self.L.orc_sched_range(p, root, r0, r1, self._p(recv), self._p(send), 1)
         return rc, recv, send
+
+    def allgather(self, p, n):
+        q = (p - 1).bit_length()
+        pack = np.zeros((p, n - 1 + q, p), np.int32)
+        unpack = np.zeros((p, n - 1 + q, p), np.int32)
+        for r in range(p):
+            if self.L.orc_allgather_tables(p, n, r, self._p(pack[r]), self._p(unpack[r])):
+                return None, None
+        return pack, unpack
 
     def expand(self, p, n, table):
         q = (p - 1).bit_length()
@@ -165,7 +179,12 @@ def pins_hold(lib):
             for r in range(1, p):
                 if sorted(er[r][er[r] >= 0].tolist()) != list(range(n)):
                     return False
-    except (ScheduleError, AssertionError):
+        for p, n in ((5, 2), (9, 3), (20, 4)):         # the allgather of Alg. 9, replayed for all processes
+            pack, unpack = lib.allgather(p, n)
+            if pack is None:
+                return False
+            simulate_allgather(p, n, pack, unpack)
+    except (ScheduleError, AllgatherError, AssertionError):
         return False
     return True
 
