@@ -124,6 +124,29 @@ int bcs_expand(int32_t p, int32_t n, int32_t r0, int32_t r1,
                const int32_t *recv, const int32_t *send,
                int32_t *recv_blocks, int32_t *send_blocks, void *stream);
 
+/* Index tables of the irregular allgather for ONE process r (Alg. 9, its pack
+ * and unpack loops; Section 2.5): in real round j the process packs, for every
+ * root `root`, block pack_idx[j*p + root] of buffer[root] for its to-neighbour
+ * and unpacks what it receives into block unpack_idx[j*p + root] of
+ * buffer[root].  Towards root `root` the process acts as virtual rank
+ * (r - root + p) mod p of a broadcast rooted at 0, with the dummy-round shift and
+ * clamping of Alg. 6 (Alg. 9 prints only x; the adjustment of the schedules is
+ * taken from Alg. 6).
+ *   pack_idx, unpack_idx: device, R x p int32, R = n-1+q, round-major;
+ *   BCS_NO_BLOCK where nothing moves.  Either may be NULL.
+ * Scratch: bcs_allgather_workspace_bytes(p) bytes (the slot-major receive table
+ * of all ranks); the plain call uses the per-device allocation of bcs_sched*,
+ * the _ws call takes it from the caller (256-byte aligned) and allocates
+ * nothing.  p = 1: R = n-1 entries of BCS_NO_BLOCK.
+ * BCS_EINVAL: p < 1, n < 1, n > BCS_MAX_N, r outside [0, p), both outputs NULL.
+ * BCS_ENOMEM: workspace NULL or too small. */
+int64_t bcs_allgather_workspace_bytes(int32_t p);
+int bcs_allgather_tables(int32_t p, int32_t n, int32_t r,
+                         int32_t *pack_idx, int32_t *unpack_idx, void *stream);
+int bcs_allgather_tables_ws(int32_t p, int32_t n, int32_t r,
+                            int32_t *pack_idx, int32_t *unpack_idx,
+                            void *workspace, size_t workspace_bytes, void *stream);
+
 /* Frees the per-device scratch kept by the plain bcs_sched* calls on the
  * current device (after synchronising that device).  Safe to call anytime. */
 int bcs_release(void);
@@ -136,7 +159,7 @@ int bcs_release(void);
  * 0..BCS_KERNEL_COUNT-1, the summed duration in milliseconds and the number
  * of timed launches into host arrays of BCS_KERNEL_COUNT entries.  Not
  * thread-safe; meant for one measuring thread. */
-#define BCS_KERNEL_COUNT         7
+#define BCS_KERNEL_COUNT         8
 #define BCS_TIMING_MAX_LAUNCHES  4096
 int bcs_timing_begin(void);
 int bcs_timing_end(double *ms_sum_host, int64_t *launches_host);

@@ -24,8 +24,9 @@ SYMBOLS = (
     "bcs_q", "bcs_skips", "bcs_rounds", "bcs_sched", "bcs_sched_rooted", "bcs_sched_workspace_bytes",
     "bcs_sched_rooted_ws", "bcs_sched_batch", "bcs_expand", "bcs_release", "bcs_strerror",
     "bcs_last_hip_error", "bcs_timing_begin", "bcs_timing_end", "bcs_kernel_name", "bcs_valu_peak_launch",
+    "bcs_allgather_workspace_bytes", "bcs_allgather_tables", "bcs_allgather_tables_ws",
 )
-KERNEL_COUNT = 7
+KERNEL_COUNT = 8
 VALU_PEAK_OPS_PER_ITER = 32
 
 _lib = None
@@ -70,6 +71,10 @@ def lib():
     L.bcs_kernel_name.argtypes = [ctypes.c_int]
     L.bcs_kernel_name.restype = ctypes.c_char_p
     L.bcs_valu_peak_launch.argtypes = [ctypes.c_uint32, ctypes.c_uint32, vp, vp]
+    L.bcs_allgather_workspace_bytes.argtypes = [i32]
+    L.bcs_allgather_workspace_bytes.restype = i64
+    L.bcs_allgather_tables.argtypes = [i32, i32, i32, vp, vp, vp]
+    L.bcs_allgather_tables_ws.argtypes = [i32, i32, i32, vp, vp, vp, sz, vp]
     _lib = L
     return L
 
@@ -172,3 +177,19 @@ def bcs_timing_end():
 def bcs_valu_peak_launch(blocks, iters, sink, stream=None):
     """`sink`: int32 device tensor of at least blocks * 256 entries."""
     _check(lib().bcs_valu_peak_launch(blocks, iters, _ptr(sink), _stream(stream)), "bcs_valu_peak_launch")
+
+
+def bcs_allgather_workspace_bytes(p):
+    return _check(lib().bcs_allgather_workspace_bytes(p), "bcs_allgather_workspace_bytes")
+
+
+def bcs_allgather_tables(p, n, r, pack_idx, unpack_idx, stream=None):
+    _check(lib().bcs_allgather_tables(p, n, r, _ptr(pack_idx), _ptr(unpack_idx), _stream(stream)),
+           "bcs_allgather_tables")
+
+
+def bcs_allgather_tables_ws(p, n, r, pack_idx, unpack_idx, workspace, stream=None):
+    wp = ctypes.c_void_p(workspace.data_ptr()) if workspace is not None else None
+    wb = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    _check(lib().bcs_allgather_tables_ws(p, n, r, _ptr(pack_idx), _ptr(unpack_idx), wp, wb, _stream(stream)),
+           "bcs_allgather_tables_ws")

@@ -17,6 +17,7 @@
 namespace {
 
 using namespace bcs;
+typedef int v4i __attribute__((ext_vector_type(4)));
 static_assert(kMaxQ == BCS_MAX_Q, "header and core disagree");
 constexpr int kBlock = 256;              // lanes (= ranks) per workgroup
 
@@ -29,10 +30,10 @@ inline int hip_fail(hipError_t e) {
 
 // Optional per-kernel device timing (bcs_timing_begin / bcs_timing_end): while it is on, a launch is
 // given a start and a stop event from a fixed pool, so its duration is the device's own.
-enum KernelId { kRecv = 0, kSendLookup, kSendRecompute, kBatch, kExpand, kFill, kValuPeak, kKernelCount };
+enum KernelId { kRecv = 0, kSendLookup, kSendRecompute, kBatch, kExpand, kFill, kValuPeak, kAllgather, kKernelCount };
 static_assert(kKernelCount == BCS_KERNEL_COUNT, "header and kernel list disagree");
 const char *const kKernelNames[kKernelCount] = {"k_recv_uniform", "k_send_lookup", "k_send_recompute", "k_batch",
-                                                "k_expand",       "k_fill",        "k_valu_peak"};
+                                                "k_expand",       "k_fill",        "k_valu_peak",   "k_allgather_tables"};
 struct Timing {
     bool on = false;
     int used = 0;
@@ -346,8 +347,6 @@ __device__ __forceinline__ void expand_store(int32_t *__restrict__ out, uint64_t
     }
 }
 
-typedef int v4i __attribute__((ext_vector_type(4)));
-
 // NT: streaming (non-temporal) stores.  Measured on MI355X they win while the schedule reads are a
 // visible share of the traffic (short rows) and lose to plain stores for long rows.
 template <bool NT>
@@ -501,6 +500,140 @@ __global__ __launch_bounds__(kBlock) void k_expand_small(const ExpandArgs a, con
     }
 }
 
+// ----------------------------------------------------------------------------------------------
+// K5: pack / unpack index tables of the irregular allgather for one process r (Alg. 9, its per-round
+// loops over the roots).  For root j the process acts as virtual rank r' = (r - j + p) mod p of a
+// broadcast rooted at 0, so unpack[round][j] is the expanded receive entry of r' and pack[round][j]
+// that of its to-neighbour's receive row: both come from the slot-major receive table recvT[k][rank].
+// All rounds that use slot k differ by a multiple of q only, so a workgroup takes one slot and
+// kAgChunk consecutive roots, reads its 2 x kAgChunk schedule entries once and walks down the rounds
+// k-x, k-x+q, ..., writing one contiguous piece of kAgChunk entries per table and round; lanes are
+// consecutive roots, so every store of a wave is one contiguous 256-byte piece.
+// ----------------------------------------------------------------------------------------------
+constexpr int kAgRootsPerLane = 16;
+constexpr int kAgChunk = kAgRootsPerLane * kBlock;
+
+__global__ __launch_bounds__(kBlock) void k_allgather_tables(const SkipTab tab, int q, uint32_t r, uint32_t x,
+                                                             int32_t nm1, uint64_t R,
+                                                             const int32_t *__restrict__ recvT, uint64_t ldT,
+                                                             int32_t *__restrict__ pack,
+                                                             int32_t *__restrict__ unpack) {
+    const uint32_t p = tab.s[q];
+    const uint32_t k = blockIdx.y;
+    const uint32_t sk = tab.s[k];
+    const int32_t *row = recvT + (uint64_t)k * ldT;
+    const uint64_t first = (uint64_t)blockIdx.x * kAgChunk + threadIdx.x;   // this lane's first root
+    int32_t tu[kAgRootsPerLane], tp[kAgRootsPerLane];                        // entry - k for unpack / pack
+#pragma unroll
+    for (int u = 0; u < kAgRootsPerLane; ++u) {
+        const uint64_t j64 = first + (uint64_t)u * kBlock;
+        const uint32_t j = j64 < p ? (uint32_t)j64 : 0u;
+        const uint32_t vr = r >= j ? r - j : r + p - j;                      // virtual rank of r under root j
+        uint32_t to = vr + sk;
+        to = to >= p ? to - p : to;
+        tu[u] = row[vr] - (int32_t)k;
+        tp[u] = row[to] - (int32_t)k;
+    }
+    // first real round that uses slot k: k - x, or one phase later when that is a dummy round
+    for (uint64_t j = k >= x ? k - x : k + (uint32_t)q - x; j < R; j += (uint32_t)q) {
+        int32_t *up = unpack ? unpack + j * p + first : nullptr;
+        int32_t *pp = pack ? pack + j * p + first : nullptr;
+#pragma unroll
+        for (int u = 0; u < kAgRootsPerLane; ++u) {
+            if (first + (uint64_t)u * kBlock >= p) break;
+            if (up) {
+                const int32_t raw = tu[u] + (int32_t)j;
+                up[u * kBlock] = raw < 0 ? -1 : (raw > nm1 ? nm1 : raw);
+            }
+            if (pp) {
+                const int32_t raw = tp[u] + (int32_t)j;
+                pp[u * kBlock] = raw < 0 ? -1 : (raw > nm1 ? nm1 : raw);
+            }
+        }
+    }
+}
+
+// K5 with 16-byte stores for any p.  Rows of p entries start on every possible 4-byte phase of a
+// 16-byte line, so the schedule entries of the workgroup's roots are staged in LDS and each round
+// reads them back at that round's phase: single entries up to the next 128-byte line, aligned groups
+// of four (a wave stores whole lines), up to three single entries.  Needs 16-byte aligned tables (else the kernel above runs).
+constexpr int kAgVecChunk = 4096;                      // roots per workgroup
+
+__global__ __launch_bounds__(kBlock) void k_allgather_tables_v4(const SkipTab tab, int q, uint32_t r, uint32_t x,
+                                                                int32_t nm1, uint64_t R,
+                                                                const int32_t *__restrict__ recvT, uint64_t ldT,
+                                                                int32_t *__restrict__ pack,
+                                                                int32_t *__restrict__ unpack) {
+    // entry - k for unpack / pack; root i of the chunk sits in plane i % 4 at i / 4, so that lanes reading every
+    // fourth entry hit consecutive words
+    constexpr uint32_t kPlane = kAgVecChunk / 4 + 16;
+    __shared__ int32_t tu[4 * kPlane], tp[4 * kPlane];
+    const uint32_t p = tab.s[q];
+    const uint32_t k = blockIdx.y;
+    const uint32_t sk = tab.s[k];
+    const int32_t *row = recvT + (uint64_t)k * ldT;
+    const uint64_t c0 = (uint64_t)blockIdx.x * kAgVecChunk;       // first root of this workgroup
+    const uint32_t valid = (uint32_t)(((uint64_t)p - c0) < (uint64_t)kAgVecChunk ? ((uint64_t)p - c0)
+                                                                                  : (uint64_t)kAgVecChunk);
+    for (uint32_t i = threadIdx.x; i < valid; i += kBlock) {
+        const uint32_t j = (uint32_t)c0 + i;
+        const uint32_t vr = r >= j ? r - j : r + p - j;           // virtual rank of r under root j
+        uint32_t to = vr + sk;
+        to = to >= p ? to - p : to;
+        const uint32_t w = (i & 3u) * kPlane + (i >> 2);
+        tu[w] = row[vr] - (int32_t)k;
+        tp[w] = row[to] - (int32_t)k;
+    }
+    __syncthreads();
+    const v4i lo = {-1, -1, -1, -1}, hi = {nm1, nm1, nm1, nm1};
+    // first real round that uses slot k: k - x, or one phase later when that is a dummy round
+    for (uint64_t j = k >= x ? k - x : k + (uint32_t)q - x; j < R; j += (uint32_t)q) {
+        const uint64_t flat0 = j * p + c0;
+        // single entries up to the next 128-byte line, so that every wave then stores whole lines
+        uint32_t lead = (32u - (uint32_t)(flat0 & 31u)) & 31u;
+        lead = lead < valid ? lead : valid;
+        const uint32_t groups = (valid - lead) >> 2;
+        const uint32_t tail0 = lead + 4u * groups;                // single entries after the last group
+        const int32_t jj = (int32_t)j;
+        const v4i add = {jj, jj, jj, jj};
+        // entry lead + 4g + c: plane (lead + c) % 4, word g + (lead + c) / 4
+        const uint32_t w0 = ((lead + 0u) & 3u) * kPlane + ((lead + 0u) >> 2), w1 = ((lead + 1u) & 3u) * kPlane + ((lead + 1u) >> 2);
+        const uint32_t w2 = ((lead + 2u) & 3u) * kPlane + ((lead + 2u) >> 2), w3 = ((lead + 3u) & 3u) * kPlane + ((lead + 3u) >> 2);
+        for (uint32_t g = threadIdx.x; g < groups; g += kBlock) {
+            const uint32_t i = lead + 4u * g;
+            if (unpack) {
+                v4i v = {tu[w0 + g], tu[w1 + g], tu[w2 + g], tu[w3 + g]};
+                v += add;
+                v = v > lo ? v : lo;
+                v = v < hi ? v : hi;
+                __builtin_nontemporal_store(v, reinterpret_cast<v4i *>(unpack + flat0 + i));
+            }
+            if (pack) {
+                v4i v = {tp[w0 + g], tp[w1 + g], tp[w2 + g], tp[w3 + g]};
+                v += add;
+                v = v > lo ? v : lo;
+                v = v < hi ? v : hi;
+                __builtin_nontemporal_store(v, reinterpret_cast<v4i *>(pack + flat0 + i));
+            }
+        }
+        // the entries outside the aligned groups: lanes 0..31 at the front, 32..34 at the back
+        const uint32_t t = threadIdx.x;
+        const uint32_t i = t < 32u ? t : tail0 + (t - 32u);
+        const bool mine = t < 32u ? t < lead : (t < 35u && i < valid);
+        if (mine) {
+            const uint32_t w = (i & 3u) * kPlane + (i >> 2);
+            if (unpack) {
+                const int32_t raw = tu[w] + jj;
+                unpack[flat0 + i] = raw < 0 ? -1 : (raw > nm1 ? nm1 : raw);
+            }
+            if (pack) {
+                const int32_t raw = tp[w] + jj;
+                pack[flat0 + i] = raw < 0 ? -1 : (raw > nm1 ? nm1 : raw);
+            }
+        }
+    }
+}
+
 // Measurement aid: the practical ceiling the `alu` roofline is set against.  kValuChains independent chains of
 // full-rate 32-bit integer vector ops of the kinds the construction is made of (add, xor, min, subtract), written
 // as instructions so that the count is exact: `iters` rounds of 4 ops per chain and lane, no memory traffic
@@ -646,9 +779,11 @@ int launch_sched(const SkipTab &tab, uint32_t root, uint32_t r0, uint32_t r1, in
     const uint64_t count = (uint64_t)r1 - r0;
     const unsigned blocks = (unsigned)((count + kBlock - 1) / kBlock);
     const bool full = (r0 == 0 && r1 == tab.s[Q]);
-    if (recv_out || (send_out && full)) {
+    // the slot-major copy feeds the send look-up; with neither table asked for it is the only output
+    const bool want_t = full && recvT && (send_out || !recv_out);
+    if (recv_out || want_t) {
         launch(kRecv, k_recv_uniform<Q>, dim3(blocks), dim3(kBlock), st, tab, root, r0, r1, recv_out,
-                           (send_out && full) ? recvT : (int32_t *)nullptr, ldT);
+               want_t ? recvT : (int32_t *)nullptr, ldT);
     }
     if (send_out) {
         if (full) {
@@ -836,6 +971,62 @@ int bcs_release(void) {
         if (e != hipSuccess) return hip_fail(e);
     }
     return BCS_OK;
+}
+
+int64_t bcs_allgather_workspace_bytes(int32_t p) {
+    if (p < 1) return BCS_EINVAL;
+    return bcs_sched_workspace_bytes(p, 0, p, 1);
+}
+
+int bcs_allgather_tables_ws(int32_t p, int32_t n, int32_t r, int32_t *pack_idx, int32_t *unpack_idx, void *workspace,
+                            size_t workspace_bytes, void *stream) {
+    if (p < 1 || n < 1 || n > BCS_MAX_N || r < 0 || r >= p) return BCS_EINVAL;
+    if (!pack_idx && !unpack_idx) return BCS_EINVAL;
+    const int q = host_q(p);
+    const uint64_t R = (uint64_t)n - 1 + q;
+    if (R == 0) return BCS_OK;
+    hipStream_t st = (hipStream_t)stream;
+    if (q == 0) {                                  // one process: nothing ever moves
+        if (pack_idx) launch(kFill, k_fill, dim3(64), dim3(kBlock), st, pack_idx, R, (int32_t)BCS_NO_BLOCK);
+        if (unpack_idx) launch(kFill, k_fill, dim3(64), dim3(kBlock), st, unpack_idx, R, (int32_t)BCS_NO_BLOCK);
+        hipError_t e0 = hipGetLastError();
+        return e0 == hipSuccess ? BCS_OK : hip_fail(e0);
+    }
+    const int64_t need = bcs_allgather_workspace_bytes(p);
+    if (!workspace || workspace_bytes < (size_t)need) return BCS_ENOMEM;
+    SkipTab tab;
+    host_skips(p, tab);
+    int rc = ensure_lowtab(st);
+    if (rc != BCS_OK) return rc;
+    const uint64_t ld = round_up((uint64_t)p, 64);
+    int32_t *recvT = (int32_t *)workspace;
+    rc = launch_for_q(q)(tab, 0u, 0u, (uint32_t)p, nullptr, nullptr, recvT, ld, st);
+    if (rc != BCS_OK) return rc;
+    const unsigned bx = (unsigned)(((uint64_t)p + kAgChunk - 1) / kAgChunk);
+    const uint32_t x = (uint32_t)((q - (int)(R % (uint64_t)q)) % q);
+    const bool vec = ((((uintptr_t)pack_idx) | ((uintptr_t)unpack_idx)) & 15u) == 0;
+    if (vec) {
+        const unsigned bv = (unsigned)(((uint64_t)p + kAgVecChunk - 1) / kAgVecChunk);
+        launch(kAllgather, k_allgather_tables_v4, dim3(bv, (unsigned)q), dim3(kBlock), st, tab, q, (uint32_t)r, x,
+               (int32_t)(n - 1), R, (const int32_t *)recvT, ld, pack_idx, unpack_idx);
+    } else {
+        launch(kAllgather, k_allgather_tables, dim3(bx, (unsigned)q), dim3(kBlock), st, tab, q, (uint32_t)r, x,
+               (int32_t)(n - 1), R, (const int32_t *)recvT, ld, pack_idx, unpack_idx);
+    }
+    hipError_t e = hipGetLastError();
+    return e == hipSuccess ? BCS_OK : hip_fail(e);
+}
+
+int bcs_allgather_tables(int32_t p, int32_t n, int32_t r, int32_t *pack_idx, int32_t *unpack_idx, void *stream) {
+    if (p < 1 || n < 1 || n > BCS_MAX_N || r < 0 || r >= p) return BCS_EINVAL;
+    if (!pack_idx && !unpack_idx) return BCS_EINVAL;
+    const int64_t need = bcs_allgather_workspace_bytes(p);
+    void *ws = nullptr;
+    if (need > 0) {
+        const int rc = scratch_get((size_t)need, &ws);
+        if (rc != BCS_OK) return rc;
+    }
+    return bcs_allgather_tables_ws(p, n, r, pack_idx, unpack_idx, ws, (size_t)need, stream);
 }
 
 int bcs_valu_peak_launch(uint32_t blocks, uint32_t iters, uint32_t *sink, void *stream) {

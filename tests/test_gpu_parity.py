@@ -239,3 +239,48 @@ def test_batch_edge_rows(bcs, oracle):
     bcs.bcs_sched_batch(*args, recv2, None, None)
     torch.cuda.synchronize()
     assert torch.equal(recv2, recv)
+
+
+def gpu_allgather(bcs, p, n, r, want_pack=True, want_unpack=True, ws=None):
+    R = bcs.bcs_rounds(p, n)
+    pack, unpack = dev_tables(R, p, fill=555)
+    if ws is None:
+        bcs.bcs_allgather_tables(p, n, r, pack if want_pack else None, unpack if want_unpack else None)
+    else:
+        bcs.bcs_allgather_tables_ws(p, n, r, pack if want_pack else None, unpack if want_unpack else None, ws)
+    torch.cuda.synchronize()
+    return pack.cpu().numpy(), unpack.cpu().numpy()
+
+
+def test_allgather_tables_against_oracle(bcs, oracle):
+    """Alg. 9's pack / unpack index tables for one process: ragged p, every kind of n, both outputs and one."""
+    for p, n in [(1, 3), (2, 1), (2, 4), (3, 2), (9, 4), (20, 6), (33, 12), (257, 3), (1000, 37), (1025, 2), (4097, 300),
+                 (65537, 9)]:
+        for r in sorted({0, 1 % p, p // 2, p - 1}):
+            opack, ounpack = oracle.allgather_tables(p, n, r)
+            if opack.size == 0:
+                continue
+            pack, unpack = gpu_allgather(bcs, p, n, r)
+            assert np.array_equal(pack, opack), (p, n, r)
+            assert np.array_equal(unpack, ounpack), (p, n, r)
+        pack, unpack = gpu_allgather(bcs, p, n, p - 1, want_unpack=False)
+        assert np.array_equal(pack, opack) and (unpack == 555).all()
+        ws = torch.empty(bcs.bcs_allgather_workspace_bytes(p) + 256, dtype=torch.uint8, device="cuda")
+        pack, unpack = gpu_allgather(bcs, p, n, p - 1, want_pack=False, ws=ws)
+        assert np.array_equal(unpack, ounpack) and (pack == 555).all()
+
+
+def test_allgather_tables_replayed_for_all_processes(bcs):
+    """The GPU's own tables, one call per process, replayed as a whole allgather."""
+    from allgather_sim import simulate_allgather
+    for p, n in [(5, 2), (20, 4), (33, 7), (64, 3)]:
+        tabs = [gpu_allgather(bcs, p, n, r) for r in range(p)]
+        simulate_allgather(p, n, np.array([t[0] for t in tabs]), np.array([t[1] for t in tabs]))
+
+
+def test_allgather_tables_one_million_processes(bcs, oracle):
+    p, n, r = (1 << 20) + 1, 5, 777777
+    opack, ounpack = oracle.allgather_tables(p, n, r)
+    pack, unpack = gpu_allgather(bcs, p, n, r)
+    assert np.array_equal(pack, opack)
+    assert np.array_equal(unpack, ounpack)
