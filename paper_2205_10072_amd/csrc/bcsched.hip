@@ -742,12 +742,14 @@ struct Scratch {
     size_t bytes = 0;
 };
 Scratch g_scratch[kMaxDevices];
+std::mutex g_scratch_mutex;
 
 int scratch_get(size_t bytes, void **out) {
     int dev = 0;
     hipError_t e = hipGetDevice(&dev);
     if (e != hipSuccess) return hip_fail(e);
     if (dev < 0 || dev >= kMaxDevices) return BCS_EINVAL;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
     Scratch &s = g_scratch[dev];
     if (s.bytes < bytes) {
         if (s.ptr) {
@@ -806,13 +808,12 @@ constexpr void fill_table(LaunchFn *t, std::integer_sequence<int, Qs...>) {
 }
 
 LaunchFn launch_for_q(int q) {
-    static LaunchFn table[kMaxQ] = {};
-    static bool ready = false;
-    if (!ready) {
-        fill_table(table, std::make_integer_sequence<int, kMaxQ>{});
-        ready = true;
-    }
-    return table[q - 1];
+    struct Table {
+        LaunchFn fn[kMaxQ];
+        Table() { fill_table(fn, std::make_integer_sequence<int, kMaxQ>{}); }
+    };
+    static const Table table;                  // initialised once, thread-safe
+    return table.fn[q - 1];
 }
 
 int check_range(int32_t p, int32_t root, int32_t r0, int32_t r1) {
@@ -961,6 +962,7 @@ int bcs_release(void) {
     hipError_t e = hipGetDevice(&dev);
     if (e != hipSuccess) return hip_fail(e);
     if (dev < 0 || dev >= kMaxDevices) return BCS_EINVAL;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
     Scratch &s = g_scratch[dev];
     if (s.ptr) {
         e = hipDeviceSynchronize();
