@@ -88,12 +88,68 @@ def cpu_baseline(budget_s=10.0):
             "single_thread_value": P / single}
 
 
+AG_PROCESS = 777777        # the process whose tables are built in the allgather-tables workload
+
+
+def bench_allgather_tables(torch, bcs, args):
+    """Alg. 9 pack/unpack index tables of one process of a p = 2^20+1 allgather with n = 256 blocks per buffer."""
+    q = bcs.bcs_q(P)
+    R = bcs.bcs_rounds(P, N_BLOCKS)
+    pack = torch.empty((R, P), dtype=torch.int32, device="cuda")
+    unpack = torch.empty((R, P), dtype=torch.int32, device="cuda")
+    ws = torch.empty(bcs.bcs_allgather_workspace_bytes(P), dtype=torch.uint8, device="cuda")
+
+    def step():
+        bcs.bcs_allgather_tables_ws(P, N_BLOCKS, AG_PROCESS, pack, unpack, ws)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    steps = max(1, min(args.steps, 1000))
+    bcs.bcs_timing_begin()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    timing = bcs.bcs_timing_end()
+    ms_per_step = (t1 - t0) * 1e3 / steps
+    ms, cnt = timing["k_allgather_tables"]
+    avg_ms = ms / cnt
+    nbytes = 2 * P * R * 4                                   # both tables, written once
+    out = {
+        "metric": "allgather pack/unpack index tables of one process, GB/s written vs HBM peak",
+        "value": nbytes / (ms_per_step * 1e-3) / 1e9, "unit": "GB/s",
+        "n_gpus": 1, "steps": steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int32", "data": "synthetic",
+        "config": {"workload": "p=2^20+1 processes, n=%d blocks per buffer, process %d: receive schedules of all "
+                               "ranks (slot-major), then 2 tables of %d rounds x p roots" % (N_BLOCKS, AG_PROCESS, R),
+                   "p": P, "q": q, "n": N_BLOCKS, "rounds": R},
+        "roofline": {"kernel": "k_allgather_tables", "bound": "hbm", "achieved": nbytes / avg_ms / 1e6,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": nbytes / avg_ms / 1e6 / HBM_PEAK_GBS,
+                     "traffic": None, "avg_ms": avg_ms},
+        "kernels_ms": {k: v[0] / v[1] for k, v in timing.items()},
+    }
+    if not args.no_cpu_baseline:
+        import oracle
+        t0 = time.perf_counter()
+        oracle.allgather_tables(P, N_BLOCKS, AG_PROCESS)
+        el = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": nbytes / el / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
+                               "sample": "one whole call (full schedule of all ranks, then both tables), %.1f s" % el}
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--workload", choices=["step", "allgather-tables"], default="step",
+                    help="step (default): the hot path this benchmark is about.  allgather-tables: the first widening, "
+                         "Alg. 9's pack/unpack index tables of one process, reported as its own line")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run three plain 1 GiB device copies before the timed region, so that a counter "
                          "profile of this command holds a kernel of known traffic to scale FETCH_SIZE/WRITE_SIZE by")
@@ -107,6 +163,9 @@ def main():
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible")
     torch.cuda.set_device(0)
+    if args.workload == "allgather-tables":
+        print(json.dumps(bench_allgather_tables(torch, bcs, args)))
+        return
     q = bcs.bcs_q(P)
     R = bcs.bcs_rounds(P, N_BLOCKS)
     recv = torch.empty((P, q), dtype=torch.int32, device="cuda")
