@@ -107,6 +107,17 @@ int hc_recv_row_perlane(int32_t p, int32_t v, int last, int wave_q, int32_t *out
     return 0;
 }
 
+// all p receive rows (uniform-p code path), rank-major with q entries a row
+int hc_recv_rows_all(int32_t p, int32_t *out) {
+    if (p < 2) return -1;
+    ready();
+    SkipTab t;
+    fill_skips(p, t);
+    const int q = host_q(p);
+    for (int32_t v = 0; v < p; ++v) g_row[q](t, (uint32_t)v, q - 1, out + (size_t)v * q);
+    return 0;
+}
+
 // mask of baseblocks of ranks a..b (1 <= a, b < p), uniform-p code path
 uint32_t hc_range_blocks(int32_t p, uint32_t a, uint32_t b) {
     ready();

@@ -27,6 +27,7 @@ def load():
         L.hc_recv_row_perlane.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int, ctypes.c_int, i32p]
         L.hc_range_blocks.argtypes = [ctypes.c_int32, ctypes.c_uint32, ctypes.c_uint32]
         L.hc_range_blocks.restype = ctypes.c_uint32
+        L.hc_recv_rows_all.argtypes = [ctypes.c_int32, i32p]
         _lib = L
     return _lib
 
@@ -47,3 +48,10 @@ def recv_row(p, v, last=None, perlane=False, wave_q=None):
 
 def range_blocks(p, a, b):
     return int(load().hc_range_blocks(p, a, b))
+
+
+def recv_rows_all(p):
+    q = (p - 1).bit_length()
+    out = np.zeros((p, q), dtype=np.int32)
+    assert load().hc_recv_rows_all(p, out.ctypes.data_as(ctypes.POINTER(ctypes.c_int32))) == 0
+    return out

@@ -284,3 +284,22 @@ def test_allgather_tables_one_million_processes(bcs, oracle):
     pack, unpack = gpu_allgather(bcs, p, n, r)
     assert np.array_equal(pack, opack)
     assert np.array_equal(unpack, ounpack)
+
+
+def test_bench_step_configuration(bcs, oracle):
+    """The very calls bench.py times (p = 2^20+1, root 0, caller workspace, n = 256), compared in full."""
+    p, n = (1 << 20) + 1, 256
+    q, R = bcs.bcs_q(p), bcs.bcs_rounds(p, n)
+    recv, send = dev_tables(p, q)
+    rb = torch.full((p, R), 4242, dtype=torch.int32, device="cuda")
+    sb = torch.full((p, R), 4242, dtype=torch.int32, device="cuda")
+    ws = torch.empty(bcs.bcs_sched_workspace_bytes(p, 0, p), dtype=torch.uint8, device="cuda")
+    for _ in range(2):                                    # twice: scratch and tables are reused across steps
+        bcs.bcs_sched_rooted_ws(p, 0, 0, p, recv, send, ws)
+        bcs.bcs_expand(p, n, 0, p, recv, send, rb, sb)
+    torch.cuda.synchronize()
+    orecv, osend = oracle.sched_range(p, threads=16)
+    assert np.array_equal(recv.cpu().numpy(), orecv)
+    assert np.array_equal(send.cpu().numpy(), osend)
+    assert np.array_equal(rb.cpu().numpy(), oracle.expand(p, n, orecv, threads=16))
+    assert np.array_equal(sb.cpu().numpy(), oracle.expand(p, n, osend, threads=16))

@@ -84,6 +84,13 @@ def test_lane_code_rows_equal_oracle_small_p(oracle):
             assert (hostcheck.recv_row(p, v)[:q] == recv[v]).all(), (p, v)
 
 
+def test_lane_code_all_rows_every_p_to_3000(oracle):
+    """The digit form's closed expressions are not proved in general: every rank of every p up to 3000."""
+    for p in range(2, 3001):
+        recv, _ = oracle.sched_range(p, want_send=False, threads=4)
+        assert np.array_equal(hostcheck.recv_rows_all(p), recv), p
+
+
 def test_lane_code_rows_equal_oracle_large_p(oracle):
     rng = np.random.default_rng(12)
     ps = [65537, 1048577, 134217727, 2**31 - 1, 2**30, 2**30 + 1, 1500000001] + \
