@@ -52,6 +52,11 @@ def _load():
     lib.orc_sched_batch.argtypes = [ctypes.c_int64, i32p, i32p, i32p, i32p, i32p, i32p, ctypes.c_int]
     lib.orc_expand.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int64, i32p, i32p, ctypes.c_int]
     lib.orc_allgather_tables.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, i32p, i32p]
+    i64p = ctypes.POINTER(ctypes.c_int64)
+    lib.orc_pack_round.argtypes = [ctypes.c_int32, ctypes.c_int32, i32p, i64p, i32p, i32p, ctypes.c_int64, i64p]
+    lib.orc_pack_round.restype = ctypes.c_int64
+    lib.orc_unpack_round.argtypes = [ctypes.c_int32, ctypes.c_int32, i32p, i64p, i32p, i32p, ctypes.c_int64, i64p]
+    lib.orc_unpack_round.restype = ctypes.c_int64
     _lib = lib
     return lib
 
@@ -173,3 +178,36 @@ def allgather_tables(p, n, r):
     unpack = np.zeros((R, p), dtype=np.int32)
     _check(_load().orc_allgather_tables(p, n, r, _ptr(pack), _ptr(unpack)), "allgather_tables")
     return pack, unpack
+
+
+def _ptr64(a):
+    return a.ctypes.data_as(ctypes.POINTER(ctypes.c_int64))
+
+
+def pack_round(n, idx, displs, data):
+    """Alg. 9 'Pack' loop of one round: (message, offsets[p+1])."""
+    idx = np.ascontiguousarray(idx, dtype=np.int32)
+    displs = np.ascontiguousarray(displs, dtype=np.int64)
+    data = np.ascontiguousarray(data, dtype=np.int32)
+    p = idx.shape[0]
+    offsets = np.zeros(p + 1, dtype=np.int64)
+    probe = np.zeros(1, dtype=np.int32)
+    total = _check(_load().orc_pack_round(p, n, _ptr(idx), _ptr64(displs), _ptr(data), _ptr(probe), 0,
+                                          _ptr64(offsets)), "pack_round")
+    packed = np.zeros(max(total, 1), dtype=np.int32)
+    _check(_load().orc_pack_round(p, n, _ptr(idx), _ptr64(displs), _ptr(data), _ptr(packed), total,
+                                  _ptr64(offsets)), "pack_round")
+    return packed[:total], offsets
+
+
+def unpack_round(n, idx, displs, data, packed):
+    """Alg. 9 'Unpack' loop of one round, in place on `data` (int32, contiguous); returns offsets[p+1]."""
+    idx = np.ascontiguousarray(idx, dtype=np.int32)
+    displs = np.ascontiguousarray(displs, dtype=np.int64)
+    packed = np.ascontiguousarray(packed, dtype=np.int32)
+    assert data.dtype == np.int32 and data.flags["C_CONTIGUOUS"]
+    p = idx.shape[0]
+    offsets = np.zeros(p + 1, dtype=np.int64)
+    _check(_load().orc_unpack_round(p, n, _ptr(idx), _ptr64(displs), _ptr(data), _ptr(packed), packed.shape[0],
+                                    _ptr64(offsets)), "unpack_round")
+    return offsets

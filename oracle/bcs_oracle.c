@@ -512,3 +512,53 @@ int orc_allgather_tables(int32_t p, int32_t n, int32_t r, int32_t *pack, int32_t
     free(sendsched);
     return 0;
 }
+
+/* Block b of a buffer of m elements cut into n blocks: elements floor(b*m/n) .. floor((b+1)*m/n) - 1.
+ * Reading: the paper cuts a buffer into "n roughly equal sized blocks" (Section 2) of "the buffer size divided by
+ * n" (Section 2.5) and gives no rule for remainders; this balanced cut covers the buffer exactly with block sizes
+ * that differ by at most one.  m < 2^31 and b <= n < 2^31 keep the product inside 64 bits. */
+static int64_t block_begin(int64_t m, int64_t n, int64_t b) { return (b * m) / n; }
+
+/* Alg. 9, "Pack" loop of one round: for every root j in order, block idx[j] of buffer[j] (nothing when idx[j] < 0)
+ * is appended to the message.  Buffers lie in `data` at element offsets displs[j] .. displs[j+1].
+ * offsets[j] = where root j's block starts in the message, offsets[p] = message length.  Returns that length
+ * (or a negative code); copies nothing beyond `capacity` elements. */
+int64_t orc_pack_round(int32_t p, int32_t n, const int32_t *idx, const int64_t *displs, const int32_t *data,
+                       int32_t *packed, int64_t capacity, int64_t *offsets)
+{
+    if (p < 1 || n < 1) return ORC_EINVAL;
+    int64_t off = 0;
+    for (int32_t j = 0; j < p; j++) {
+        offsets[j] = off;
+        if (idx[j] < 0) continue;
+        if (idx[j] >= n) return ORC_EINVAL;
+        int64_t m = displs[j + 1] - displs[j];
+        int64_t lo = block_begin(m, n, idx[j]), hi = block_begin(m, n, (int64_t)idx[j] + 1);
+        for (int64_t e = lo; e < hi; e++)
+            if (off + (e - lo) < capacity) packed[off + (e - lo)] = data[displs[j] + e];
+        off += hi - lo;
+    }
+    offsets[p] = off;
+    return off;
+}
+
+/* Alg. 9, "Unpack" loop of one round: the message is cut in the same way and each piece stored as block idx[j]
+ * of buffer[j]. */
+int64_t orc_unpack_round(int32_t p, int32_t n, const int32_t *idx, const int64_t *displs, int32_t *data,
+                         const int32_t *packed, int64_t length, int64_t *offsets)
+{
+    if (p < 1 || n < 1) return ORC_EINVAL;
+    int64_t off = 0;
+    for (int32_t j = 0; j < p; j++) {
+        offsets[j] = off;
+        if (idx[j] < 0) continue;
+        if (idx[j] >= n) return ORC_EINVAL;
+        int64_t m = displs[j + 1] - displs[j];
+        int64_t lo = block_begin(m, n, idx[j]), hi = block_begin(m, n, (int64_t)idx[j] + 1);
+        if (off + (hi - lo) > length) return ORC_EINVAL;
+        for (int64_t e = lo; e < hi; e++) data[displs[j] + e] = packed[off + (e - lo)];
+        off += hi - lo;
+    }
+    offsets[p] = off;
+    return off;
+}

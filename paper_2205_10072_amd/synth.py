@@ -44,3 +44,14 @@ def batch_triples(count, seed=BATCH_SEED):
     r = (u[:, 2] % p.astype(np.uint64)).astype(np.int64)
     root = (u[:, 3] % p.astype(np.uint64)).astype(np.int64)
     return p.astype(np.int32), r.astype(np.int32), root.astype(np.int32)
+
+
+def irregular_sizes(p, m):
+    """Buffer sizes of the paper's irregular allgather experiment (Section 3.2): m_r = (r mod 3) * floor(m / p)
+    elements for r < p-1 and the remainder of m for the last process.  Returns (sizes, displs[p+1]) as int64."""
+    sizes = (np.arange(p, dtype=np.int64) % 3) * (m // p)
+    sizes[p - 1] = m - int(sizes[:p - 1].sum())
+    assert sizes[p - 1] >= 0
+    displs = np.zeros(p + 1, dtype=np.int64)
+    np.cumsum(sizes, out=displs[1:])
+    return sizes, displs

@@ -55,3 +55,71 @@ def test_degenerate_sizes(oracle):
     assert pack.shape == (3, 1) and (pack == -1).all() and (unpack == -1).all()
     pack, unpack = oracle.allgather_tables(2, 1, 1)
     assert pack.tolist() == [[-1, 0]] and unpack.tolist() == [[0, -1]]
+
+
+def replay_with_data(oracle, p, n, displs, pack_round, unpack_round, tables):
+    """The whole irregular allgather with real payload: every process packs, 'sends' and unpacks round by round.
+    At the end every process must hold every buffer (the definition of an allgather)."""
+    from bcast_sim import closed_form_skips
+    total = int(displs[-1])
+    truth = (np.arange(total, dtype=np.int64) * 2654435761 % 2147483647).astype(np.int32)
+    data = [np.full(total, -7, dtype=np.int32) for _ in range(p)]
+    for r in range(p):
+        data[r][displs[r]:displs[r + 1]] = truth[displs[r]:displs[r + 1]]
+    q = (p - 1).bit_length()
+    R = n - 1 + q
+    x = (q - R % q) % q
+    skips = closed_form_skips(p)
+    for j in range(R):
+        k = (x + j) % q
+        msgs = [pack_round(n, tables[r][0][j], displs, data[r])[0] for r in range(p)]
+        for r in range(p):
+            t = (r + skips[k]) % p
+            unpack_round(n, tables[t][1][j], displs, data[t], msgs[r])
+    for r in range(p):
+        assert np.array_equal(data[r], truth), "process %d is missing data" % r
+
+
+@pytest.mark.parametrize("p,n,m", [(2, 1, 10), (3, 4, 50), (5, 3, 17), (9, 4, 1000), (12, 7, 333), (20, 5, 4001),
+                                   (33, 6, 5000), (16, 9, 64)])
+def test_irregular_allgather_moves_all_the_data(oracle, p, n, m):
+    from paper_2205_10072_amd import synth
+    sizes, displs = synth.irregular_sizes(p, m)
+    tables = [oracle.allgather_tables(p, n, r) for r in range(p)]
+    replay_with_data(oracle, p, n, displs, oracle.pack_round, oracle.unpack_round, tables)
+
+
+def test_blocks_cut_a_buffer_exactly(oracle):
+    """The n blocks of a buffer are disjoint, in order, cover it and differ in size by at most one."""
+    rng = np.random.default_rng(8)
+    for _ in range(200):
+        n = int(rng.integers(1, 40))
+        m = int(rng.integers(0, 300))
+        displs = np.array([0, m], dtype=np.int64)
+        data = np.arange(m, dtype=np.int32)
+        pieces = [oracle.pack_round(n, [b], displs, data)[0] for b in range(n)]
+        assert np.array_equal(np.concatenate(pieces) if pieces else data, data)
+        sizes = [len(x) for x in pieces]
+        assert max(sizes) - min(sizes) <= 1
+
+
+def test_pack_then_unpack_is_the_identity_on_the_blocks(oracle):
+    rng = np.random.default_rng(9)
+    p, n = 37, 6
+    sizes = rng.integers(0, 50, p).astype(np.int64)
+    displs = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int64)
+    data = rng.integers(0, 1 << 30, int(displs[-1])).astype(np.int32)
+    idx = rng.integers(-1, n, p).astype(np.int32)
+    msg, offsets = oracle.pack_round(n, idx, displs, data)
+    assert offsets[0] == 0 and offsets[-1] == len(msg) and (np.diff(offsets) >= 0).all()
+    blank = np.full_like(data, -1)
+    oracle.unpack_round(n, idx, displs, blank, msg)
+    for j in range(p):
+        m = sizes[j]
+        if idx[j] < 0:
+            assert (blank[displs[j]:displs[j + 1]] == -1).all()
+            continue
+        lo, hi = idx[j] * m // n, (idx[j] + 1) * m // n
+        seg = slice(displs[j] + lo, displs[j] + hi)
+        assert np.array_equal(blank[seg], data[seg])
+        assert np.array_equal(msg[offsets[j]:offsets[j + 1]], data[seg])
