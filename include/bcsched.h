@@ -153,6 +153,36 @@ int bcs_allgather_tables_ws(int32_t p, int32_t n, int32_t r,
                             int32_t *pack_idx, int32_t *unpack_idx,
                             void *workspace, size_t workspace_bytes, void *stream);
 
+/* One round of packing / unpacking for the irregular allgather (Alg. 9, its
+ * "Pack" and "Unpack" loops).  A process keeps the p buffers in one device
+ * array `data` of int32 elements, buffer j at elements displs[j] ..
+ * displs[j+1]-1 (displs: device, p+1 int64, non-decreasing; a buffer has fewer
+ * than 2^31 elements).  A buffer of m elements is cut into n blocks, block b
+ * being elements floor(b*m/n) .. floor((b+1)*m/n)-1 (the paper says "roughly
+ * equal sized" and gives no rule for remainders).
+ *   idx: device, p int32: the block of each buffer that moves in this round
+ *   (a row of the tables of bcs_allgather_tables); negative = none; values
+ *   above n-1 are read as n-1.
+ * bcs_pack_round appends, root by root, block idx[j] of buffer j to the
+ * message `packed` (device, `capacity` elements; what does not fit is not
+ * written).  bcs_unpack_round cuts the message `packed` of `length` elements
+ * the same way and stores the pieces as block idx[j] of buffer j.
+ *   offsets: device, p+1 int64, output of both: where root j's piece starts in
+ *   the message; offsets[p] = length of the whole message (compare it with
+ *   `capacity` / `length` after synchronising).
+ *   workspace: device, 8-byte aligned, bcs_pack_workspace_bytes(p) bytes.
+ * Both calls enqueue four kernels and allocate nothing.
+ * BCS_EINVAL: p < 1, n < 1, a NULL array (`packed` may be NULL when capacity /
+ * length is 0: then only `offsets` is produced), negative capacity / length.
+ * BCS_ENOMEM: workspace NULL, misaligned or too small. */
+int64_t bcs_pack_workspace_bytes(int32_t p);
+int bcs_pack_round(int32_t p, int32_t n, const int32_t *idx, const int64_t *displs,
+                   const int32_t *data, int32_t *packed, int64_t capacity,
+                   int64_t *offsets, void *workspace, size_t workspace_bytes, void *stream);
+int bcs_unpack_round(int32_t p, int32_t n, const int32_t *idx, const int64_t *displs,
+                     int32_t *data, const int32_t *packed, int64_t length,
+                     int64_t *offsets, void *workspace, size_t workspace_bytes, void *stream);
+
 /* Frees the per-device scratch kept by the plain bcs_sched* calls on the
  * current device (after synchronising that device).  Safe to call anytime. */
 int bcs_release(void);
@@ -165,7 +195,7 @@ int bcs_release(void);
  * 0..BCS_KERNEL_COUNT-1, the summed duration in milliseconds and the number
  * of timed launches into host arrays of BCS_KERNEL_COUNT entries.  Not
  * thread-safe; meant for one measuring thread. */
-#define BCS_KERNEL_COUNT         8
+#define BCS_KERNEL_COUNT         10
 #define BCS_TIMING_MAX_LAUNCHES  4096
 int bcs_timing_begin(void);
 int bcs_timing_end(double *ms_sum_host, int64_t *launches_host);

@@ -531,9 +531,9 @@ int64_t orc_pack_round(int32_t p, int32_t n, const int32_t *idx, const int64_t *
     for (int32_t j = 0; j < p; j++) {
         offsets[j] = off;
         if (idx[j] < 0) continue;
-        if (idx[j] >= n) return ORC_EINVAL;
+        int64_t b = idx[j] > n - 1 ? n - 1 : idx[j];      /* caption of Alg. 9: beyond n-1 means n-1 */
         int64_t m = displs[j + 1] - displs[j];
-        int64_t lo = block_begin(m, n, idx[j]), hi = block_begin(m, n, (int64_t)idx[j] + 1);
+        int64_t lo = block_begin(m, n, b), hi = block_begin(m, n, b + 1);
         for (int64_t e = lo; e < hi; e++)
             if (off + (e - lo) < capacity) packed[off + (e - lo)] = data[displs[j] + e];
         off += hi - lo;
@@ -552,9 +552,9 @@ int64_t orc_unpack_round(int32_t p, int32_t n, const int32_t *idx, const int64_t
     for (int32_t j = 0; j < p; j++) {
         offsets[j] = off;
         if (idx[j] < 0) continue;
-        if (idx[j] >= n) return ORC_EINVAL;
+        int64_t b = idx[j] > n - 1 ? n - 1 : idx[j];
         int64_t m = displs[j + 1] - displs[j];
-        int64_t lo = block_begin(m, n, idx[j]), hi = block_begin(m, n, (int64_t)idx[j] + 1);
+        int64_t lo = block_begin(m, n, b), hi = block_begin(m, n, b + 1);
         if (off + (hi - lo) > length) return ORC_EINVAL;
         for (int64_t e = lo; e < hi; e++) data[displs[j] + e] = packed[off + (e - lo)];
         off += hi - lo;

@@ -25,8 +25,9 @@ SYMBOLS = (
     "bcs_sched_rooted_ws", "bcs_sched_batch", "bcs_expand", "bcs_release", "bcs_strerror",
     "bcs_last_hip_error", "bcs_timing_begin", "bcs_timing_end", "bcs_kernel_name", "bcs_valu_peak_launch",
     "bcs_allgather_workspace_bytes", "bcs_allgather_tables", "bcs_allgather_tables_ws",
+    "bcs_pack_workspace_bytes", "bcs_pack_round", "bcs_unpack_round",
 )
-KERNEL_COUNT = 8
+KERNEL_COUNT = 10
 VALU_PEAK_OPS_PER_ITER = 32
 
 _lib = None
@@ -75,6 +76,10 @@ def lib():
     L.bcs_allgather_workspace_bytes.restype = i64
     L.bcs_allgather_tables.argtypes = [i32, i32, i32, vp, vp, vp]
     L.bcs_allgather_tables_ws.argtypes = [i32, i32, i32, vp, vp, vp, sz, vp]
+    L.bcs_pack_workspace_bytes.argtypes = [i32]
+    L.bcs_pack_workspace_bytes.restype = i64
+    L.bcs_pack_round.argtypes = [i32, i32, vp, vp, vp, vp, i64, vp, vp, sz, vp]
+    L.bcs_unpack_round.argtypes = [i32, i32, vp, vp, vp, vp, i64, vp, vp, sz, vp]
     _lib = L
     return L
 
@@ -193,3 +198,32 @@ def bcs_allgather_tables_ws(p, n, r, pack_idx, unpack_idx, workspace, stream=Non
     wb = workspace.numel() * workspace.element_size() if workspace is not None else 0
     _check(lib().bcs_allgather_tables_ws(p, n, r, _ptr(pack_idx), _ptr(unpack_idx), wp, wb, _stream(stream)),
            "bcs_allgather_tables_ws")
+
+
+def _dev(t, dtype):
+    """Device pointer of a contiguous device tensor of the given torch dtype."""
+    import torch
+    if not (isinstance(t, torch.Tensor) and t.is_cuda and t.dtype == dtype and t.is_contiguous()):
+        raise TypeError("expected a contiguous %s tensor in device memory" % dtype)
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def bcs_pack_workspace_bytes(p):
+    return _check(lib().bcs_pack_workspace_bytes(p), "bcs_pack_workspace_bytes")
+
+
+def bcs_pack_round(n, idx, displs, data, packed, offsets, workspace, stream=None):
+    """idx int32[p], displs int64[p+1], data int32, packed int32 (its numel is the capacity), offsets int64[p+1]."""
+    import torch
+    p = idx.numel()
+    _check(lib().bcs_pack_round(p, n, _ptr(idx), _dev(displs, torch.int64), _ptr(data), _ptr(packed), packed.numel(),
+                                _dev(offsets, torch.int64), ctypes.c_void_p(workspace.data_ptr()),
+                                workspace.numel() * workspace.element_size(), _stream(stream)), "bcs_pack_round")
+
+
+def bcs_unpack_round(n, idx, displs, data, packed, length, offsets, workspace, stream=None):
+    import torch
+    p = idx.numel()
+    _check(lib().bcs_unpack_round(p, n, _ptr(idx), _dev(displs, torch.int64), _ptr(data), _ptr(packed), length,
+                                  _dev(offsets, torch.int64), ctypes.c_void_p(workspace.data_ptr()),
+                                  workspace.numel() * workspace.element_size(), _stream(stream)), "bcs_unpack_round")

@@ -30,10 +30,14 @@ inline int hip_fail(hipError_t e) {
 
 // Optional per-kernel device timing (bcs_timing_begin / bcs_timing_end): while it is on, a launch is
 // given a start and a stop event from a fixed pool, so its duration is the device's own.
-enum KernelId { kRecv = 0, kSendLookup, kSendRecompute, kBatch, kExpand, kFill, kValuPeak, kAllgather, kKernelCount };
+enum KernelId {
+    kRecv = 0, kSendLookup, kSendRecompute, kBatch, kExpand, kFill, kValuPeak, kAllgather, kPackPlan, kPackCopy,
+    kKernelCount
+};
 static_assert(kKernelCount == BCS_KERNEL_COUNT, "header and kernel list disagree");
 const char *const kKernelNames[kKernelCount] = {"k_recv_uniform", "k_send_lookup", "k_send_recompute", "k_batch",
-                                                "k_expand",       "k_fill",        "k_valu_peak",   "k_allgather_tables"};
+                                                "k_expand",       "k_fill",        "k_valu_peak",   "k_allgather_tables",
+                                                "k_pack_plan",    "k_pack_copy"};
 struct Timing {
     bool on = false;
     int used = 0;
@@ -634,6 +638,163 @@ __global__ __launch_bounds__(kBlock) void k_allgather_tables_v4(const SkipTab ta
     }
 }
 
+// ----------------------------------------------------------------------------------------------
+// K6: pack / unpack of one round of the irregular allgather (Alg. 9, its "Pack" and "Unpack" loops).
+// The message is the concatenation, root by root, of one block of each buffer; buffers have any
+// sizes (Section 3.2 uses (r mod 3) * floor(m/p)), a buffer of m elements is cut into n blocks at
+// floor(b*m/n).  Three small kernels make the plan -- each root's block length and source offset, an
+// exclusive scan of the lengths (1024 roots per workgroup, then the workgroup totals, then the sum) --
+// and one kernel moves the payload: it walks the MESSAGE in 16-byte pieces (aligned on that side), a
+// lane finds the root of its piece by a search that starts where its previous piece ended, and the
+// buffer side is read or written with whatever alignment the block happens to have.
+// ----------------------------------------------------------------------------------------------
+constexpr int kPlanRoots = 1024;                     // roots per workgroup in the scan (4 per lane)
+
+struct PackPlan {
+    int64_t *offsets;                                // [p+1] message offset of each root's block; [p] = length
+    int64_t *src;                                    // [p]   element offset of that block inside `data`
+    int64_t *totals;                                 // [ceil(p / kPlanRoots) + 1] workgroup totals, then their scan
+};
+
+__global__ __launch_bounds__(kBlock) void k_pack_plan_local(uint32_t p, uint32_t n, const int32_t *__restrict__ idx,
+                                                            const int64_t *__restrict__ displs, PackPlan plan) {
+    __shared__ int64_t wave_sum[kBlock / 64];
+    const uint64_t first = (uint64_t)blockIdx.x * kPlanRoots + threadIdx.x * 4u;
+    int64_t len[4];
+    int64_t mine = 0;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+        const uint64_t j = first + c;
+        len[c] = 0;
+        if (j < p) {
+            const int64_t begin = displs[j], m = displs[j + 1] - begin;
+            int64_t b = idx[j];
+            b = b > (int64_t)n - 1 ? (int64_t)n - 1 : b;             // caption of Alg. 9: beyond n-1 means n-1
+            int64_t lo = 0, hi = 0;
+            if (b >= 0 && m > 0) {
+                lo = (int64_t)(((uint64_t)b * (uint64_t)m) / n);
+                hi = (int64_t)((((uint64_t)b + 1u) * (uint64_t)m) / n);
+            }
+            plan.src[j] = begin + lo;
+            len[c] = hi - lo;
+        }
+        mine += len[c];
+    }
+    // exclusive scan of `mine` over the workgroup: inside a wave by shuffles, across the four waves through LDS
+    int64_t incl = mine;
+    const int lane = threadIdx.x & 63;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const int64_t up = __shfl_up(incl, off, 64);
+        if (lane >= off) incl += up;
+    }
+    if (lane == 63) wave_sum[threadIdx.x >> 6] = incl;
+    __syncthreads();
+    int64_t before = incl - mine;
+    for (int w = 0; w < (int)(threadIdx.x >> 6); ++w) before += wave_sum[w];
+    if (threadIdx.x == kBlock - 1) plan.totals[blockIdx.x] = before + mine;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+        const uint64_t j = first + c;
+        if (j < p) plan.offsets[j] = before;
+        before += len[c];
+    }
+}
+
+// one workgroup: exclusive scan of the workgroup totals in place; the grand total goes to offsets[p]
+__global__ __launch_bounds__(kBlock) void k_pack_plan_totals(uint32_t p, uint32_t groups, PackPlan plan) {
+    __shared__ int64_t wave_sum[kBlock / 64];
+    __shared__ int64_t carry_s;
+    if (threadIdx.x == 0) carry_s = 0;
+    __syncthreads();
+    const int lane = threadIdx.x & 63;
+    for (uint32_t base = 0; base < groups; base += kBlock) {
+        const uint32_t g = base + threadIdx.x;
+        const int64_t mine = g < groups ? plan.totals[g] : 0;
+        int64_t incl = mine;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const int64_t up = __shfl_up(incl, off, 64);
+            if (lane >= off) incl += up;
+        }
+        if (lane == 63) wave_sum[threadIdx.x >> 6] = incl;
+        __syncthreads();
+        int64_t before = carry_s + incl - mine;
+        for (int w = 0; w < (int)(threadIdx.x >> 6); ++w) before += wave_sum[w];
+        if (g < groups) plan.totals[g] = before;
+        __syncthreads();
+        if (threadIdx.x == kBlock - 1) carry_s = before + mine;
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) plan.offsets[p] = carry_s;
+}
+
+__global__ __launch_bounds__(kBlock) void k_pack_plan_finish(uint32_t p, PackPlan plan) {
+    const uint64_t j = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (j < p) plan.offsets[j] += plan.totals[j / kPlanRoots];
+}
+
+constexpr int kCopyIter = 4;                          // 16-byte pieces per lane
+constexpr int kCopyChunk = kCopyIter * kBlock * 4;    // message elements per workgroup
+
+// PACK: data -> message.  !PACK: message -> data.  `limit` = capacity (pack) or message length (unpack).
+template <bool PACK>
+__global__ __launch_bounds__(kBlock) void k_pack_copy(uint32_t p, int64_t limit, const int64_t *__restrict__ offsets,
+                                                      const int64_t *__restrict__ src, int32_t *data,
+                                                      int32_t *message, int msg_aligned) {
+    int64_t end = offsets[p];
+    end = end < limit ? end : limit;
+    int64_t e = (int64_t)blockIdx.x * kCopyChunk + threadIdx.x * 4;
+    if (e >= end) return;
+    // root of this lane's first element: the last j with offsets[j] <= e
+    uint32_t lo = 0, hi = p;                                        // answer in [lo, hi)
+    while (hi - lo > 1u) {
+        const uint32_t mid = lo + ((hi - lo) >> 1);
+        if (offsets[mid] <= e) lo = mid; else hi = mid;
+    }
+    uint32_t j = lo;
+#pragma unroll 1
+    for (int it = 0; it < kCopyIter; ++it, e += (int64_t)kBlock * 4) {
+        if (e >= end) break;
+        // move on to the root that holds element e: gallop, then bisect
+        if (offsets[j + 1] <= e) {
+            uint32_t step = 1, a = j + 1;                           // offsets[a] <= e
+            while (a + step < p && offsets[a + step] <= e) { a += step; step <<= 1; }
+            uint32_t b = a + step < p ? a + step : p;               // offsets[b] > e or b == p
+            while (b - a > 1u) {
+                const uint32_t mid = a + ((b - a) >> 1);
+                if (offsets[mid] <= e) a = mid; else b = mid;
+            }
+            j = a;
+        }
+        const int64_t seg_begin = offsets[j], seg_end = offsets[j + 1];
+        if (e + 4 <= seg_end && e + 4 <= end) {
+            // the whole piece lies in this root's block
+            int32_t *d = data + src[j] + (e - seg_begin);
+            if (PACK) {
+                const v4i v = {d[0], d[1], d[2], d[3]};
+                if (msg_aligned) __builtin_nontemporal_store(v, reinterpret_cast<v4i *>(message + e));
+                else { message[e] = v[0]; message[e + 1] = v[1]; message[e + 2] = v[2]; message[e + 3] = v[3]; }
+            } else {
+                v4i v;
+                if (msg_aligned) v = *reinterpret_cast<const v4i *>(message + e);
+                else v = (v4i){message[e], message[e + 1], message[e + 2], message[e + 3]};
+                d[0] = v[0]; d[1] = v[1]; d[2] = v[2]; d[3] = v[3];
+            }
+        } else {
+            // a piece that crosses into other roots' blocks (or the end): element by element
+            uint32_t jj = j;
+            for (int c = 0; c < 4; ++c) {
+                const int64_t ee = e + c;
+                if (ee >= end) break;
+                while (offsets[jj + 1] <= ee) ++jj;                 // ends: offsets[p] = length > ee
+                int32_t *d = data + src[jj] + (ee - offsets[jj]);
+                if (PACK) message[ee] = *d; else *d = message[ee];
+            }
+        }
+    }
+}
+
 // Measurement aid: the practical ceiling the `alu` roofline is set against.  kValuChains independent chains of
 // full-rate 32-bit integer vector ops of the kinds the construction is made of (add, xor, min, subtract), written
 // as instructions so that the count is exact: `iters` rounds of 4 ops per chain and lane, no memory traffic
@@ -1029,6 +1190,62 @@ int bcs_allgather_tables(int32_t p, int32_t n, int32_t r, int32_t *pack_idx, int
         if (rc != BCS_OK) return rc;
     }
     return bcs_allgather_tables_ws(p, n, r, pack_idx, unpack_idx, ws, (size_t)need, stream);
+}
+
+int64_t bcs_pack_workspace_bytes(int32_t p) {
+    if (p < 1) return BCS_EINVAL;
+    const uint64_t groups = ((uint64_t)p + kPlanRoots - 1) / kPlanRoots;
+    return (int64_t)(((uint64_t)p + groups + 1) * sizeof(int64_t));
+}
+
+namespace {
+int pack_plan(int32_t p, int32_t n, const int32_t *idx, const int64_t *displs, int64_t *offsets, void *workspace,
+              size_t workspace_bytes, hipStream_t st, PackPlan &plan) {
+    if (p < 1 || n < 1 || !idx || !displs || !offsets) return BCS_EINVAL;
+    const int64_t need = bcs_pack_workspace_bytes(p);
+    if (!workspace || workspace_bytes < (size_t)need || (((uintptr_t)workspace) & 7u)) return BCS_ENOMEM;
+    const uint32_t groups = (uint32_t)(((uint64_t)p + kPlanRoots - 1) / kPlanRoots);
+    plan.offsets = offsets;
+    plan.src = (int64_t *)workspace;
+    plan.totals = plan.src + p;
+    launch(kPackPlan, k_pack_plan_local, dim3(groups), dim3(kBlock), st, (uint32_t)p, (uint32_t)n, idx, displs, plan);
+    launch(kPackPlan, k_pack_plan_totals, dim3(1), dim3(kBlock), st, (uint32_t)p, groups, plan);
+    launch(kPackPlan, k_pack_plan_finish, dim3(((unsigned)p + kBlock - 1) / kBlock), dim3(kBlock), st, (uint32_t)p, plan);
+    hipError_t e = hipGetLastError();
+    return e == hipSuccess ? BCS_OK : hip_fail(e);
+}
+}  // namespace
+
+int bcs_pack_round(int32_t p, int32_t n, const int32_t *idx, const int64_t *displs, const int32_t *data,
+                   int32_t *packed, int64_t capacity, int64_t *offsets, void *workspace, size_t workspace_bytes,
+                   void *stream) {
+    if (!data || capacity < 0 || (!packed && capacity > 0)) return BCS_EINVAL;
+    PackPlan plan;
+    const int rc = pack_plan(p, n, idx, displs, offsets, workspace, workspace_bytes, (hipStream_t)stream, plan);
+    if (rc != BCS_OK || capacity == 0) return rc;
+    const uint64_t blocks = ((uint64_t)capacity + kCopyChunk - 1) / kCopyChunk;
+    if (blocks > 0x7fffffffull) return BCS_EINVAL;
+    launch(kPackCopy, k_pack_copy<true>, dim3((unsigned)blocks), dim3(kBlock), (hipStream_t)stream, (uint32_t)p,
+           capacity, (const int64_t *)offsets, (const int64_t *)plan.src, const_cast<int32_t *>(data), packed,
+           (int)((((uintptr_t)packed) & 15u) == 0));
+    hipError_t e = hipGetLastError();
+    return e == hipSuccess ? BCS_OK : hip_fail(e);
+}
+
+int bcs_unpack_round(int32_t p, int32_t n, const int32_t *idx, const int64_t *displs, int32_t *data,
+                     const int32_t *packed, int64_t length, int64_t *offsets, void *workspace, size_t workspace_bytes,
+                     void *stream) {
+    if (!data || length < 0 || (!packed && length > 0)) return BCS_EINVAL;
+    PackPlan plan;
+    const int rc = pack_plan(p, n, idx, displs, offsets, workspace, workspace_bytes, (hipStream_t)stream, plan);
+    if (rc != BCS_OK || length == 0) return rc;
+    const uint64_t blocks = ((uint64_t)length + kCopyChunk - 1) / kCopyChunk;
+    if (blocks > 0x7fffffffull) return BCS_EINVAL;
+    launch(kPackCopy, k_pack_copy<false>, dim3((unsigned)blocks), dim3(kBlock), (hipStream_t)stream, (uint32_t)p,
+           length, (const int64_t *)offsets, (const int64_t *)plan.src, data, const_cast<int32_t *>(packed),
+           (int)((((uintptr_t)packed) & 15u) == 0));
+    hipError_t e = hipGetLastError();
+    return e == hipSuccess ? BCS_OK : hip_fail(e);
 }
 
 int bcs_valu_peak_launch(uint32_t blocks, uint32_t iters, uint32_t *sink, void *stream) {

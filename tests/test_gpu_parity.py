@@ -303,3 +303,101 @@ def test_bench_step_configuration(bcs, oracle):
     assert np.array_equal(send.cpu().numpy(), osend)
     assert np.array_equal(rb.cpu().numpy(), oracle.expand(p, n, orecv, threads=16))
     assert np.array_equal(sb.cpu().numpy(), oracle.expand(p, n, osend, threads=16))
+
+
+def _pack_case(rng, p, n, kind):
+    if kind == "paper":
+        from paper_2205_10072_amd import synth
+        sizes, displs = synth.irregular_sizes(p, int(rng.integers(p, 40 * p)))
+    elif kind == "tiny":
+        sizes = rng.integers(0, 4, p).astype(np.int64)
+        displs = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int64)
+    else:
+        sizes = rng.integers(0, 3000, p).astype(np.int64)
+        sizes[rng.integers(0, p, max(1, p // 3))] = 0
+        displs = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int64)
+    data = rng.integers(0, 1 << 30, max(1, int(displs[-1]))).astype(np.int32)
+    idx = rng.integers(-1, n, p).astype(np.int32)
+    if kind == "tiny":
+        idx[rng.integers(0, p, p // 2)] = -1
+    return displs, data, idx
+
+
+def test_pack_and_unpack_one_round(bcs, oracle):
+    """Alg. 9's pack and unpack loops on irregular buffers: message, offsets and unpacked buffers, bit for bit."""
+    rng = np.random.default_rng(77)
+    for p, n in [(1, 1), (2, 3), (5, 2), (37, 6), (1000, 9), (1025, 4), (5000, 33), (70000, 5)]:
+        for kind in ("paper", "tiny", "mixed"):
+            displs, data, idx = _pack_case(rng, p, n, kind)
+            omsg, ooff = oracle.pack_round(n, idx, displs, data)
+            d_idx = torch.from_numpy(idx).cuda()
+            d_displs = torch.from_numpy(displs).cuda()
+            d_data = torch.from_numpy(data).cuda()
+            cap = len(omsg) + 5
+            d_msg = torch.full((cap,), -99, dtype=torch.int32, device="cuda")
+            d_off = torch.full((p + 1,), -1, dtype=torch.int64, device="cuda")
+            ws = torch.empty(bcs.bcs_pack_workspace_bytes(p), dtype=torch.uint8, device="cuda")
+            bcs.bcs_pack_round(n, d_idx, d_displs, d_data, d_msg, d_off, ws)
+            torch.cuda.synchronize()
+            assert np.array_equal(d_off.cpu().numpy(), ooff), (p, n, kind)
+            got = d_msg.cpu().numpy()
+            assert np.array_equal(got[:len(omsg)], omsg), (p, n, kind)
+            assert (got[len(omsg):] == -99).all()
+            # a message buffer that is too small is filled and not overrun
+            if len(omsg) > 3:
+                small = torch.full((len(omsg) - 3 + 8,), -99, dtype=torch.int32, device="cuda")
+                bcs.bcs_pack_round(n, d_idx, d_displs, d_data, small[:len(omsg) - 3], d_off, ws)
+                torch.cuda.synchronize()
+                s = small.cpu().numpy()
+                assert np.array_equal(s[:len(omsg) - 3], omsg[:-3]) and (s[len(omsg) - 3:] == -99).all()
+                assert int(d_off[p]) == len(omsg)
+            # unpack into blank buffers, from a message at an odd address
+            blank = np.full_like(data, -5)
+            oracle.unpack_round(n, idx, displs, blank, omsg)
+            shifted = torch.empty(len(omsg) + 1, dtype=torch.int32, device="cuda")
+            shifted[1:] = torch.from_numpy(omsg).cuda()
+            d_blank = torch.full((len(data),), -5, dtype=torch.int32, device="cuda")
+            bcs.bcs_unpack_round(n, d_idx, d_displs, d_blank, shifted[1:], len(omsg), d_off, ws)
+            torch.cuda.synchronize()
+            assert np.array_equal(d_blank.cpu().numpy(), blank), (p, n, kind)
+            assert np.array_equal(d_off.cpu().numpy(), ooff)
+
+
+def test_irregular_allgather_on_the_gpu_moves_all_the_data(bcs):
+    """The whole allgather of Alg. 9 with payload, every process simulated on the one GPU with the library's own
+    tables, pack and unpack: at the end every process holds every buffer."""
+    from paper_2205_10072_amd import synth
+    for p, n, m in [(5, 3, 170), (20, 5, 4001), (33, 6, 50000)]:
+        sizes, displs = synth.irregular_sizes(p, m)
+        total = int(displs[-1])
+        truth = (np.arange(total, dtype=np.int64) * 2654435761 % 2147483647).astype(np.int32)
+        q, R = bcs.bcs_q(p), bcs.bcs_rounds(p, n)
+        skips = bcs.bcs_skips(p)
+        x = (q - R % q) % q
+        d_displs = torch.from_numpy(displs).cuda()
+        tabs, data = [], []
+        for r in range(p):
+            pack, unpack = dev_tables(R, p)
+            bcs.bcs_allgather_tables(p, n, r, pack, unpack)
+            tabs.append((pack, unpack))
+            mine = np.full(total, -7, dtype=np.int32)
+            mine[displs[r]:displs[r + 1]] = truth[displs[r]:displs[r + 1]]
+            data.append(torch.from_numpy(mine).cuda())
+        ws = torch.empty(bcs.bcs_pack_workspace_bytes(p), dtype=torch.uint8, device="cuda")
+        off = torch.empty(p + 1, dtype=torch.int64, device="cuda")
+        for j in range(R):
+            k = (x + j) % q
+            msgs, lens = [], []
+            for r in range(p):
+                msg = torch.empty(total // n + p + 8, dtype=torch.int32, device="cuda")
+                bcs.bcs_pack_round(n, tabs[r][0][j], d_displs, data[r], msg, off, ws)
+                torch.cuda.synchronize()
+                lens.append(int(off[p]))
+                assert lens[-1] <= msg.numel()
+                msgs.append(msg)
+            for r in range(p):
+                t = (r + skips[k]) % p
+                bcs.bcs_unpack_round(n, tabs[t][1][j], d_displs, data[t], msgs[r], lens[r], off, ws)
+            torch.cuda.synchronize()
+        for r in range(p):
+            assert np.array_equal(data[r].cpu().numpy(), truth), (p, n, r)
