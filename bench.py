@@ -141,15 +141,103 @@ def bench_allgather_tables(torch, bcs, args):
     return out
 
 
+PACK_P = 1152              # the paper's largest run: 36 nodes x 32 processes
+
+
+def bench_pack_round(torch, bcs, args):
+    """One round of Alg. 9's pack and unpack for process 0 of p = 1152, buffer sizes (r mod 3) * floor(m/p).
+    Large case: m = 2^31 elements (8 GiB of buffers), n = 8 blocks, about 1 GiB moves per round.
+    Paper-shaped case: m = 10^8 elements (400 MB), n = 1658 blocks (the paper's rule with G = 40): 241 KB."""
+    import numpy as np
+    from paper_2205_10072_amd import synth
+
+    def setup(m, n):
+        sizes, displs = synth.irregular_sizes(PACK_P, m)
+        R = bcs.bcs_rounds(PACK_P, n)
+        pack_t = torch.empty((R, PACK_P), dtype=torch.int32, device="cuda")
+        unpack_t = torch.empty((R, PACK_P), dtype=torch.int32, device="cuda")
+        bcs.bcs_allgather_tables(PACK_P, n, 0, pack_t, unpack_t)
+        torch.cuda.synchronize()
+        j = R // 2                                        # a round in the steady state: every root moves a block
+        data = torch.empty(int(displs[-1]), dtype=torch.int32, device="cuda").random_(0, 1 << 30)
+        d_displs = torch.from_numpy(displs).cuda()
+        off = torch.empty(PACK_P + 1, dtype=torch.int64, device="cuda")
+        ws = torch.empty(bcs.bcs_pack_workspace_bytes(PACK_P), dtype=torch.uint8, device="cuda")
+        msg = torch.empty(int(sizes.max()) // n * PACK_P // 2 + 4 * PACK_P + 16, dtype=torch.int32, device="cuda")
+        bcs.bcs_pack_round(n, pack_t[j], d_displs, data, msg, off, ws)
+        torch.cuda.synchronize()
+        length = int(off[PACK_P])
+        assert 0 < length <= msg.numel()
+        return dict(n=n, m=m, displs=displs, d_displs=d_displs, data=data, off=off, ws=ws, msg=msg, length=length,
+                    pack_row=pack_t[j], unpack_row=pack_t[j])
+
+    def run(c, steps, warmup):
+        def step():
+            bcs.bcs_pack_round(c["n"], c["pack_row"], c["d_displs"], c["data"], c["msg"], c["off"], c["ws"])
+            bcs.bcs_unpack_round(c["n"], c["unpack_row"], c["d_displs"], c["data"], c["msg"], c["length"], c["off"],
+                                 c["ws"])
+        for _ in range(warmup):
+            step()
+        torch.cuda.synchronize()
+        bcs.bcs_timing_begin()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            step()
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        timing = bcs.bcs_timing_end()
+        return (t1 - t0) * 1e3 / steps, {k: v[0] / v[1] for k, v in timing.items()}
+
+    steps = max(1, min(args.steps, 500))
+    big = setup(1 << 31, 8)
+    ms_big, k_big = run(big, steps, args.warmup)
+    moved = 2 * 2 * big["length"] * 4                     # pack and unpack, each reads and writes the message once
+    copy_bytes = 2 * big["length"] * 4
+    out = {
+        "metric": "pack + unpack of one allgather round on irregular buffers, GB/s moved vs HBM peak",
+        "value": moved / (ms_big * 1e-3) / 1e9, "unit": "GB/s",
+        "n_gpus": 1, "steps": steps, "warmup": args.warmup, "ms_per_step": ms_big,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int32", "data": "synthetic",
+        "config": {"workload": "p=1152, buffer sizes (r mod 3)*floor(m/p) with m=2^31 int32 elements, n=8 blocks, "
+                               "process 0, a steady-state round: message of %d elements packed, then unpacked"
+                               % big["length"], "p": PACK_P, "m": 1 << 31, "n": 8, "message_elements": big["length"]},
+        "roofline": {"kernel": "k_pack_copy", "bound": "hbm", "achieved": copy_bytes / k_big["k_pack_copy"] / 1e6,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": copy_bytes / k_big["k_pack_copy"] / 1e6 / HBM_PEAK_GBS, "traffic": None,
+                     "avg_ms": k_big["k_pack_copy"]},
+        "kernels_ms": k_big,
+    }
+    del big
+    torch.cuda.empty_cache()
+    small = setup(100000000, 1658)
+    ms_small, k_small = run(small, steps, args.warmup)
+    out["paper_shaped"] = {"m": 100000000, "n": 1658, "message_bytes": small["length"] * 4,
+                           "pack_plus_unpack_us": ms_small * 1e3, "kernels_ms": k_small}
+    if not args.no_cpu_baseline:
+        import oracle
+        c = setup(1 << 28, 8)                             # an eighth of the large case keeps this to seconds
+        h_idx = c["pack_row"].cpu().numpy()
+        h_data = c["data"].cpu().numpy()
+        t0 = time.perf_counter()
+        msg, _ = oracle.pack_round(8, h_idx, c["displs"], h_data)
+        oracle.unpack_round(8, h_idx, c["displs"], h_data, msg)
+        el = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": 2 * 2 * len(msg) * 4 / el / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
+                               "sample": "same round at m=2^28 elements (message of %d elements), %.1f s" % (len(msg), el)}
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--workload", choices=["step", "allgather-tables"], default="step",
+    ap.add_argument("--workload", choices=["step", "allgather-tables", "pack-round"], default="step",
                     help="step (default): the hot path this benchmark is about.  allgather-tables: the first widening, "
-                         "Alg. 9's pack/unpack index tables of one process, reported as its own line")
+                         "Alg. 9's pack/unpack index tables of one process, reported as its own line.  pack-round: the second, "
+                         "packing and unpacking one round's message on irregular buffers")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run three plain 1 GiB device copies before the timed region, so that a counter "
                          "profile of this command holds a kernel of known traffic to scale FETCH_SIZE/WRITE_SIZE by")
@@ -165,6 +253,9 @@ def main():
     torch.cuda.set_device(0)
     if args.workload == "allgather-tables":
         print(json.dumps(bench_allgather_tables(torch, bcs, args)))
+        return
+    if args.workload == "pack-round":
+        print(json.dumps(bench_pack_round(torch, bcs, args)))
         return
     q = bcs.bcs_q(P)
     R = bcs.bcs_rounds(P, N_BLOCKS)
