@@ -183,6 +183,23 @@ int bcs_unpack_round(int32_t p, int32_t n, const int32_t *idx, const int64_t *di
                      int32_t *data, const int32_t *packed, int64_t length,
                      int64_t *offsets, void *workspace, size_t workspace_bytes, void *stream);
 
+/* Plans of the two other collectives the paper runs on the same circulant
+ * graph; host-side, O(q), all arrays are host memory with room for q entries,
+ * the return value is q (or BCS_EINVAL for p < 1, r outside [0, p), NULL).
+ * bcs_allgather_plan (Alg. 7, regular allgather): in round k process r sends
+ * the first count[k] = skips[k+1]-skips[k] blocks of its buffer to to[k] =
+ * (r - skips[k] + p) mod p and receives count[k] blocks from from[k] =
+ * (r + skips[k]) mod p into buffer[recv_first[k] ..], recv_first[k] = skips[k];
+ * buffer[i] ends up holding the block of process (r + i) mod p.
+ * bcs_census_plan (Alg. 8, census / allreduce): in round k process r sends to
+ * to[k] and receives from from[k]; own[k] = 1: it sends x_r + S (partner at
+ * distance skips[k]); own[k] = 0: it sends its partial sum S alone (partner at
+ * distance skips[k] - 1; this is the case skips[k] + skips[k] > skips[k+1]).
+ * After the q rounds S + x_r is the sum over all processes. */
+int bcs_allgather_plan(int32_t p, int32_t r, int32_t *to, int32_t *from,
+                       int32_t *count, int32_t *recv_first);
+int bcs_census_plan(int32_t p, int32_t r, int32_t *to, int32_t *from, int32_t *own);
+
 /* Frees the per-device scratch kept by the plain bcs_sched* calls on the
  * current device (after synchronising that device).  Safe to call anytime. */
 int bcs_release(void);

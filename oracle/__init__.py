@@ -53,6 +53,8 @@ def _load():
     lib.orc_expand.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int64, i32p, i32p, ctypes.c_int]
     lib.orc_allgather_tables.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, i32p, i32p]
     i64p = ctypes.POINTER(ctypes.c_int64)
+    lib.orc_allgather_plan.argtypes = [ctypes.c_int32, ctypes.c_int32, i32p, i32p, i32p, i32p]
+    lib.orc_census_plan.argtypes = [ctypes.c_int32, ctypes.c_int32, i32p, i32p, i32p]
     lib.orc_pack_round.argtypes = [ctypes.c_int32, ctypes.c_int32, i32p, i64p, i32p, i32p, ctypes.c_int64, i64p]
     lib.orc_pack_round.restype = ctypes.c_int64
     lib.orc_unpack_round.argtypes = [ctypes.c_int32, ctypes.c_int32, i32p, i64p, i32p, i32p, ctypes.c_int64, i64p]
@@ -211,3 +213,19 @@ def unpack_round(n, idx, displs, data, packed):
     _check(_load().orc_unpack_round(p, n, _ptr(idx), _ptr64(displs), _ptr(data), _ptr(packed), packed.shape[0],
                                     _ptr64(offsets)), "unpack_round")
     return offsets
+
+
+def allgather_plan(p, r):
+    """Alg. 7: (to, from, count, recv_first), q entries each."""
+    q = q_of(p)
+    a = [np.zeros(max(q, 1), dtype=np.int32) for _ in range(4)]
+    _check(_load().orc_allgather_plan(p, r, *[_ptr(x) for x in a]), "allgather_plan")
+    return [x[:q] for x in a]
+
+
+def census_plan(p, r):
+    """Alg. 8: (to, from, own), q entries each."""
+    q = q_of(p)
+    a = [np.zeros(max(q, 1), dtype=np.int32) for _ in range(3)]
+    _check(_load().orc_census_plan(p, r, *[_ptr(x) for x in a]), "census_plan")
+    return [x[:q] for x in a]

@@ -562,3 +562,43 @@ int64_t orc_unpack_round(int32_t p, int32_t n, const int32_t *idx, const int64_t
     offsets[p] = off;
     return off;
 }
+
+/* Alg. 7 (regular allgather on the circulant graph), the plan of process r: in round k it sends the first
+ * skips[k+1]-skips[k] blocks of its buffer to (r - skips[k] + p) mod p and receives as many from
+ * (r + skips[k]) mod p into buffer[skips[k] ..]; buffer[i] then holds the block of process (r + i) mod p.
+ * Arrays of q entries. */
+int orc_allgather_plan(int32_t p, int32_t r, int32_t *to, int32_t *from, int32_t *count, int32_t *recv_first)
+{
+    int32_t skips[ORC_MAXQ + 2];
+    if (p < 1 || r < 0 || r >= p) return ORC_EINVAL;
+    int q = orc_skips(p, skips);
+    for (int k = 0; k < q; k++) {
+        to[k] = (int32_t)(((int64_t)r - skips[k] + p) % p);
+        from[k] = (int32_t)(((int64_t)r + skips[k]) % p);
+        count[k] = skips[k + 1] - skips[k];
+        recv_first[k] = skips[k];
+    }
+    return q;
+}
+
+/* Alg. 8 (census / allreduce), the plan of process r.  Round k: when skips[k] + skips[k] > skips[k+1] the partner
+ * is one rank closer on both sides and only the partial sum S is sent; otherwise the own value is folded in
+ * (own[k] = 1).  Reading: the condition is printed with index i where the loop variable is k. */
+int orc_census_plan(int32_t p, int32_t r, int32_t *to, int32_t *from, int32_t *own)
+{
+    int32_t skips[ORC_MAXQ + 2];
+    if (p < 1 || r < 0 || r >= p) return ORC_EINVAL;
+    int q = orc_skips(p, skips);
+    for (int k = 0; k < q; k++) {
+        if ((int64_t)skips[k] + skips[k] > skips[k + 1]) {
+            to[k] = (int32_t)(((int64_t)r - skips[k] + 1 + p) % p);
+            from[k] = (int32_t)(((int64_t)r + skips[k] - 1) % p);
+            own[k] = 0;
+        } else {
+            to[k] = (int32_t)(((int64_t)r - skips[k] + p) % p);
+            from[k] = (int32_t)(((int64_t)r + skips[k]) % p);
+            own[k] = 1;
+        }
+    }
+    return q;
+}

@@ -25,7 +25,7 @@ SYMBOLS = (
     "bcs_sched_rooted_ws", "bcs_sched_batch", "bcs_expand", "bcs_release", "bcs_strerror",
     "bcs_last_hip_error", "bcs_timing_begin", "bcs_timing_end", "bcs_kernel_name", "bcs_valu_peak_launch",
     "bcs_allgather_workspace_bytes", "bcs_allgather_tables", "bcs_allgather_tables_ws",
-    "bcs_pack_workspace_bytes", "bcs_pack_round", "bcs_unpack_round",
+    "bcs_pack_workspace_bytes", "bcs_pack_round", "bcs_unpack_round", "bcs_allgather_plan", "bcs_census_plan",
 )
 KERNEL_COUNT = 10
 VALU_PEAK_OPS_PER_ITER = 32
@@ -76,6 +76,8 @@ def lib():
     L.bcs_allgather_workspace_bytes.restype = i64
     L.bcs_allgather_tables.argtypes = [i32, i32, i32, vp, vp, vp]
     L.bcs_allgather_tables_ws.argtypes = [i32, i32, i32, vp, vp, vp, sz, vp]
+    L.bcs_allgather_plan.argtypes = [i32, i32, vp, vp, vp, vp]
+    L.bcs_census_plan.argtypes = [i32, i32, vp, vp, vp]
     L.bcs_pack_workspace_bytes.argtypes = [i32]
     L.bcs_pack_workspace_bytes.restype = i64
     L.bcs_pack_round.argtypes = [i32, i32, vp, vp, vp, vp, i64, vp, vp, sz, vp]
@@ -227,3 +229,20 @@ def bcs_unpack_round(n, idx, displs, data, packed, length, offsets, workspace, s
     _check(lib().bcs_unpack_round(p, n, _ptr(idx), _dev(displs, torch.int64), _ptr(data), _ptr(packed), length,
                                   _dev(offsets, torch.int64), ctypes.c_void_p(workspace.data_ptr()),
                                   workspace.numel() * workspace.element_size(), _stream(stream)), "bcs_unpack_round")
+
+
+def _host_plan(fn, what, p, r, arrays):
+    q = bcs_q(p)
+    bufs = [(ctypes.c_int32 * max(q, 1))() for _ in range(arrays)]
+    _check(fn(p, r, *[ctypes.cast(b, ctypes.c_void_p) for b in bufs]), what)
+    return [list(b)[:q] for b in bufs]
+
+
+def bcs_allgather_plan(p, r):
+    """Alg. 7: lists (to, from, count, recv_first) of q entries."""
+    return _host_plan(lib().bcs_allgather_plan, "bcs_allgather_plan", p, r, 4)
+
+
+def bcs_census_plan(p, r):
+    """Alg. 8: lists (to, from, own) of q entries."""
+    return _host_plan(lib().bcs_census_plan, "bcs_census_plan", p, r, 3)

@@ -1192,6 +1192,36 @@ int bcs_allgather_tables(int32_t p, int32_t n, int32_t r, int32_t *pack_idx, int
     return bcs_allgather_tables_ws(p, n, r, pack_idx, unpack_idx, ws, (size_t)need, stream);
 }
 
+int bcs_allgather_plan(int32_t p, int32_t r, int32_t *to, int32_t *from, int32_t *count, int32_t *recv_first) {
+    if (p < 1 || r < 0 || r >= p || !to || !from || !count || !recv_first) return BCS_EINVAL;
+    SkipTab t;
+    const int q = host_skips(p, t);
+    for (int k = 0; k < q; ++k) {
+        const uint32_t s = t.s[k];
+        to[k] = (int32_t)((uint32_t)r >= s ? (uint32_t)r - s : (uint32_t)r + (uint32_t)p - s);
+        const uint32_t f = (uint32_t)r + s;
+        from[k] = (int32_t)(f >= (uint32_t)p ? f - (uint32_t)p : f);
+        count[k] = (int32_t)(t.s[k + 1] - s);
+        recv_first[k] = (int32_t)s;
+    }
+    return q;
+}
+
+int bcs_census_plan(int32_t p, int32_t r, int32_t *to, int32_t *from, int32_t *own) {
+    if (p < 1 || r < 0 || r >= p || !to || !from || !own) return BCS_EINVAL;
+    SkipTab t;
+    const int q = host_skips(p, t);
+    for (int k = 0; k < q; ++k) {
+        const bool odd = ((t.odd >> k) & 1u) != 0;             // 2 skips[k] - skips[k+1] = 1
+        const uint32_t s = t.s[k] - (odd ? 1u : 0u);            // partner distance
+        to[k] = (int32_t)((uint32_t)r >= s ? (uint32_t)r - s : (uint32_t)r + (uint32_t)p - s);
+        const uint32_t f = (uint32_t)r + s;
+        from[k] = (int32_t)(f >= (uint32_t)p ? f - (uint32_t)p : f);
+        own[k] = odd ? 0 : 1;
+    }
+    return q;
+}
+
 int64_t bcs_pack_workspace_bytes(int32_t p) {
     if (p < 1) return BCS_EINVAL;
     const uint64_t groups = ((uint64_t)p + kPlanRoots - 1) / kPlanRoots;
