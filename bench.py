@@ -141,6 +141,76 @@ def bench_allgather_tables(torch, bcs, args):
     return out
 
 
+def bench_configs(torch, bcs, args):
+    """Per-call device time of the baseline's other configurations (each parity-tested in tests/)."""
+    from paper_2205_10072_amd import synth
+    reps = max(3, min(args.steps, 20))
+
+    def kernels(fn):
+        fn()
+        torch.cuda.synchronize()
+        bcs.bcs_timing_begin()
+        for _ in range(reps):
+            fn()
+        torch.cuda.synchronize()
+        t = bcs.bcs_timing_end()
+        return {k: v[0] / v[1] * (v[1] / reps) for k, v in t.items()}      # ms per call, summed over its launches
+
+    out = {"metric": "per-call device time of the other baseline configurations", "unit": "ms", "n_gpus": 1,
+           "steps": reps, "data": "synthetic", "dtype": "int32", "results": {}}
+    res = out["results"]
+    # C3: p = 2^27 - 1, all ranks, recv + send by look-up
+    p = (1 << 27) - 1
+    q = bcs.bcs_q(p)
+    recv = torch.empty((p, q), dtype=torch.int32, device="cuda")
+    send = torch.empty((p, q), dtype=torch.int32, device="cuda")
+    k = kernels(lambda: bcs.bcs_sched(p, 0, p, recv, send))
+    ms = sum(k.values())
+    res["C3 p=2^27-1 all ranks recv+send"] = {"ms": ms, "kernels_ms": k, "rank_schedules_per_s": p / ms * 1e3,
+                                              "written_GBps": 2 * p * q * 4 / ms / 1e6}
+    # partial range of the same p: send rows by Alg. 5
+    n_part = 1 << 20
+    k = kernels(lambda: bcs.bcs_sched(p, 12345, 12345 + n_part, recv[:n_part], send[:n_part]))
+    ms = sum(k.values())
+    res["p=2^27-1, 2^20 ranks, send by Alg. 5"] = {"ms": ms, "kernels_ms": k, "rank_schedules_per_s": n_part / ms * 1e3}
+    del recv, send
+    bcs.bcs_release()
+    torch.cuda.empty_cache()
+    # C2 partial
+    p = (1 << 20) + 1
+    q = bcs.bcs_q(p)
+    recv = torch.empty((n_part, q), dtype=torch.int32, device="cuda")
+    send = torch.empty((n_part, q), dtype=torch.int32, device="cuda")
+    k = kernels(lambda: bcs.bcs_sched(p, 1, 1 + n_part, recv, send))
+    ms = sum(k.values())
+    res["p=2^20+1, 2^20 ranks, send by Alg. 5"] = {"ms": ms, "kernels_ms": k, "rank_schedules_per_s": n_part / ms * 1e3}
+    # C4: expansion p = 65537, n = 4096
+    p, n = 65537, 4096
+    q, R = bcs.bcs_q(p), bcs.bcs_rounds(p, n)
+    recv = torch.empty((p, q), dtype=torch.int32, device="cuda")
+    send = torch.empty((p, q), dtype=torch.int32, device="cuda")
+    bcs.bcs_sched(p, 0, p, recv, send)
+    rb = torch.empty((p, R), dtype=torch.int32, device="cuda")
+    sb = torch.empty((p, R), dtype=torch.int32, device="cuda")
+    k = kernels(lambda: bcs.bcs_expand(p, n, 0, p, recv, send, rb, sb))
+    ms = sum(k.values())
+    res["C4 expand p=65537 n=4096"] = {"ms": ms, "kernels_ms": k, "written_GBps": 2 * p * R * 4 / ms / 1e6,
+                                      "frac_of_hbm_peak": 2 * p * R * 4 / ms / 1e6 / HBM_PEAK_GBS}
+    del rb, sb
+    # C5: 2^20 seeded triples, mixed q
+    count = 1 << 20
+    pp, rr, ro = (torch.from_numpy(a).cuda() for a in synth.batch_triples(count))
+    brecv = torch.empty((count, 32), dtype=torch.int32, device="cuda")
+    bsend = torch.empty((count, 32), dtype=torch.int32, device="cuda")
+    qv = torch.empty(count, dtype=torch.int32, device="cuda")
+    k = kernels(lambda: bcs.bcs_sched_batch(pp, rr, ro, brecv, bsend, qv))
+    ms = sum(k.values())
+    res["C5 batch 2^20 triples recv+send"] = {"ms": ms, "kernels_ms": k, "rank_schedules_per_s": count / ms * 1e3}
+    k = kernels(lambda: bcs.bcs_sched_batch(pp, rr, ro, brecv, None, qv))
+    res["C5 batch 2^20 triples recv only"] = {"ms": sum(k.values()), "rank_schedules_per_s": count / sum(k.values()) * 1e3}
+    return out
+
+
 PACK_P = 1152              # the paper's largest run: 36 nodes x 32 processes
 
 
@@ -234,10 +304,12 @@ def main():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--workload", choices=["step", "allgather-tables", "pack-round"], default="step",
+    ap.add_argument("--workload", choices=["step", "allgather-tables", "pack-round", "configs"], default="step",
                     help="step (default): the hot path this benchmark is about.  allgather-tables: the first widening, "
                          "Alg. 9's pack/unpack index tables of one process, reported as its own line.  pack-round: the second, "
-                         "packing and unpacking one round's message on irregular buffers")
+                         "packing and unpacking one round's message on irregular buffers.  configs: the other "
+                         "configurations of the baseline (largest p, expansion at p=65537, irregular batch, partial "
+                         "ranges), one line of per-call timings")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run three plain 1 GiB device copies before the timed region, so that a counter "
                          "profile of this command holds a kernel of known traffic to scale FETCH_SIZE/WRITE_SIZE by")
@@ -256,6 +328,9 @@ def main():
         return
     if args.workload == "pack-round":
         print(json.dumps(bench_pack_round(torch, bcs, args)))
+        return
+    if args.workload == "configs":
+        print(json.dumps(bench_configs(torch, bcs, args)))
         return
     q = bcs.bcs_q(P)
     R = bcs.bcs_rounds(P, N_BLOCKS)

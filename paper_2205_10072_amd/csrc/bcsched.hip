@@ -1250,6 +1250,7 @@ int bcs_pack_round(int32_t p, int32_t n, const int32_t *idx, const int64_t *disp
                    int32_t *packed, int64_t capacity, int64_t *offsets, void *workspace, size_t workspace_bytes,
                    void *stream) {
     if (!data || capacity < 0 || (!packed && capacity > 0)) return BCS_EINVAL;
+    if (((uint64_t)capacity + kCopyChunk - 1) / kCopyChunk > 0x7fffffffull) return BCS_EINVAL;
     PackPlan plan;
     const int rc = pack_plan(p, n, idx, displs, offsets, workspace, workspace_bytes, (hipStream_t)stream, plan);
     if (rc != BCS_OK || capacity == 0) return rc;
@@ -1266,6 +1267,7 @@ int bcs_unpack_round(int32_t p, int32_t n, const int32_t *idx, const int64_t *di
                      const int32_t *packed, int64_t length, int64_t *offsets, void *workspace, size_t workspace_bytes,
                      void *stream) {
     if (!data || length < 0 || (!packed && length > 0)) return BCS_EINVAL;
+    if (((uint64_t)length + kCopyChunk - 1) / kCopyChunk > 0x7fffffffull) return BCS_EINVAL;
     PackPlan plan;
     const int rc = pack_plan(p, n, idx, displs, offsets, workspace, workspace_bytes, (hipStream_t)stream, plan);
     if (rc != BCS_OK || length == 0) return rc;
