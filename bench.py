@@ -21,7 +21,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-P = (1 << 20) + 1          # BASELINE config 2: non-power-of-two, q = 21
+P = (1 << 20) + 1          # the headline configuration: non-power-of-two, q = 21
 ROOT_RANK = 0
 N_BLOCKS = 256             # expansion of the same tables; R = 276 rounds, x = 18 dummy rounds
 
@@ -316,7 +316,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU; --gpus %d is not supported (ranks shard trivially "
-                 "over [r0, r1), see DESIGN.md)" % args.gpus)
+                 "over [r0, r1) with no exchange for receive rows)" % args.gpus)
     import torch
     import paper_2205_10072_amd as bcs
     bcs.lib()
