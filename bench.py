@@ -184,6 +184,22 @@ def bench_configs(torch, bcs, args):
     k = kernels(lambda: bcs.bcs_sched(p, 1, 1 + n_part, recv, send))
     ms = sum(k.values())
     res["p=2^20+1, 2^20 ranks, send by Alg. 5"] = {"ms": ms, "kernels_ms": k, "rank_schedules_per_s": n_part / ms * 1e3}
+    # short rows, all four tables of all ranks: one call (fused kernels) against the separate calls
+    n = 64
+    R = bcs.bcs_rounds(p, n)
+    recv = torch.empty((p, q), dtype=torch.int32, device="cuda")
+    send = torch.empty((p, q), dtype=torch.int32, device="cuda")
+    rb = torch.empty((p, R), dtype=torch.int32, device="cuda")
+    sb = torch.empty((p, R), dtype=torch.int32, device="cuda")
+    ws = torch.empty(bcs.bcs_sched_workspace_bytes(p, 0, p), dtype=torch.uint8, device="cuda")
+    k = kernels(lambda: bcs.bcs_sched_expand_ws(p, 0, n, recv, send, rb, sb, ws))
+    ms = sum(k.values())
+    res["p=2^20+1 n=64 schedules+tables, one call"] = {"ms": ms, "kernels_ms": k, "rank_schedules_per_s": p / ms * 1e3}
+    k = kernels(lambda: (bcs.bcs_sched_rooted_ws(p, 0, 0, p, recv, send, ws), bcs.bcs_expand(p, n, 0, p, recv, send, rb, sb)))
+    ms = sum(k.values())
+    res["p=2^20+1 n=64 schedules+tables, separate calls"] = {"ms": ms, "kernels_ms": k,
+                                                             "rank_schedules_per_s": p / ms * 1e3}
+    del rb, sb, ws
     # C4: expansion p = 65537, n = 4096
     p, n = 65537, 4096
     q, R = bcs.bcs_q(p), bcs.bcs_rounds(p, n)

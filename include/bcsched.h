@@ -130,6 +130,28 @@ int bcs_expand(int32_t p, int32_t n, int32_t r0, int32_t r1,
                const int32_t *recv, const int32_t *send,
                int32_t *recv_blocks, int32_t *send_blocks, void *stream);
 
+/* Schedules of all p ranks and both of their (rank, round) -> block tables in
+ * one call: the same results as bcs_sched_rooted_ws(p, root, 0, p, ...) followed
+ * by bcs_expand(p, n, 0, p, ...) (Alg. 4, Alg. 9's send look-up, index arithmetic
+ * of Alg. 6), bit for bit.  For many ranks and moderate n the rows are expanded
+ * by the workgroup that built them, straight from on-chip memory; other sizes
+ * run the two calls above one after the other.
+ *   recv_out, send_out: device, p x q int32 (required when q > 0).
+ *   recv_blocks, send_blocks: device, p x R int32, R = n-1+q (required when
+ *   R > 0; p = 1 with n = 1 has nothing to write and returns BCS_OK).
+ * Scratch: bcs_sched_workspace_bytes(p, 0, p, 1) bytes; the plain call uses the
+ * per-device allocation, the _ws call takes it from the caller and allocates
+ * nothing.  p = 1: both block tables get n-1 columns of BCS_NO_BLOCK.
+ * BCS_EINVAL: p < 1, root outside [0, p), n < 1, n > BCS_MAX_N, a required
+ * table NULL.  BCS_ENOMEM: workspace NULL or too small. */
+int bcs_sched_expand(int32_t p, int32_t root, int32_t n,
+                     int32_t *recv_out, int32_t *send_out,
+                     int32_t *recv_blocks, int32_t *send_blocks, void *stream);
+int bcs_sched_expand_ws(int32_t p, int32_t root, int32_t n,
+                        int32_t *recv_out, int32_t *send_out,
+                        int32_t *recv_blocks, int32_t *send_blocks,
+                        void *workspace, size_t workspace_bytes, void *stream);
+
 /* Index tables of the irregular allgather for ONE process r (Alg. 9, its pack
  * and unpack loops; Section 2.5): in real round j the process packs, for every
  * root `root`, block pack_idx[j*p + root] of buffer[root] for its to-neighbour
@@ -212,7 +234,7 @@ int bcs_release(void);
  * 0..BCS_KERNEL_COUNT-1, the summed duration in milliseconds and the number
  * of timed launches into host arrays of BCS_KERNEL_COUNT entries.  Not
  * thread-safe; meant for one measuring thread. */
-#define BCS_KERNEL_COUNT         10
+#define BCS_KERNEL_COUNT         12
 #define BCS_TIMING_MAX_LAUNCHES  4096
 int bcs_timing_begin(void);
 int bcs_timing_end(double *ms_sum_host, int64_t *launches_host);

@@ -22,12 +22,13 @@ NO_BLOCK = -1
 # every symbol include/bcsched.h declares
 SYMBOLS = (
     "bcs_q", "bcs_skips", "bcs_rounds", "bcs_sched", "bcs_sched_rooted", "bcs_sched_workspace_bytes",
-    "bcs_sched_rooted_ws", "bcs_sched_batch", "bcs_expand", "bcs_release", "bcs_strerror",
+    "bcs_sched_rooted_ws", "bcs_sched_batch", "bcs_expand", "bcs_sched_expand", "bcs_sched_expand_ws",
+    "bcs_release", "bcs_strerror",
     "bcs_last_hip_error", "bcs_timing_begin", "bcs_timing_end", "bcs_kernel_name", "bcs_valu_peak_launch",
     "bcs_allgather_workspace_bytes", "bcs_allgather_tables", "bcs_allgather_tables_ws",
     "bcs_pack_workspace_bytes", "bcs_pack_round", "bcs_unpack_round", "bcs_allgather_plan", "bcs_census_plan",
 )
-KERNEL_COUNT = 10
+KERNEL_COUNT = 12
 VALU_PEAK_OPS_PER_ITER = 32
 
 _lib = None
@@ -63,6 +64,8 @@ def lib():
     L.bcs_sched_rooted_ws.argtypes = [i32, i32, i32, i32, vp, vp, vp, sz, vp]
     L.bcs_sched_batch.argtypes = [i64, vp, vp, vp, vp, vp, vp, vp]
     L.bcs_expand.argtypes = [i32, i32, i32, i32, vp, vp, vp, vp, vp]
+    L.bcs_sched_expand.argtypes = [i32, i32, i32, vp, vp, vp, vp, vp]
+    L.bcs_sched_expand_ws.argtypes = [i32, i32, i32, vp, vp, vp, vp, vp, sz, vp]
     L.bcs_release.argtypes = []
     L.bcs_strerror.argtypes = [ctypes.c_int]
     L.bcs_strerror.restype = ctypes.c_char_p
@@ -162,6 +165,19 @@ def bcs_sched_batch(p, r, root, recv_out, send_out, q_out, stream=None):
 def bcs_expand(p, n, r0, r1, recv, send, recv_blocks, send_blocks, stream=None):
     _check(lib().bcs_expand(p, n, r0, r1, _ptr(recv), _ptr(send), _ptr(recv_blocks), _ptr(send_blocks),
                             _stream(stream)), "bcs_expand")
+
+
+def bcs_sched_expand(p, root, n, recv_out, send_out, recv_blocks, send_blocks, stream=None):
+    _check(lib().bcs_sched_expand(p, root, n, _ptr(recv_out), _ptr(send_out), _ptr(recv_blocks),
+                                  _ptr(send_blocks), _stream(stream)), "bcs_sched_expand")
+
+
+def bcs_sched_expand_ws(p, root, n, recv_out, send_out, recv_blocks, send_blocks, workspace, stream=None):
+    """`workspace`: a device tensor of any dtype (or None when no scratch is needed)."""
+    wp = ctypes.c_void_p(workspace.data_ptr()) if workspace is not None else None
+    wb = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    _check(lib().bcs_sched_expand_ws(p, root, n, _ptr(recv_out), _ptr(send_out), _ptr(recv_blocks),
+                                     _ptr(send_blocks), wp, wb, _stream(stream)), "bcs_sched_expand_ws")
 
 
 def bcs_release():

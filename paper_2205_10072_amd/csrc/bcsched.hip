@@ -32,12 +32,12 @@ inline int hip_fail(hipError_t e) {
 // given a start and a stop event from a fixed pool, so its duration is the device's own.
 enum KernelId {
     kRecv = 0, kSendLookup, kSendRecompute, kBatch, kExpand, kFill, kValuPeak, kAllgather, kPackPlan, kPackCopy,
-    kKernelCount
+    kRecvExpand, kSendExpand, kKernelCount
 };
 static_assert(kKernelCount == BCS_KERNEL_COUNT, "header and kernel list disagree");
 const char *const kKernelNames[kKernelCount] = {"k_recv_uniform", "k_send_lookup", "k_send_recompute", "k_batch",
                                                 "k_expand",       "k_fill",        "k_valu_peak",   "k_allgather_tables",
-                                                "k_pack_plan",    "k_pack_copy"};
+                                                "k_pack_plan",    "k_pack_copy",   "k_recv_expand", "k_send_expand"};
 struct Timing {
     bool on = false;
     int used = 0;
@@ -448,6 +448,155 @@ __global__ __launch_bounds__(kBlock) void k_expand(const ExpandArgs a, const int
         k = k >= q ? k - q : k;
         k = k >= q ? k - q : k;
     }
+}
+
+// ----------------------------------------------------------------------------------------------
+// K1+K4 and K2+K4 fused: a workgroup that has just built (or looked up) the schedule rows of its 256
+// ranks expands them straight from LDS, so the rows are not read back from memory and the integer
+// work of the construction overlaps with the stores of the expansion.  The tile is kept in the
+// mirrored T layout of k_expand (row stride odd, so the lanes' row writes do not collide); the 256
+// rows of a tile are one contiguous piece of the expanded table that starts on a 16-byte boundary.
+// Used for short rows (see use_fused).
+// ----------------------------------------------------------------------------------------------
+template <int Q>
+struct FusedTile {
+    static constexpr int kWidth = (Q + (int)kExpPad) | 1;
+};
+
+// after the rows T[k] = entry - k are in place: add the three mirrors of every row (see k_expand)
+template <int Q>
+__device__ __forceinline__ void tile_mirrors(int32_t *tile, uint32_t x, uint32_t R) {
+    constexpr int W = FusedTile<Q>::kWidth;
+    static_assert(Q >= (int)kExpMinQ, "the mirrored layout needs three slots");
+    int32_t *my = tile + threadIdx.x * W;
+#pragma unroll
+    for (int m = 0; m < 3; ++m) {
+        my[Q + m] = my[m];
+        my[Q + 3 + m] = my[Q - 3 + m];
+    }
+    __syncthreads();
+    if (threadIdx.x + 1 < kBlock) {
+        const int32_t *next = my + W;
+#pragma unroll
+        for (int m = 0; m < 3; ++m) {
+            uint32_t slot = x + m;
+            slot = slot >= (uint32_t)Q ? slot - (uint32_t)Q : slot;
+            my[Q + 6 + m] = next[slot] - (int32_t)R;
+        }
+    }
+    __syncthreads();
+}
+
+// rank-major schedule rows of the tile: entry = T + slot
+template <int Q>
+__device__ __forceinline__ void tile_rows_out(const int32_t *tile, uint32_t rows, int32_t *__restrict__ dst) {
+    constexpr int W = FusedTile<Q>::kWidth;
+    const uint32_t n = rows * Q;
+    for (uint32_t e = threadIdx.x; e < n; e += kBlock) {
+        const uint32_t row = e / Q, col = e - row * Q;
+        dst[e] = tile[row * W + col] + (int32_t)col;
+    }
+}
+
+// the expanded entries of the tile's rows: `rows` x R entries starting at flat index first_row * R
+template <int Q, bool NT>
+__device__ __forceinline__ void tile_expand(const int32_t *tile, uint32_t rows, uint64_t first_row,
+                                            const ExpandArgs &a, int32_t *__restrict__ out) {
+    constexpr uint32_t W = FusedTile<Q>::kWidth;
+    const uint32_t R = a.R;
+    const uint64_t count = (uint64_t)rows * R;
+    int32_t *dst = out + first_row * R;
+    const uint32_t t = threadIdx.x * 4u;
+    uint32_t rd = __umulhi(t, a.magic_R);                             // t < 2^14, R <= kFusedMaxR
+    uint32_t j = t - rd * R;
+    const uint32_t kv = a.x + t + rd * a.wrap_k;                    // congruent to x + j mod q
+    uint32_t k = kv - (uint32_t)Q * __umulhi(kv, a.magic_q);
+    const int32_t lo = -1, hi = a.nm1;
+#pragma unroll 1
+    for (uint64_t e = t; e < count; e += (uint64_t)kBlock * 4u) {
+        const uint32_t left = R - j;
+        const int32_t *wp = tile + rd * W + k + (left < 4u ? 6u : 0u);
+        int32_t v[4];
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const int32_t raw = wp[c] + (int32_t)(j + c);
+            const int32_t m = raw > lo ? raw : lo;
+            v[c] = m < hi ? m : hi;
+        }
+        if (e + 4 <= count) {
+            const v4i pack = {v[0], v[1], v[2], v[3]};
+            if constexpr (NT) __builtin_nontemporal_store(pack, reinterpret_cast<v4i *>(dst + e));
+            else *reinterpret_cast<v4i *>(dst + e) = pack;
+        } else {
+            for (int c = 0; c < 4; ++c)
+                if (e + c < count) dst[e + c] = v[c];
+        }
+        rd += a.step_rows;
+        j += a.step_j;
+        k += a.step_k;
+        if (j >= R) {
+            j -= R;
+            ++rd;
+            k += a.wrap_k;
+        }
+        k = k >= (uint32_t)Q ? k - (uint32_t)Q : k;
+        k = k >= (uint32_t)Q ? k - (uint32_t)Q : k;
+    }
+}
+
+template <int Q>
+__global__ __launch_bounds__(kBlock) void k_recv_expand(const SkipTab tab, uint32_t root, const ExpandArgs ea,
+                                                        int32_t *__restrict__ recv_out, int32_t *__restrict__ recvT,
+                                                        uint64_t ldT, int32_t *__restrict__ blocks_out) {
+    constexpr int W = FusedTile<Q>::kWidth;
+    __shared__ int32_t tile[kBlock * W];
+    __shared__ uint32_t lowtab[kLowShapeBytes / 4];
+    Uniform<Q> pol;
+#pragma unroll
+    for (int k = 0; k <= Q; ++k) pol.S[k] = tab.s[k];
+    pol.tab = &tab;
+    pol.low = reinterpret_cast<const uint8_t *>(lowtab);
+    const uint32_t p = pol.p();
+    stage_lowtab(lowtab, low_shape(p, Q));
+    __syncthreads();
+    const uint64_t first = (uint64_t)blockIdx.x * kBlock;
+    const uint64_t idx = first + threadIdx.x;
+    const bool live = idx < p;
+    const uint32_t r = live ? (uint32_t)idx : root;
+    const uint32_t v = r >= root ? r - root : r + p - root;
+    int32_t *my = tile + threadIdx.x * W;
+    recv_row(pol, v, Q - 1, [&](int i, int val) {
+        my[i] = val - i;
+        if (live) recvT[(uint64_t)i * ldT + idx] = val;
+    });
+    tile_mirrors<Q>(tile, ea.x, ea.R);
+    const uint32_t rows = (uint32_t)(((uint64_t)p - first) < (uint64_t)kBlock ? ((uint64_t)p - first) : (uint64_t)kBlock);
+    tile_rows_out<Q>(tile, rows, recv_out + first * Q);
+    tile_expand<Q, true>(tile, rows, first, ea, blocks_out);
+}
+
+template <int Q>
+__global__ __launch_bounds__(kBlock) void k_send_expand(const SkipTab tab, const ExpandArgs ea,
+                                                        const int32_t *__restrict__ recvT, uint64_t ldT,
+                                                        int32_t *__restrict__ send_out,
+                                                        int32_t *__restrict__ blocks_out) {
+    constexpr int W = FusedTile<Q>::kWidth;
+    __shared__ int32_t tile[kBlock * W];
+    const uint32_t p = tab.s[Q];
+    const uint64_t first = (uint64_t)blockIdx.x * kBlock;
+    const uint64_t idx = first + threadIdx.x;
+    const uint32_t me = idx < p ? (uint32_t)idx : 0u;               // idle lanes replay rank 0
+    int32_t *my = tile + threadIdx.x * W;
+#pragma unroll
+    for (int k = 0; k < Q; ++k) {
+        uint32_t t = me + tab.s[k];
+        t = t >= p ? t - p : t;
+        my[k] = recvT[(uint64_t)k * ldT + t] - k;
+    }
+    tile_mirrors<Q>(tile, ea.x, ea.R);
+    const uint32_t rows = (uint32_t)(((uint64_t)p - first) < (uint64_t)kBlock ? ((uint64_t)p - first) : (uint64_t)kBlock);
+    tile_rows_out<Q>(tile, rows, send_out + first * Q);
+    tile_expand<Q, true>(tile, rows, first, ea, blocks_out);
 }
 
 __global__ __launch_bounds__(kBlock) void k_expand_small(const ExpandArgs a, const int32_t *__restrict__ in,
@@ -977,6 +1126,71 @@ LaunchFn launch_for_q(int q) {
     return table.fn[q - 1];
 }
 
+ExpandArgs expand_args(uint64_t rows, uint64_t R, int q, int32_t n, const void *out) {
+    ExpandArgs ea;
+    ea.total = rows * R;
+    ea.rows = rows;
+    ea.R = (uint32_t)R;
+    ea.q = (uint32_t)q;
+    ea.x = (uint32_t)((q - (int)(R % (uint64_t)q)) % q);
+    ea.nm1 = n - 1;
+    ea.step_rows = (uint32_t)((kBlock * 4u) / R);
+    ea.step_j = (uint32_t)((kBlock * 4u) % R);
+    ea.step_k = ea.step_j % (uint32_t)q;
+    ea.wrap_k = (uint32_t)q - (uint32_t)(R % (uint64_t)q);
+    ea.aligned = (((uintptr_t)out) & 15u) == 0 ? 1 : 0;
+    ea.magic_R = (uint32_t)((1ull << 32) / R + 1ull);
+    ea.magic_q = q >= 2 ? (uint32_t)((1ull << 32) / (uint64_t)q + 1ull) : 0u;
+    ea.magic_w = (uint32_t)((1ull << 32) / (uint64_t)(q + kExpPad) + 1ull);
+    return ea;
+}
+
+// Fused construction + expansion of all ranks (tiles of 256 rows).  Measured on MI355X against the
+// separate kernels for p = 2^12 .. 2^22 and n = 1 .. 1024: 15-40 % less time while rows are short (the
+// schedule rows are a large share of the traffic, and two launches replace four); for longer rows the
+// flat stream of k_expand, whose workgroups are small and many, writes faster than a tile at a time.
+constexpr uint64_t kFusedShortR = 96;              // rows up to this length: fused for any p
+constexpr uint64_t kFusedMaxR = 160;               // rows up to this length: fused when p >= kFusedMinP
+constexpr uint32_t kFusedMinP = 1u << 16;
+
+inline bool use_fused(int32_t p, int q, uint64_t R, bool aligned) {
+    if (q < (int)kExpMinQ || R < kExpMinR || !aligned) return false;
+    return R <= kFusedShortR || (R <= kFusedMaxR && (uint32_t)p >= kFusedMinP);
+}
+
+template <int Q>
+int launch_fused(const SkipTab &tab, uint32_t root, const ExpandArgs &ea, int32_t *recv_out, int32_t *send_out,
+                 int32_t *recvT, uint64_t ldT, int32_t *recv_blocks, int32_t *send_blocks, hipStream_t st) {
+    if constexpr (Q >= (int)kExpMinQ) {
+        const unsigned blocks = (unsigned)(((uint64_t)tab.s[Q] + kBlock - 1) / kBlock);
+        launch(kRecvExpand, k_recv_expand<Q>, dim3(blocks), dim3(kBlock), st, tab, root, ea, recv_out, recvT, ldT,
+               recv_blocks);
+        launch(kSendExpand, k_send_expand<Q>, dim3(blocks), dim3(kBlock), st, tab, ea, (const int32_t *)recvT, ldT,
+               send_out, send_blocks);
+        hipError_t e = hipGetLastError();
+        return e == hipSuccess ? BCS_OK : hip_fail(e);
+    } else {
+        return BCS_EINVAL;
+    }
+}
+
+typedef int (*FusedFn)(const SkipTab &, uint32_t, const ExpandArgs &, int32_t *, int32_t *, int32_t *, uint64_t,
+                       int32_t *, int32_t *, hipStream_t);
+
+template <int... Qs>
+constexpr void fill_fused(FusedFn *t, std::integer_sequence<int, Qs...>) {
+    ((t[Qs] = &launch_fused<Qs + 1>), ...);
+}
+
+FusedFn fused_for_q(int q) {
+    struct Table {
+        FusedFn fn[kMaxQ];
+        Table() { fill_fused(fn, std::make_integer_sequence<int, kMaxQ>{}); }
+    };
+    static const Table table;
+    return table.fn[q - 1];
+}
+
 int check_range(int32_t p, int32_t root, int32_t r0, int32_t r1) {
     if (p < 1 || root < 0 || root >= p || r0 < 0 || r0 > r1 || r1 > p) return BCS_EINVAL;
     return BCS_OK;
@@ -1083,21 +1297,7 @@ int bcs_expand(int32_t p, int32_t n, int32_t r0, int32_t r1, const int32_t *recv
             launch(kFill, k_fill, dim3(1024), dim3(kBlock), st, outs[t], rows * R, (int32_t)BCS_NO_BLOCK);
             continue;
         }
-        ExpandArgs ea;
-        ea.total = rows * R;
-        ea.rows = rows;
-        ea.R = (uint32_t)R;
-        ea.q = (uint32_t)q;
-        ea.x = (uint32_t)((q - (int)(R % (uint64_t)q)) % q);
-        ea.nm1 = n - 1;
-        ea.step_rows = (uint32_t)((kBlock * 4u) / R);
-        ea.step_j = (uint32_t)((kBlock * 4u) % R);
-        ea.step_k = ea.step_j % (uint32_t)q;
-        ea.wrap_k = (uint32_t)q - (uint32_t)(R % (uint64_t)q);
-        ea.aligned = (((uintptr_t)outs[t]) & 15u) == 0 ? 1 : 0;
-        ea.magic_R = (uint32_t)((1ull << 32) / R + 1ull);
-        ea.magic_q = q >= 2 ? (uint32_t)((1ull << 32) / (uint64_t)q + 1ull) : 0u;
-        ea.magic_w = (uint32_t)((1ull << 32) / (uint64_t)(q + kExpPad) + 1ull);
+        const ExpandArgs ea = expand_args(rows, R, q, n, outs[t]);
         const uint64_t blocks = (ea.total + kExpChunk - 1) / kExpChunk;
         if (blocks > 0x7fffffffull) return BCS_EINVAL;
         if (R >= kExpMinR && (uint32_t)q >= kExpMinQ) {
@@ -1116,6 +1316,46 @@ int bcs_expand(int32_t p, int32_t n, int32_t r0, int32_t r1, const int32_t *recv
     }
     hipError_t e = hipGetLastError();
     return e == hipSuccess ? BCS_OK : hip_fail(e);
+}
+
+int bcs_sched_expand_ws(int32_t p, int32_t root, int32_t n, int32_t *recv_out, int32_t *send_out,
+                        int32_t *recv_blocks, int32_t *send_blocks, void *workspace, size_t workspace_bytes,
+                        void *stream) {
+    if (p < 1 || root < 0 || root >= p || n < 1 || n > BCS_MAX_N) return BCS_EINVAL;
+    const int q = host_q(p);
+    const uint64_t R = (uint64_t)n - 1 + q;
+    if (R == 0) return BCS_OK;                     // one process, one block: every table is empty
+    if (!recv_blocks || !send_blocks) return BCS_EINVAL;
+    if (q > 0 && (!recv_out || !send_out)) return BCS_EINVAL;
+    const bool aligned = ((((uintptr_t)recv_blocks) | ((uintptr_t)send_blocks)) & 15u) == 0;
+    if (!use_fused(p, q, R, aligned)) {
+        if (q > 0) {
+            const int rc = bcs_sched_rooted_ws(p, root, 0, p, recv_out, send_out, workspace, workspace_bytes, stream);
+            if (rc != BCS_OK) return rc;
+        }
+        return bcs_expand(p, n, 0, p, recv_out, send_out, recv_blocks, send_blocks, stream);
+    }
+    const int64_t need = bcs_sched_workspace_bytes(p, 0, p, 1);
+    if (!workspace || workspace_bytes < (size_t)need) return BCS_ENOMEM;
+    SkipTab tab;
+    host_skips(p, tab);
+    const int rc = ensure_lowtab((hipStream_t)stream);
+    if (rc != BCS_OK) return rc;
+    const ExpandArgs ea = expand_args((uint64_t)p, R, q, n, recv_blocks);
+    return fused_for_q(q)(tab, (uint32_t)root, ea, recv_out, send_out, (int32_t *)workspace,
+                          round_up((uint64_t)p, 64), recv_blocks, send_blocks, (hipStream_t)stream);
+}
+
+int bcs_sched_expand(int32_t p, int32_t root, int32_t n, int32_t *recv_out, int32_t *send_out, int32_t *recv_blocks,
+                     int32_t *send_blocks, void *stream) {
+    if (p < 1) return BCS_EINVAL;
+    const int64_t need = bcs_sched_workspace_bytes(p, 0, p, 1);
+    void *ws = nullptr;
+    if (need > 0) {
+        const int rc = scratch_get((size_t)need, &ws);
+        if (rc != BCS_OK) return rc;
+    }
+    return bcs_sched_expand_ws(p, root, n, recv_out, send_out, recv_blocks, send_blocks, ws, (size_t)need, stream);
 }
 
 int bcs_release(void) {

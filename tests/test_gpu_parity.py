@@ -305,6 +305,61 @@ def test_bench_step_configuration(bcs, oracle):
     assert np.array_equal(sb.cpu().numpy(), oracle.expand(p, n, osend, threads=16))
 
 
+def _sched_expand_case(bcs, oracle, p, n, root, own_ws=False, misalign=False):
+    q, R = bcs.bcs_q(p), bcs.bcs_rounds(p, n)
+    recv, send = dev_tables(p, max(q, 1))
+    recv, send = recv[:, :q].contiguous(), send[:, :q].contiguous()
+    flat = [torch.full((p * R + 4,), 4242, dtype=torch.int32, device="cuda") for _ in range(2)]
+    off = 1 if misalign else 0                          # one int32 off a 16-byte boundary
+    rb, sb = (t[off:off + p * R].view(p, R) for t in flat)
+    args = (p, root, n, recv if q else None, send if q else None, rb, sb)
+    if own_ws:
+        ws = torch.empty(max(1, bcs.bcs_sched_workspace_bytes(p, 0, p)), dtype=torch.uint8, device="cuda")
+        bcs.bcs_sched_expand_ws(*args, ws)
+    else:
+        bcs.bcs_sched_expand(*args)
+    torch.cuda.synchronize()
+    orecv, osend = oracle.sched_range(p, root, 0, p, threads=16)
+    tag = (p, n, root)
+    if q:
+        assert np.array_equal(recv.cpu().numpy(), orecv), tag
+        assert np.array_equal(send.cpu().numpy(), osend), tag
+    if R:
+        assert np.array_equal(rb.cpu().numpy(), oracle.expand(p, n, orecv, threads=16)), tag
+        assert np.array_equal(sb.cpu().numpy(), oracle.expand(p, n, osend, threads=16)), tag
+    for t in flat:                                      # nothing written outside the tables
+        assert int(t[off + p * R:].min()) == 4242 and int(t[:off].sum()) == 4242 * off, tag
+
+
+def test_sched_expand_one_call(bcs, oracle):
+    """bcs_sched_expand: schedules and both block tables of all ranks in one call.  Short rows are expanded by
+    the workgroup that built them (every q from 3 to 23 here; larger q would need more than 2^23 ranks at
+    once), other sizes take the separate kernels; both are compared in full with the oracle."""
+    rng = np.random.default_rng(2205)
+    for q in range(3, 22):                              # fused: R = n-1+q <= 96
+        p = (1 << (q - 1)) + 1 + int(rng.integers(0, 1 << (q - 1)))
+        _sched_expand_case(bcs, oracle, p, int(rng.integers(max(1, 17 - q), 60)), int(rng.integers(0, p)),
+                           own_ws=bool(q & 1))
+    _sched_expand_case(bcs, oracle, (1 << 21) + 77, 3, 5)               # q = 22
+    _sched_expand_case(bcs, oracle, (1 << 22) + 1, 1, (1 << 22), own_ws=True)   # q = 23, n = 1
+    for p, n, root in [(5, 14, 4), (255, 89, 0), (256, 89, 255), (257, 88, 1), (511, 9, 77), (513, 87, 512),
+                       (1000, 37, 123), (65536, 145, 9), (70001, 130, 70000), (65535, 81, 3)]:
+        _sched_expand_case(bcs, oracle, p, n, root)     # fused, tiles with ragged tails, both length classes
+    for p, n, root in [(1, 1, 0), (1, 9, 0), (2, 40, 1), (3, 20, 2), (4, 33, 0), (9, 3, 8), (1000, 5, 1),
+                       (1000, 200, 999), (4097, 100, 5), (65535, 145, 9), (70000, 1000, 7)]:
+        _sched_expand_case(bcs, oracle, p, n, root, own_ws=(p % 2 == 0))    # the separate kernels
+    _sched_expand_case(bcs, oracle, 1000, 37, 123, misalign=True)
+    _sched_expand_case(bcs, oracle, 70001, 130, 1, own_ws=True, misalign=True)
+    with pytest.raises(bcs.BcsError):
+        bcs.bcs_sched_expand(1000, 1000, 5, *dev_tables(1000, 10), *dev_tables(1000, 14))
+    with pytest.raises(bcs.BcsError):
+        bcs.bcs_sched_expand(1000, 0, 5, None, None, *dev_tables(1000, 14))
+    with pytest.raises(bcs.BcsError):                   # caller workspace too small
+        r, s = dev_tables(1000, 10)
+        rb, sb = dev_tables(1000, 46)
+        bcs.bcs_sched_expand_ws(1000, 0, 37, r, s, rb, sb, torch.empty(64, dtype=torch.uint8, device="cuda"))
+
+
 def _pack_case(rng, p, n, kind):
     if kind == "paper":
         from paper_2205_10072_amd import synth
