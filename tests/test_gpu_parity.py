@@ -136,9 +136,10 @@ def test_largest_p_sampled_chunks(bcs, oracle):
             assert np.array_equal(send, osend), (p, r0)
 
 
-def test_largest_p_all_ranks_sampled_rows(bcs, oracle):
-    """Config 3 in the all-ranks launch configuration (send by look-up): rows sampled against the oracle,
-    every row checked for the structure any size must have."""
+def test_largest_p_all_ranks_in_full(bcs, oracle):
+    """Config 3 in the all-ranks launch configuration (send by look-up), compared in full: every receive row
+    against the oracle, chunk by chunk, and every send entry against its definition
+    send[r][k] = recv[(r + skips[k]) mod p][k] (Alg. 9's look-up; Alg. 5) on the verified receive table."""
     p = 134217727
     q = 27
     recv = torch.empty((p, q), dtype=torch.int32, device="cuda")
@@ -153,19 +154,48 @@ def test_largest_p_all_ranks_sampled_rows(bcs, oracle):
     assert bool((rowsum[1:] == -(q * (q - 1)) // 2).all())
     assert int(rowsum[0]) == -(q * (q + 1)) // 2
     del nonneg, rowsum
-    rng = np.random.default_rng(21)
-    starts = [0, p - 4096] + [int(v) for v in rng.integers(0, p - 4096, 6)]
-    for r0 in starts:
-        orecv, _ = oracle.sched_range(p, r0=r0, r1=r0 + 4096, want_send=False, threads=16)
-        assert np.array_equal(recv[r0:r0 + 4096].cpu().numpy(), orecv), r0
+    chunk = 1 << 24
+    for r0 in range(0, p, chunk):
+        r1 = min(p, r0 + chunk)
+        orecv, _ = oracle.sched_range(p, r0=r0, r1=r1, want_send=False, threads=16)
+        assert np.array_equal(recv[r0:r1].cpu().numpy(), orecv), r0
+        del orecv
     skips = bcs.bcs_skips(p)
-    rows = torch.from_numpy(rng.integers(0, p, 200000)).cuda()
-    for k in range(q):                       # the look-up itself, against the GPU's own receive table
-        t = (rows + skips[k]) % p
-        assert bool((send[rows, k] == recv[t, k]).all()), k
+    for k in range(q):
+        assert torch.equal(send[:, k], torch.roll(recv[:, k], -int(skips[k]))), k
+    rng = np.random.default_rng(21)                      # and a few send chunks by the oracle's Alg. 5
+    for r0 in [0, p - 2048] + [int(v) for v in rng.integers(0, p - 2048, 2)]:
+        _, osend = oracle.sched_range(p, r0=r0, r1=r0 + 2048, threads=16)
+        assert np.array_equal(send[r0:r0 + 2048].cpu().numpy(), osend), r0
     del recv, send
     bcs.bcs_release()
     torch.cuda.empty_cache()
+
+
+def test_largest_p_whole_table_replayed(bcs):
+    """Config 3 without the oracle: the tables the GPU builds for all 2^27 - 1 ranks are played round by round
+    (tests/bcast_sim_torch.py, on the device) and must broadcast n = 1, 2, 3 and q + 2 blocks correctly in
+    n - 1 + q rounds.  The same for p = 2^20 + 1 under another root."""
+    import bcast_sim_torch
+    p, q = 134217727, 27
+    recv = torch.empty((p, q), dtype=torch.int32, device="cuda")
+    send = torch.empty((p, q), dtype=torch.int32, device="cuda")
+    bcs.bcs_sched(p, 0, p, recv, send)
+    torch.cuda.synchronize()
+    for n in (1, 2, 3, q + 2):
+        assert bcast_sim_torch.simulate(p, n, recv, send) == n - 1 + q
+    del recv, send
+    bcs.bcs_release()
+    torch.cuda.empty_cache()
+    p, root = (1 << 20) + 1, 777777
+    q = bcs.bcs_q(p)
+    recv, send = dev_tables(p, q)
+    bcs.bcs_sched_rooted(p, root, 0, p, recv, send)
+    torch.cuda.synchronize()
+    # a schedule rooted at `root` is the root-0 schedule of the ranks renumbered from the root
+    recv0, send0 = torch.roll(recv, -root, 0), torch.roll(send, -root, 0)
+    for n in (1, 5, 64):
+        assert bcast_sim_torch.simulate(p, n, recv0, send0) == n - 1 + q
 
 
 def test_expand_p65537_n4096(bcs, oracle):
