@@ -887,24 +887,43 @@ constexpr int kCopyIter = 4;                          // 16-byte pieces per lane
 constexpr int kCopyChunk = kCopyIter * kBlock * 4;    // message elements per workgroup
 
 // PACK: data -> message.  !PACK: message -> data.  `limit` = capacity (pack) or message length (unpack).
+// A wave first finds the root of its first element together (64 probes of `offsets` per step), each lane then
+// walks on from there; the roots of a lane's kCopyIter pieces are all found before any payload is touched, so
+// that the payload loads of the pieces are in flight together.
 template <bool PACK>
 __global__ __launch_bounds__(kBlock) void k_pack_copy(uint32_t p, int64_t limit, const int64_t *__restrict__ offsets,
                                                       const int64_t *__restrict__ src, int32_t *data,
                                                       int32_t *message, int msg_aligned) {
     int64_t end = offsets[p];
     end = end < limit ? end : limit;
-    int64_t e = (int64_t)blockIdx.x * kCopyChunk + threadIdx.x * 4;
-    if (e >= end) return;
-    // root of this lane's first element: the last j with offsets[j] <= e
-    uint32_t lo = 0, hi = p;                                        // answer in [lo, hi)
+    const int64_t e0 = (int64_t)blockIdx.x * kCopyChunk + threadIdx.x * 4;
+    const int64_t e_wave = (int64_t)blockIdx.x * kCopyChunk + (threadIdx.x & ~63u) * 4;
+    if (e_wave >= end) return;                                      // the whole wave leaves together
+    // root of the wave's first element: the last j with offsets[j] <= e_wave, answer in [lo, hi)
+    uint32_t lo = 0, hi = p;
+    const uint32_t lane = threadIdx.x & 63u;
     while (hi - lo > 1u) {
-        const uint32_t mid = lo + ((hi - lo) >> 1);
-        if (offsets[mid] <= e) lo = mid; else hi = mid;
+        const uint32_t step = (hi - lo + 63u) >> 6;
+        const uint64_t probe = (uint64_t)lo + (uint64_t)(lane + 1u) * step;
+        const bool below = probe < hi && offsets[probe] <= e_wave;  // true for a prefix of the lanes
+        const uint32_t c = (uint32_t)__popcll(__ballot(below));
+        const uint64_t nlo = (uint64_t)lo + (uint64_t)c * step;
+        const uint64_t nhi = nlo + step;
+        lo = (uint32_t)nlo;
+        hi = nhi < hi ? (uint32_t)nhi : hi;
     }
     uint32_t j = lo;
-#pragma unroll 1
-    for (int it = 0; it < kCopyIter; ++it, e += (int64_t)kBlock * 4) {
-        if (e >= end) break;
+    // the pieces of this lane: 0 = none, 1 = whole piece inside one root's block, 2 = crosses a boundary
+    int kind[kCopyIter];
+    int32_t *inner[kCopyIter];
+    uint32_t first_root[kCopyIter];
+#pragma unroll
+    for (int it = 0; it < kCopyIter; ++it) {
+        const int64_t e = e0 + (int64_t)it * kBlock * 4;
+        kind[it] = 0;
+        inner[it] = data;
+        first_root[it] = j;
+        if (e >= end) continue;
         // move on to the root that holds element e: gallop, then bisect
         if (offsets[j + 1] <= e) {
             uint32_t step = 1, a = j + 1;                           // offsets[a] <= e
@@ -917,29 +936,53 @@ __global__ __launch_bounds__(kBlock) void k_pack_copy(uint32_t p, int64_t limit,
             j = a;
         }
         const int64_t seg_begin = offsets[j], seg_end = offsets[j + 1];
+        first_root[it] = j;
         if (e + 4 <= seg_end && e + 4 <= end) {
-            // the whole piece lies in this root's block
-            int32_t *d = data + src[j] + (e - seg_begin);
-            if (PACK) {
-                const v4i v = {d[0], d[1], d[2], d[3]};
-                if (msg_aligned) __builtin_nontemporal_store(v, reinterpret_cast<v4i *>(message + e));
-                else { message[e] = v[0]; message[e + 1] = v[1]; message[e + 2] = v[2]; message[e + 3] = v[3]; }
-            } else {
-                v4i v;
-                if (msg_aligned) v = *reinterpret_cast<const v4i *>(message + e);
-                else v = (v4i){message[e], message[e + 1], message[e + 2], message[e + 3]};
-                d[0] = v[0]; d[1] = v[1]; d[2] = v[2]; d[3] = v[3];
-            }
+            kind[it] = 1;
+            inner[it] = data + src[j] + (e - seg_begin);
         } else {
-            // a piece that crosses into other roots' blocks (or the end): element by element
-            uint32_t jj = j;
-            for (int c = 0; c < 4; ++c) {
-                const int64_t ee = e + c;
-                if (ee >= end) break;
-                while (offsets[jj + 1] <= ee) ++jj;                 // ends: offsets[p] = length > ee
-                int32_t *d = data + src[jj] + (ee - offsets[jj]);
-                if (PACK) message[ee] = *d; else *d = message[ee];
-            }
+            kind[it] = 2;
+        }
+    }
+    v4i val[kCopyIter];
+#pragma unroll
+    for (int it = 0; it < kCopyIter; ++it) {
+        if (kind[it] != 1) continue;
+        const int64_t e = e0 + (int64_t)it * kBlock * 4;
+        if (PACK) {
+            const int32_t *d = inner[it];
+            val[it] = (v4i){d[0], d[1], d[2], d[3]};
+        } else if (msg_aligned) {
+            val[it] = *reinterpret_cast<const v4i *>(message + e);
+        } else {
+            val[it] = (v4i){message[e], message[e + 1], message[e + 2], message[e + 3]};
+        }
+    }
+#pragma unroll
+    for (int it = 0; it < kCopyIter; ++it) {
+        if (kind[it] != 1) continue;
+        const int64_t e = e0 + (int64_t)it * kBlock * 4;
+        const v4i v = val[it];
+        if (PACK) {
+            if (msg_aligned) __builtin_nontemporal_store(v, reinterpret_cast<v4i *>(message + e));
+            else { message[e] = v[0]; message[e + 1] = v[1]; message[e + 2] = v[2]; message[e + 3] = v[3]; }
+        } else {
+            int32_t *d = inner[it];
+            d[0] = v[0]; d[1] = v[1]; d[2] = v[2]; d[3] = v[3];
+        }
+    }
+    // pieces that cross into other roots' blocks (or the end): element by element
+#pragma unroll
+    for (int it = 0; it < kCopyIter; ++it) {
+        if (kind[it] != 2) continue;
+        const int64_t e = e0 + (int64_t)it * kBlock * 4;
+        uint32_t jj = first_root[it];
+        for (int c = 0; c < 4; ++c) {
+            const int64_t ee = e + c;
+            if (ee >= end) break;
+            while (offsets[jj + 1] <= ee) ++jj;                     // ends: offsets[p] = length > ee
+            int32_t *d = data + src[jj] + (ee - offsets[jj]);
+            if (PACK) message[ee] = *d; else *d = message[ee];
         }
     }
 }
