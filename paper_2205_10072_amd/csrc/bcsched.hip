@@ -717,13 +717,15 @@ __global__ __launch_bounds__(kBlock) void k_allgather_tables_v4(const SkipTab ta
                                                                 const int32_t *__restrict__ recvT, uint64_t ldT,
                                                                 int32_t *__restrict__ pack,
                                                                 int32_t *__restrict__ unpack) {
-    // entry - k for unpack / pack; root i of the chunk sits in plane i % 4 at i / 4, so that lanes reading every
-    // fourth entry hit consecutive words
+    // blockIdx.z picks the table: a workgroup writes one stream.  entry - k of its table; root i of the chunk
+    // sits in plane i % 4 at i / 4, so that lanes reading every fourth entry hit consecutive words
     constexpr uint32_t kPlane = kAgVecChunk / 4 + 16;
-    __shared__ int32_t tu[4 * kPlane], tp[4 * kPlane];
+    __shared__ int32_t tt[4 * kPlane];
+    const bool packing = unpack == nullptr || blockIdx.z == 1;
+    int32_t *__restrict__ out = packing ? pack : unpack;
     const uint32_t p = tab.s[q];
     const uint32_t k = blockIdx.y;
-    const uint32_t sk = tab.s[k];
+    const uint32_t sk = packing ? tab.s[k] : 0u;                  // the pack entry is that of the to-neighbour
     const int32_t *row = recvT + (uint64_t)k * ldT;
     const uint64_t c0 = (uint64_t)blockIdx.x * kAgVecChunk;       // first root of this workgroup
     const uint32_t valid = (uint32_t)(((uint64_t)p - c0) < (uint64_t)kAgVecChunk ? ((uint64_t)p - c0)
@@ -731,11 +733,9 @@ __global__ __launch_bounds__(kBlock) void k_allgather_tables_v4(const SkipTab ta
     for (uint32_t i = threadIdx.x; i < valid; i += kBlock) {
         const uint32_t j = (uint32_t)c0 + i;
         const uint32_t vr = r >= j ? r - j : r + p - j;           // virtual rank of r under root j
-        uint32_t to = vr + sk;
-        to = to >= p ? to - p : to;
-        const uint32_t w = (i & 3u) * kPlane + (i >> 2);
-        tu[w] = row[vr] - (int32_t)k;
-        tp[w] = row[to] - (int32_t)k;
+        uint32_t from = vr + sk;
+        from = from >= p ? from - p : from;
+        tt[(i & 3u) * kPlane + (i >> 2)] = row[from] - (int32_t)k;
     }
     __syncthreads();
     const v4i lo = {-1, -1, -1, -1}, hi = {nm1, nm1, nm1, nm1};
@@ -754,35 +754,19 @@ __global__ __launch_bounds__(kBlock) void k_allgather_tables_v4(const SkipTab ta
         const uint32_t w2 = ((lead + 2u) & 3u) * kPlane + ((lead + 2u) >> 2), w3 = ((lead + 3u) & 3u) * kPlane + ((lead + 3u) >> 2);
         for (uint32_t g = threadIdx.x; g < groups; g += kBlock) {
             const uint32_t i = lead + 4u * g;
-            if (unpack) {
-                v4i v = {tu[w0 + g], tu[w1 + g], tu[w2 + g], tu[w3 + g]};
-                v += add;
-                v = v > lo ? v : lo;
-                v = v < hi ? v : hi;
-                __builtin_nontemporal_store(v, reinterpret_cast<v4i *>(unpack + flat0 + i));
-            }
-            if (pack) {
-                v4i v = {tp[w0 + g], tp[w1 + g], tp[w2 + g], tp[w3 + g]};
-                v += add;
-                v = v > lo ? v : lo;
-                v = v < hi ? v : hi;
-                __builtin_nontemporal_store(v, reinterpret_cast<v4i *>(pack + flat0 + i));
-            }
+            v4i v = {tt[w0 + g], tt[w1 + g], tt[w2 + g], tt[w3 + g]};
+            v += add;
+            v = v > lo ? v : lo;
+            v = v < hi ? v : hi;
+            __builtin_nontemporal_store(v, reinterpret_cast<v4i *>(out + flat0 + i));
         }
         // the entries outside the aligned groups: lanes 0..31 at the front, 32..34 at the back
         const uint32_t t = threadIdx.x;
         const uint32_t i = t < 32u ? t : tail0 + (t - 32u);
         const bool mine = t < 32u ? t < lead : (t < 35u && i < valid);
         if (mine) {
-            const uint32_t w = (i & 3u) * kPlane + (i >> 2);
-            if (unpack) {
-                const int32_t raw = tu[w] + jj;
-                unpack[flat0 + i] = raw < 0 ? -1 : (raw > nm1 ? nm1 : raw);
-            }
-            if (pack) {
-                const int32_t raw = tp[w] + jj;
-                pack[flat0 + i] = raw < 0 ? -1 : (raw > nm1 ? nm1 : raw);
-            }
+            const int32_t raw = tt[(i & 3u) * kPlane + (i >> 2)] + jj;
+            out[flat0 + i] = raw < 0 ? -1 : (raw > nm1 ? nm1 : raw);
         }
     }
 }
@@ -1453,7 +1437,7 @@ int bcs_allgather_tables_ws(int32_t p, int32_t n, int32_t r, int32_t *pack_idx, 
     const bool vec = ((((uintptr_t)pack_idx) | ((uintptr_t)unpack_idx)) & 15u) == 0;
     if (vec) {
         const unsigned bv = (unsigned)(((uint64_t)p + kAgVecChunk - 1) / kAgVecChunk);
-        launch(kAllgather, k_allgather_tables_v4, dim3(bv, (unsigned)q), dim3(kBlock), st, tab, q, (uint32_t)r, x,
+        launch(kAllgather, k_allgather_tables_v4, dim3(bv, (unsigned)q, (pack_idx && unpack_idx) ? 2u : 1u), dim3(kBlock), st, tab, q, (uint32_t)r, x,
                (int32_t)(n - 1), R, (const int32_t *)recvT, ld, pack_idx, unpack_idx);
     } else {
         launch(kAllgather, k_allgather_tables, dim3(bx, (unsigned)q), dim3(kBlock), st, tab, q, (uint32_t)r, x,
