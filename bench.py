@@ -32,9 +32,9 @@ INT_VALU_PEAK_GOPS = 256 * 4 * 16 * 2.4     # CUs x SIMDs x lanes x GHz = 39 321
 # HBM bytes per launch at this workload, from the rocprofv3 counter runs summarised in
 # profiles/bench_c2_kernels.md (FETCH_SIZE scaled x2.0, WRITE_SIZE x1.0 by the 1 GiB copy calibration).
 PROFILED_TRAFFIC_BYTES = {
-    "k_expand": (2 * 53089 + 1130913) * 1024,
-    "k_recv_uniform": (2 * 55 + 172033) * 1024,
-    "k_send_lookup": (2 * 48172 + 86016) * 1024,
+    "k_expand": (2 * 53089 + 1130922) * 1024,
+    "k_recv_uniform": (2 * 51 + 107521) * 1024,
+    "k_send_lookup": (2 * 15894 + 86016) * 1024,
 }
 
 
@@ -391,7 +391,7 @@ def main():
             nbytes = P * R * 4                                  # one table per launch, written once
             ent.update(bound="hbm", achieved=nbytes / avg_ms / 1e6, peak=HBM_PEAK_GBS, unit="GB/s")
         elif name == "k_send_lookup":
-            nbytes = 2 * P * q * 4                              # read one table, write one table
+            nbytes = P * q * (1 + 4)                            # read the one-byte slot-major entries, write one table
             ent.update(bound="hbm", achieved=nbytes / avg_ms / 1e6, peak=HBM_PEAK_GBS, unit="GB/s")
         elif name == "k_recv_uniform":
             ops = valu_ops_per_rank(q) * P

@@ -18,6 +18,8 @@ namespace {
 
 using namespace bcs;
 typedef int v4i __attribute__((ext_vector_type(4)));
+// An entry of the slot-major receive table kept in scratch memory: schedule entries lie in [-q, q-1], q <= 31.
+typedef int8_t slot_t;
 static_assert(kMaxQ == BCS_MAX_Q, "header and core disagree");
 constexpr int kBlock = 256;              // lanes (= ranks) per workgroup
 
@@ -102,7 +104,7 @@ __device__ __forceinline__ void stage_lowtab(uint32_t *dst, int shape) {
 template <int Q>
 __global__ __launch_bounds__(kBlock) void k_recv_uniform(const SkipTab tab, uint32_t root, uint32_t r0, uint32_t r1,
                                                          int32_t *__restrict__ recv_out,
-                                                         int32_t *__restrict__ recvT, uint64_t ldT) {
+                                                         slot_t *__restrict__ recvT, uint64_t ldT) {
     constexpr int kStride = Q | 1;
     __shared__ int32_t tile[kBlock * kStride];
     __shared__ uint32_t lowtab[kLowShapeBytes / 4];
@@ -123,7 +125,7 @@ __global__ __launch_bounds__(kBlock) void k_recv_uniform(const SkipTab tab, uint
     int32_t *my = tile + threadIdx.x * kStride;
     recv_row(pol, v, Q - 1, [&](int i, int val) {
         my[i] = val;
-        if (recvT && live) recvT[(uint64_t)i * ldT + idx] = val;
+        if (recvT && live) recvT[(uint64_t)i * ldT + idx] = (slot_t)val;
     });
     if (!recv_out) return;
     __syncthreads();
@@ -139,7 +141,7 @@ __global__ __launch_bounds__(kBlock) void k_recv_uniform(const SkipTab tab, uint
 // K2: send rows from the slot-major receive table of ALL ranks (Alg. 9, second loop):
 // send[r][k] = recv[(r + skips[k]) mod p][k].  Reads are contiguous per slot, rows leave through LDS.
 template <int Q>
-__global__ __launch_bounds__(kBlock) void k_send_lookup(const SkipTab tab, const int32_t *__restrict__ recvT,
+__global__ __launch_bounds__(kBlock) void k_send_lookup(const SkipTab tab, const slot_t *__restrict__ recvT,
                                                         uint64_t ldT, int32_t *__restrict__ send_out) {
     constexpr int kStride = Q | 1;
     __shared__ int32_t tile[kBlock * kStride];
@@ -546,7 +548,7 @@ __device__ __forceinline__ void tile_expand(const int32_t *tile, uint32_t rows, 
 
 template <int Q>
 __global__ __launch_bounds__(kBlock) void k_recv_expand(const SkipTab tab, uint32_t root, const ExpandArgs ea,
-                                                        int32_t *__restrict__ recv_out, int32_t *__restrict__ recvT,
+                                                        int32_t *__restrict__ recv_out, slot_t *__restrict__ recvT,
                                                         uint64_t ldT, int32_t *__restrict__ blocks_out) {
     constexpr int W = FusedTile<Q>::kWidth;
     __shared__ int32_t tile[kBlock * W];
@@ -567,7 +569,7 @@ __global__ __launch_bounds__(kBlock) void k_recv_expand(const SkipTab tab, uint3
     int32_t *my = tile + threadIdx.x * W;
     recv_row(pol, v, Q - 1, [&](int i, int val) {
         my[i] = val - i;
-        if (live) recvT[(uint64_t)i * ldT + idx] = val;
+        if (live) recvT[(uint64_t)i * ldT + idx] = (slot_t)val;
     });
     tile_mirrors<Q>(tile, ea.x, ea.R);
     const uint32_t rows = (uint32_t)(((uint64_t)p - first) < (uint64_t)kBlock ? ((uint64_t)p - first) : (uint64_t)kBlock);
@@ -577,7 +579,7 @@ __global__ __launch_bounds__(kBlock) void k_recv_expand(const SkipTab tab, uint3
 
 template <int Q>
 __global__ __launch_bounds__(kBlock) void k_send_expand(const SkipTab tab, const ExpandArgs ea,
-                                                        const int32_t *__restrict__ recvT, uint64_t ldT,
+                                                        const slot_t *__restrict__ recvT, uint64_t ldT,
                                                         int32_t *__restrict__ send_out,
                                                         int32_t *__restrict__ blocks_out) {
     constexpr int W = FusedTile<Q>::kWidth;
@@ -668,13 +670,13 @@ constexpr int kAgChunk = kAgRootsPerLane * kBlock;
 
 __global__ __launch_bounds__(kBlock) void k_allgather_tables(const SkipTab tab, int q, uint32_t r, uint32_t x,
                                                              int32_t nm1, uint64_t R,
-                                                             const int32_t *__restrict__ recvT, uint64_t ldT,
+                                                             const slot_t *__restrict__ recvT, uint64_t ldT,
                                                              int32_t *__restrict__ pack,
                                                              int32_t *__restrict__ unpack) {
     const uint32_t p = tab.s[q];
     const uint32_t k = blockIdx.y;
     const uint32_t sk = tab.s[k];
-    const int32_t *row = recvT + (uint64_t)k * ldT;
+    const slot_t *row = recvT + (uint64_t)k * ldT;
     const uint64_t first = (uint64_t)blockIdx.x * kAgChunk + threadIdx.x;   // this lane's first root
     int32_t tu[kAgRootsPerLane], tp[kAgRootsPerLane];                        // entry - k for unpack / pack
 #pragma unroll
@@ -714,7 +716,7 @@ constexpr int kAgVecChunk = 4096;                      // roots per workgroup
 
 __global__ __launch_bounds__(kBlock) void k_allgather_tables_v4(const SkipTab tab, int q, uint32_t r, uint32_t x,
                                                                 int32_t nm1, uint64_t R,
-                                                                const int32_t *__restrict__ recvT, uint64_t ldT,
+                                                                const slot_t *__restrict__ recvT, uint64_t ldT,
                                                                 int32_t *__restrict__ pack,
                                                                 int32_t *__restrict__ unpack) {
     // blockIdx.z picks the table: a workgroup writes one stream.  entry - k of its table; root i of the chunk
@@ -726,7 +728,7 @@ __global__ __launch_bounds__(kBlock) void k_allgather_tables_v4(const SkipTab ta
     const uint32_t p = tab.s[q];
     const uint32_t k = blockIdx.y;
     const uint32_t sk = packing ? tab.s[k] : 0u;                  // the pack entry is that of the to-neighbour
-    const int32_t *row = recvT + (uint64_t)k * ldT;
+    const slot_t *row = recvT + (uint64_t)k * ldT;
     const uint64_t c0 = (uint64_t)blockIdx.x * kAgVecChunk;       // first root of this workgroup
     const uint32_t valid = (uint32_t)(((uint64_t)p - c0) < (uint64_t)kAgVecChunk ? ((uint64_t)p - c0)
                                                                                   : (uint64_t)kAgVecChunk);
@@ -1112,9 +1114,12 @@ int scratch_get(size_t bytes, void **out) {
 
 inline uint64_t round_up(uint64_t v, uint64_t m) { return (v + m - 1) / m * m; }
 
+// row length of the slot-major receive table (rows start on 256-byte boundaries)
+inline uint64_t slot_ld(int32_t p) { return round_up((uint64_t)p, 256); }
+
 template <int Q>
 int launch_sched(const SkipTab &tab, uint32_t root, uint32_t r0, uint32_t r1, int32_t *recv_out, int32_t *send_out,
-                 int32_t *recvT, uint64_t ldT, hipStream_t st) {
+                 slot_t *recvT, uint64_t ldT, hipStream_t st) {
     const uint64_t count = (uint64_t)r1 - r0;
     const unsigned blocks = (unsigned)((count + kBlock - 1) / kBlock);
     const bool full = (r0 == 0 && r1 == tab.s[Q]);
@@ -1122,11 +1127,11 @@ int launch_sched(const SkipTab &tab, uint32_t root, uint32_t r0, uint32_t r1, in
     const bool want_t = full && recvT && (send_out || !recv_out);
     if (recv_out || want_t) {
         launch(kRecv, k_recv_uniform<Q>, dim3(blocks), dim3(kBlock), st, tab, root, r0, r1, recv_out,
-               want_t ? recvT : (int32_t *)nullptr, ldT);
+               want_t ? recvT : (slot_t *)nullptr, ldT);
     }
     if (send_out) {
         if (full) {
-            launch(kSendLookup, k_send_lookup<Q>, dim3(blocks), dim3(kBlock), st, tab, (const int32_t *)recvT, ldT,
+            launch(kSendLookup, k_send_lookup<Q>, dim3(blocks), dim3(kBlock), st, tab, (const slot_t *)recvT, ldT,
                                send_out);
         } else {
             launch(kSendRecompute, k_send_recompute<Q>, dim3(blocks), dim3(kBlock), st, tab, root, r0, r1, send_out);
@@ -1136,7 +1141,7 @@ int launch_sched(const SkipTab &tab, uint32_t root, uint32_t r0, uint32_t r1, in
     return e == hipSuccess ? BCS_OK : hip_fail(e);
 }
 
-typedef int (*LaunchFn)(const SkipTab &, uint32_t, uint32_t, uint32_t, int32_t *, int32_t *, int32_t *, uint64_t,
+typedef int (*LaunchFn)(const SkipTab &, uint32_t, uint32_t, uint32_t, int32_t *, int32_t *, slot_t *, uint64_t,
                         hipStream_t);
 
 template <int... Qs>
@@ -1187,12 +1192,12 @@ inline bool use_fused(int32_t p, int q, uint64_t R, bool aligned) {
 
 template <int Q>
 int launch_fused(const SkipTab &tab, uint32_t root, const ExpandArgs &ea, int32_t *recv_out, int32_t *send_out,
-                 int32_t *recvT, uint64_t ldT, int32_t *recv_blocks, int32_t *send_blocks, hipStream_t st) {
+                 slot_t *recvT, uint64_t ldT, int32_t *recv_blocks, int32_t *send_blocks, hipStream_t st) {
     if constexpr (Q >= (int)kExpMinQ) {
         const unsigned blocks = (unsigned)(((uint64_t)tab.s[Q] + kBlock - 1) / kBlock);
         launch(kRecvExpand, k_recv_expand<Q>, dim3(blocks), dim3(kBlock), st, tab, root, ea, recv_out, recvT, ldT,
                recv_blocks);
-        launch(kSendExpand, k_send_expand<Q>, dim3(blocks), dim3(kBlock), st, tab, ea, (const int32_t *)recvT, ldT,
+        launch(kSendExpand, k_send_expand<Q>, dim3(blocks), dim3(kBlock), st, tab, ea, (const slot_t *)recvT, ldT,
                send_out, send_blocks);
         hipError_t e = hipGetLastError();
         return e == hipSuccess ? BCS_OK : hip_fail(e);
@@ -1201,7 +1206,7 @@ int launch_fused(const SkipTab &tab, uint32_t root, const ExpandArgs &ea, int32_
     }
 }
 
-typedef int (*FusedFn)(const SkipTab &, uint32_t, const ExpandArgs &, int32_t *, int32_t *, int32_t *, uint64_t,
+typedef int (*FusedFn)(const SkipTab &, uint32_t, const ExpandArgs &, int32_t *, int32_t *, slot_t *, uint64_t,
                        int32_t *, int32_t *, hipStream_t);
 
 template <int... Qs>
@@ -1246,8 +1251,8 @@ int64_t bcs_sched_workspace_bytes(int32_t p, int32_t r0, int32_t r1, int want_se
     if (check_range(p, 0, r0, r1) != BCS_OK) return BCS_EINVAL;
     const int q = host_q(p);
     if (!want_send || q == 0 || !(r0 == 0 && r1 == p)) return 0;
-    const uint64_t ld = round_up((uint64_t)p, 64);
-    return (int64_t)(ld * (uint64_t)q * sizeof(int32_t));
+    const uint64_t ld = slot_ld(p);
+    return (int64_t)(ld * (uint64_t)q * sizeof(slot_t));
 }
 
 int bcs_sched_rooted_ws(int32_t p, int32_t root, int32_t r0, int32_t r1, int32_t *recv_out, int32_t *send_out,
@@ -1263,9 +1268,9 @@ int bcs_sched_rooted_ws(int32_t p, int32_t root, int32_t r0, int32_t r1, int32_t
     host_skips(p, tab);
     rc = ensure_lowtab((hipStream_t)stream);
     if (rc != BCS_OK) return rc;
-    const uint64_t ld = round_up((uint64_t)p, 64);
+    const uint64_t ld = slot_ld(p);
     return launch_for_q(q)(tab, (uint32_t)root, (uint32_t)r0, (uint32_t)r1, recv_out, send_out,
-                           need > 0 ? (int32_t *)workspace : nullptr, ld, (hipStream_t)stream);
+                           need > 0 ? (slot_t *)workspace : nullptr, ld, (hipStream_t)stream);
 }
 
 int bcs_sched_rooted(int32_t p, int32_t root, int32_t r0, int32_t r1, int32_t *recv_out, int32_t *send_out,
@@ -1369,8 +1374,8 @@ int bcs_sched_expand_ws(int32_t p, int32_t root, int32_t n, int32_t *recv_out, i
     const int rc = ensure_lowtab((hipStream_t)stream);
     if (rc != BCS_OK) return rc;
     const ExpandArgs ea = expand_args((uint64_t)p, R, q, n, recv_blocks);
-    return fused_for_q(q)(tab, (uint32_t)root, ea, recv_out, send_out, (int32_t *)workspace,
-                          round_up((uint64_t)p, 64), recv_blocks, send_blocks, (hipStream_t)stream);
+    return fused_for_q(q)(tab, (uint32_t)root, ea, recv_out, send_out, (slot_t *)workspace,
+                          slot_ld(p), recv_blocks, send_blocks, (hipStream_t)stream);
 }
 
 int bcs_sched_expand(int32_t p, int32_t root, int32_t n, int32_t *recv_out, int32_t *send_out, int32_t *recv_blocks,
@@ -1428,8 +1433,8 @@ int bcs_allgather_tables_ws(int32_t p, int32_t n, int32_t r, int32_t *pack_idx, 
     host_skips(p, tab);
     int rc = ensure_lowtab(st);
     if (rc != BCS_OK) return rc;
-    const uint64_t ld = round_up((uint64_t)p, 64);
-    int32_t *recvT = (int32_t *)workspace;
+    const uint64_t ld = slot_ld(p);
+    slot_t *recvT = (slot_t *)workspace;
     rc = launch_for_q(q)(tab, 0u, 0u, (uint32_t)p, nullptr, nullptr, recvT, ld, st);
     if (rc != BCS_OK) return rc;
     const unsigned bx = (unsigned)(((uint64_t)p + kAgChunk - 1) / kAgChunk);
@@ -1438,10 +1443,10 @@ int bcs_allgather_tables_ws(int32_t p, int32_t n, int32_t r, int32_t *pack_idx, 
     if (vec) {
         const unsigned bv = (unsigned)(((uint64_t)p + kAgVecChunk - 1) / kAgVecChunk);
         launch(kAllgather, k_allgather_tables_v4, dim3(bv, (unsigned)q, (pack_idx && unpack_idx) ? 2u : 1u), dim3(kBlock), st, tab, q, (uint32_t)r, x,
-               (int32_t)(n - 1), R, (const int32_t *)recvT, ld, pack_idx, unpack_idx);
+               (int32_t)(n - 1), R, (const slot_t *)recvT, ld, pack_idx, unpack_idx);
     } else {
         launch(kAllgather, k_allgather_tables, dim3(bx, (unsigned)q), dim3(kBlock), st, tab, q, (uint32_t)r, x,
-               (int32_t)(n - 1), R, (const int32_t *)recvT, ld, pack_idx, unpack_idx);
+               (int32_t)(n - 1), R, (const slot_t *)recvT, ld, pack_idx, unpack_idx);
     }
     hipError_t e = hipGetLastError();
     return e == hipSuccess ? BCS_OK : hip_fail(e);
