@@ -234,6 +234,57 @@ def test_expand_small_and_ragged(bcs, oracle):
             assert np.array_equal(sb.cpu().numpy(), oracle.expand(p, n, osend[r0:r1])), (p, n, r0, r1)
 
 
+def _check_blocks_on_device(p, n, sched, blocks, oracle, osched, seed):
+    """`blocks` (device, [p][R]) against the index arithmetic of Alg. 6 applied to `sched` (device, [p][q]) with
+    tensor operations, chunk by chunk, and sampled rows against the oracle's expansion of its own rows."""
+    q = sched.shape[1]
+    R = n - 1 + q
+    x = (q - R % q) % q
+    j = torch.arange(R, device="cuda")
+    k = (x + j) % q
+    shift = (j - k).to(torch.int32)
+    step = max(1, (1 << 28) // R)
+    for r0 in range(0, p, step):
+        want = (sched[r0:r0 + step][:, k] + shift).clamp_(min=-1, max=n - 1)
+        assert torch.equal(blocks[r0:r0 + step], want), r0
+        del want
+    rng = np.random.default_rng(seed)
+    rows = np.unique(np.concatenate([[0, 1, p - 1], rng.integers(0, p, 3000)]))
+    got = blocks[torch.from_numpy(rows).cuda()].cpu().numpy()
+    assert np.array_equal(got, oracle.expand(p, n, osched[rows]))
+
+
+def test_tables_of_more_than_2_to_32_entries(bcs, oracle):
+    """Flat indices beyond 32 bits in the expansion (both store variants) and in the one-call entry point."""
+    for p, n in [((1 << 22) + 1, 1100), ((1 << 23) + 1, 500)]:        # rows above / below 640 rounds
+        q, R = bcs.bcs_q(p), bcs.bcs_rounds(p, n)
+        assert p * R > 1 << 32
+        orecv, _ = oracle.sched_range(p, want_send=False, threads=16)
+        recv = torch.from_numpy(orecv).cuda()
+        rb = torch.full((p, R), 4242, dtype=torch.int32, device="cuda")
+        bcs.bcs_expand(p, n, 0, p, recv, None, rb, None)
+        torch.cuda.synchronize()
+        _check_blocks_on_device(p, n, recv, rb, oracle, orecv, seed=p)
+        del recv, rb, orecv
+        torch.cuda.empty_cache()
+    p, n, root = (1 << 25) + 1, 135, 31415926                          # fused kernels, R = 160
+    q, R = bcs.bcs_q(p), bcs.bcs_rounds(p, n)
+    assert R == 160 and p * R > 1 << 32
+    recv, send = dev_tables(p, q)
+    rb = torch.full((p, R), 4242, dtype=torch.int32, device="cuda")
+    sb = torch.full((p, R), 4242, dtype=torch.int32, device="cuda")
+    bcs.bcs_sched_expand(p, root, n, recv, send, rb, sb)
+    torch.cuda.synchronize()
+    orecv, osend = oracle.sched_range(p, root=root, threads=16)
+    assert np.array_equal(recv.cpu().numpy(), orecv)
+    assert np.array_equal(send.cpu().numpy(), osend)
+    _check_blocks_on_device(p, n, recv, rb, oracle, orecv, seed=1)
+    _check_blocks_on_device(p, n, send, sb, oracle, osend, seed=2)
+    del recv, send, rb, sb
+    bcs.bcs_release()
+    torch.cuda.empty_cache()
+
+
 def test_irregular_batch(bcs, oracle):
     """Config 5: 2^20 seeded (p, r, root) triples, p log-uniform up to 2^31 - 1."""
     from paper_2205_10072_amd import synth
@@ -446,6 +497,66 @@ def test_pack_and_unpack_one_round(bcs, oracle):
             torch.cuda.synchronize()
             assert np.array_equal(d_blank.cpu().numpy(), blank), (p, n, kind)
             assert np.array_equal(d_off.cpu().numpy(), ooff)
+
+
+def test_allgather_tables_and_messages_beyond_32_bit_sizes(bcs, oracle):
+    """Index tables of 2 x 4.4 G entries and a packed message of 4.1 G elements: the 64-bit paths, checked on the
+    device against the defining index arithmetic (Alg. 9; Alg. 6 for the round shift) written with tensor operations."""
+    p, n, r = (1 << 23) + 1, 500, 1234567
+    q, R = bcs.bcs_q(p), bcs.bcs_rounds(p, n)
+    assert R * p > 1 << 32
+    skips = bcs.bcs_skips(p)
+    recv, _ = dev_tables(p, q)
+    bcs.bcs_sched(p, 0, p, recv, None)
+    pack = torch.full((R, p), 4242, dtype=torch.int32, device="cuda")
+    unpack = torch.full((R, p), 4242, dtype=torch.int32, device="cuda")
+    bcs.bcs_allgather_tables(p, n, r, pack, unpack)
+    torch.cuda.synchronize()
+    orecv, _ = oracle.sched_range(p, want_send=False, threads=16)
+    assert np.array_equal(recv.cpu().numpy(), orecv)
+    del orecv
+    x = (q - R % q) % q
+    vr = (r - torch.arange(p, device="cuda")) % p                  # virtual rank of r towards each root
+    cols = [recv[:, k].contiguous() for k in range(q)]
+    for j in range(R):
+        k = (x + j) % q
+        assert torch.equal(unpack[j], (cols[k][vr] + (j - k)).clamp_(min=-1, max=n - 1)), j
+        assert torch.equal(pack[j], (cols[k][(vr + int(skips[k])) % p] + (j - k)).clamp_(min=-1, max=n - 1)), j
+    del pack, unpack, recv, cols, vr
+    bcs.bcs_release()
+    torch.cuda.empty_cache()
+
+    from paper_2205_10072_amd import synth
+    p, n = 1152, 2
+    sizes, displs = synth.irregular_sizes(p, 1 << 33)
+    total = int(displs[-1])
+    rng = np.random.default_rng(9)
+    idx = rng.integers(0, n, p).astype(np.int32)
+    idx[rng.integers(0, p, 40)] = -1                                # some roots send nothing
+    begin = np.where(idx >= 0, idx.astype(np.int64) * sizes // n, 0)
+    length = np.where(idx >= 0, (idx.astype(np.int64) + 1) * sizes // n - begin, 0)
+    offsets = np.concatenate([[0], np.cumsum(length)]).astype(np.int64)
+    msg_len = int(offsets[-1])
+    assert msg_len > 1 << 31                                       # element indices do not fit in int32
+    data = torch.randint(0, 1 << 30, (total,), dtype=torch.int32, device="cuda")
+    d_idx, d_displs = torch.from_numpy(idx).cuda(), torch.from_numpy(displs).cuda()
+    d_msg = torch.full((msg_len + 4,), -99, dtype=torch.int32, device="cuda")
+    d_off = torch.full((p + 1,), -1, dtype=torch.int64, device="cuda")
+    ws = torch.empty(bcs.bcs_pack_workspace_bytes(p), dtype=torch.uint8, device="cuda")
+    bcs.bcs_pack_round(n, d_idx, d_displs, data, d_msg[:msg_len], d_off, ws)
+    torch.cuda.synchronize()
+    assert np.array_equal(d_off.cpu().numpy(), offsets)
+    assert bool((d_msg[msg_len:] == -99).all())
+    for j in range(p):
+        src = int(displs[j] + begin[j])
+        assert torch.equal(d_msg[int(offsets[j]):int(offsets[j + 1])], data[src:src + int(length[j])]), j
+    blank = torch.full((total,), -5, dtype=torch.int32, device="cuda")
+    bcs.bcs_unpack_round(n, d_idx, d_displs, blank, d_msg[:msg_len], msg_len, d_off, ws)
+    torch.cuda.synchronize()
+    for j in range(p):
+        lo, src = int(displs[j]), int(displs[j] + begin[j])
+        assert torch.equal(blank[src:src + int(length[j])], data[src:src + int(length[j])]), j
+        assert bool((blank[lo:src] == -5).all()) and bool((blank[src + int(length[j]):int(displs[j + 1])] == -5).all()), j
 
 
 def test_irregular_allgather_on_the_gpu_moves_all_the_data(bcs):
