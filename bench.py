@@ -77,7 +77,7 @@ def cpu_baseline(budget_s=10.0):
         one_step(threads)
         done += 1
         el = time.perf_counter() - t0
-        if el >= budget_s or done >= 50:
+        if el >= budget_s or done >= 1000:
             break
     t1 = time.perf_counter()
     one_step(1)
