@@ -557,6 +557,8 @@ def test_allgather_tables_and_messages_beyond_32_bit_sizes(bcs, oracle):
         lo, src = int(displs[j]), int(displs[j] + begin[j])
         assert torch.equal(blank[src:src + int(length[j])], data[src:src + int(length[j])]), j
         assert bool((blank[lo:src] == -5).all()) and bool((blank[src + int(length[j]):int(displs[j + 1])] == -5).all()), j
+    del data, blank, d_msg
+    torch.cuda.empty_cache()
 
 
 def test_irregular_allgather_on_the_gpu_moves_all_the_data(bcs):
