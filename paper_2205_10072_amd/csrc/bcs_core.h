@@ -208,17 +208,27 @@ BCS_HD uint32_t digits(const Pol &pol, uint32_t y) {
                 : "vcc");
         }
     } else {
+        // Per-lane p: the lane's own levels come first, whatever the wave's bound.  Step m handles level
+        // q-1-m, whose skip is ((p-1) >> (m+1)) + 1 (Alg. 1's halving), so g = skip - 1 is one shift a
+        // step and "y - g - 1 with borrow-out" (borrow-in forced to one) subtracts the skip: four vector
+        // ops a level.  Steps past level 0 find y = 0 below a skip of 1 and change nothing; the digits
+        // are moved down to their places at the end.
+        const int steps = pol.top() + 1;
+        const uint64_t ones = ~0ull;
+        uint32_t g = pol.pm1;
 #pragma unroll 1
-        for (int k = pol.top(); k >= 0; --k) {
+        for (int m = 0; m < steps; ++m) {
             uint32_t t;
-            asm("v_subrev_co_u32 %0, vcc, %3, %1\n\t"
+            asm("v_lshrrev_b32 %3, 1, %3\n\t"
+                "v_subb_co_u32_e64 %0, vcc, %1, %3, %4\n\t"
                 "s_nop 1\n\t"
                 "v_cndmask_b32 %1, %0, %1, vcc\n\t"
                 "v_addc_co_u32 %2, vcc, %2, %2, vcc"
-                : "=&v"(t), "+v"(y), "+v"(inv)
-                : "v"(pol.s(k))
+                : "=&v"(t), "+v"(y), "+v"(inv), "+v"(g)
+                : "s"(ones)
                 : "vcc");
         }
+        return steps > 0 ? ((~inv & (0xffffffffu >> (32 - steps))) >> (steps - pol.ql)) : 0u;
     }
     const int levels = pol.top() + 1;
     return levels > 0 ? (~inv & (0xffffffffu >> (32 - levels))) : 0u;
