@@ -660,10 +660,11 @@ __global__ __launch_bounds__(kBlock) void k_expand_small(const ExpandArgs a, con
 // loops over the roots).  For root j the process acts as virtual rank r' = (r - j + p) mod p of a
 // broadcast rooted at 0, so unpack[round][j] is the expanded receive entry of r' and pack[round][j]
 // that of its to-neighbour's receive row: both come from the slot-major receive table recvT[k][rank].
-// All rounds that use slot k differ by a multiple of q only, so a workgroup takes one slot and
-// kAgChunk consecutive roots, reads its 2 x kAgChunk schedule entries once and walks down the rounds
-// k-x, k-x+q, ..., writing one contiguous piece of kAgChunk entries per table and round; lanes are
-// consecutive roots, so every store of a wave is one contiguous 256-byte piece.
+// k_allgather_tables (outputs at any 4-byte alignment): all rounds that use slot k differ by a multiple
+// of q only, so a workgroup takes one slot and kAgChunk consecutive roots, reads its 2 x kAgChunk
+// schedule entries once and walks down the rounds k-x, k-x+q, ..., writing one contiguous piece of
+// kAgChunk entries per table and round; lanes are consecutive roots, so every store of a wave is one
+// contiguous 256-byte piece.  k_allgather_tables_flat (16-byte aligned outputs) is described with it.
 // ----------------------------------------------------------------------------------------------
 constexpr int kAgRootsPerLane = 16;
 constexpr int kAgChunk = kAgRootsPerLane * kBlock;
@@ -712,64 +713,73 @@ __global__ __launch_bounds__(kBlock) void k_allgather_tables(const SkipTab tab, 
 // 16-byte line, so the schedule entries of the workgroup's roots are staged in LDS and each round
 // reads them back at that round's phase: single entries up to the next 128-byte line, aligned groups
 // of four (a wave stores whole lines), up to three single entries.  Needs 16-byte aligned tables (else the kernel above runs).
-constexpr int kAgVecChunk = 4096;                      // roots per workgroup
+// The same tables as ONE flat stream of R * p entries each, for 16-byte aligned outputs: a workgroup writes one
+// piece of 1024 consecutive entries (4 KiB, whole lines whatever p is) and ends; a lane resolves round and root
+// of its four entries by itself (exact division by p with a multiply-high and one correction), reads the four
+// one-byte table entries -- consecutive ranks, descending -- with one unaligned load, and stores 16 bytes.  No
+// staging and no barrier: measured on MI355X, short workgroups that are dispatched in address order write
+// 7.0 TB/s where a workgroup that walks down the rounds of one slot reaches 5.2 TB/s.
+struct AgFlatArgs {
+    uint64_t total;                       // R * p
+    uint64_t magic_p;                     // floor(2^64 / p) + 1
+    uint32_t p, q, r, x;
+    int32_t nm1;
+    uint32_t magic_q;                     // floor(2^32 / q) + 1; x + j can pass 2^16, the quotient is corrected
+};
 
-__global__ __launch_bounds__(kBlock) void k_allgather_tables_v4(const SkipTab tab, int q, uint32_t r, uint32_t x,
-                                                                int32_t nm1, uint64_t R,
-                                                                const slot_t *__restrict__ recvT, uint64_t ldT,
-                                                                int32_t *__restrict__ pack,
-                                                                int32_t *__restrict__ unpack) {
-    // blockIdx.z picks the table: a workgroup writes one stream.  entry - k of its table; root i of the chunk
-    // sits in plane i % 4 at i / 4, so that lanes reading every fourth entry hit consecutive words
-    constexpr uint32_t kPlane = kAgVecChunk / 4 + 16;
-    __shared__ int32_t tt[4 * kPlane];
-    const bool packing = unpack == nullptr || blockIdx.z == 1;
+__device__ __forceinline__ int32_t ag_entry(const AgFlatArgs &a, const SkipTab &tab, const slot_t *__restrict__ recvT,
+                                            uint64_t ldT, bool packing, uint64_t e) {
+    uint64_t j = __umul64hi(e, a.magic_p);
+    int64_t root = (int64_t)(e - j * a.p);
+    if (root < 0) { root += a.p; --j; }
+    const uint32_t i = a.x + (uint32_t)j;
+    const uint32_t k = i % a.q;
+    const uint32_t vr = a.r >= (uint32_t)root ? a.r - (uint32_t)root : a.r + a.p - (uint32_t)root;
+    uint32_t from = vr + (packing ? tab.s[k] : 0u);
+    from = from >= a.p ? from - a.p : from;
+    const int32_t raw = (int32_t)recvT[(uint64_t)k * ldT + from] - (int32_t)k + (int32_t)j;
+    return raw < 0 ? -1 : (raw > a.nm1 ? a.nm1 : raw);
+}
+
+__global__ __launch_bounds__(kBlock) void k_allgather_tables_flat(const SkipTab tab, const AgFlatArgs a,
+                                                                  const slot_t *__restrict__ recvT, uint64_t ldT,
+                                                                  int32_t *__restrict__ pack,
+                                                                  int32_t *__restrict__ unpack) {
+    const bool packing = unpack == nullptr || blockIdx.y == 1;
     int32_t *__restrict__ out = packing ? pack : unpack;
-    const uint32_t p = tab.s[q];
-    const uint32_t k = blockIdx.y;
-    const uint32_t sk = packing ? tab.s[k] : 0u;                  // the pack entry is that of the to-neighbour
-    const slot_t *row = recvT + (uint64_t)k * ldT;
-    const uint64_t c0 = (uint64_t)blockIdx.x * kAgVecChunk;       // first root of this workgroup
-    const uint32_t valid = (uint32_t)(((uint64_t)p - c0) < (uint64_t)kAgVecChunk ? ((uint64_t)p - c0)
-                                                                                  : (uint64_t)kAgVecChunk);
-    for (uint32_t i = threadIdx.x; i < valid; i += kBlock) {
-        const uint32_t j = (uint32_t)c0 + i;
-        const uint32_t vr = r >= j ? r - j : r + p - j;           // virtual rank of r under root j
-        uint32_t from = vr + sk;
-        from = from >= p ? from - p : from;
-        tt[(i & 3u) * kPlane + (i >> 2)] = row[from] - (int32_t)k;
-    }
-    __syncthreads();
-    const v4i lo = {-1, -1, -1, -1}, hi = {nm1, nm1, nm1, nm1};
-    // first real round that uses slot k: k - x, or one phase later when that is a dummy round
-    for (uint64_t j = k >= x ? k - x : k + (uint32_t)q - x; j < R; j += (uint32_t)q) {
-        const uint64_t flat0 = j * p + c0;
-        // single entries up to the next 128-byte line, so that every wave then stores whole lines
-        uint32_t lead = (32u - (uint32_t)(flat0 & 31u)) & 31u;
-        lead = lead < valid ? lead : valid;
-        const uint32_t groups = (valid - lead) >> 2;
-        const uint32_t tail0 = lead + 4u * groups;                // single entries after the last group
-        const int32_t jj = (int32_t)j;
-        const v4i add = {jj, jj, jj, jj};
-        // entry lead + 4g + c: plane (lead + c) % 4, word g + (lead + c) / 4
-        const uint32_t w0 = ((lead + 0u) & 3u) * kPlane + ((lead + 0u) >> 2), w1 = ((lead + 1u) & 3u) * kPlane + ((lead + 1u) >> 2);
-        const uint32_t w2 = ((lead + 2u) & 3u) * kPlane + ((lead + 2u) >> 2), w3 = ((lead + 3u) & 3u) * kPlane + ((lead + 3u) >> 2);
-        for (uint32_t g = threadIdx.x; g < groups; g += kBlock) {
-            const uint32_t i = lead + 4u * g;
-            v4i v = {tt[w0 + g], tt[w1 + g], tt[w2 + g], tt[w3 + g]};
-            v += add;
-            v = v > lo ? v : lo;
-            v = v < hi ? v : hi;
-            __builtin_nontemporal_store(v, reinterpret_cast<v4i *>(out + flat0 + i));
+    const uint64_t e = ((uint64_t)blockIdx.x * kBlock + threadIdx.x) * 4u;
+    if (e >= a.total) return;
+    // round j = e / p and root = e mod p of the first entry
+    uint64_t j = __umul64hi(e, a.magic_p);
+    int64_t root64 = (int64_t)(e - j * a.p);
+    if (root64 < 0) { root64 += a.p; --j; }
+    const uint32_t root = (uint32_t)root64;
+    // slot k = (x + j) mod q
+    const uint32_t i = a.x + (uint32_t)j;
+    uint32_t k = i - a.q * __umulhi(i, a.magic_q);
+    k = (int32_t)k < 0 ? k + a.q : k;                              // the multiply-high may be one too large
+    const uint32_t vr = a.r >= root ? a.r - root : a.r + a.p - root;   // virtual rank towards `root`
+    uint32_t from = vr + (packing ? tab.s[k] : 0u);                // the pack entry is the to-neighbour's
+    from = from >= a.p ? from - a.p : from;
+    if (e + 4 <= a.total && root + 3u < a.p && from >= 3u) {
+        // entries root .. root+3 of round j read ranks from, from-1, from-2, from-3 of row k
+        const slot_t *src = recvT + (uint64_t)k * ldT + (from - 3u);
+        uint32_t four;
+        __builtin_memcpy(&four, src, 4);
+        const int32_t shift = (int32_t)j - (int32_t)k;
+        const int32_t lo = -1, hi = a.nm1;
+        v4i v;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const int32_t raw = (int32_t)(int8_t)(four >> (8 * (3 - c))) + shift;
+            const int32_t m = raw > lo ? raw : lo;
+            v[c] = m < hi ? m : hi;
         }
-        // the entries outside the aligned groups: lanes 0..31 at the front, 32..34 at the back
-        const uint32_t t = threadIdx.x;
-        const uint32_t i = t < 32u ? t : tail0 + (t - 32u);
-        const bool mine = t < 32u ? t < lead : (t < 35u && i < valid);
-        if (mine) {
-            const int32_t raw = tt[(i & 3u) * kPlane + (i >> 2)] + jj;
-            out[flat0 + i] = raw < 0 ? -1 : (raw > nm1 ? nm1 : raw);
-        }
+        __builtin_nontemporal_store(v, reinterpret_cast<v4i *>(out + e));
+    } else {
+        // the end of a row, a wrap of the ranks, or the end of the table: entry by entry
+        for (int c = 0; c < 4; ++c)
+            if (e + c < a.total) out[e + c] = ag_entry(a, tab, recvT, ldT, packing, e + c);
     }
 }
 
@@ -1441,9 +1451,19 @@ int bcs_allgather_tables_ws(int32_t p, int32_t n, int32_t r, int32_t *pack_idx, 
     const uint32_t x = (uint32_t)((q - (int)(R % (uint64_t)q)) % q);
     const bool vec = ((((uintptr_t)pack_idx) | ((uintptr_t)unpack_idx)) & 15u) == 0;
     if (vec) {
-        const unsigned bv = (unsigned)(((uint64_t)p + kAgVecChunk - 1) / kAgVecChunk);
-        launch(kAllgather, k_allgather_tables_v4, dim3(bv, (unsigned)q, (pack_idx && unpack_idx) ? 2u : 1u), dim3(kBlock), st, tab, q, (uint32_t)r, x,
-               (int32_t)(n - 1), R, (const slot_t *)recvT, ld, pack_idx, unpack_idx);
+        AgFlatArgs fa;
+        fa.total = R * (uint64_t)p;
+        fa.magic_p = ~0ull / (uint64_t)p + 1ull;
+        fa.p = (uint32_t)p;
+        fa.q = (uint32_t)q;
+        fa.r = (uint32_t)r;
+        fa.x = x;
+        fa.nm1 = n - 1;
+        fa.magic_q = (uint32_t)((1ull << 32) / (uint64_t)q + 1ull);
+        const uint64_t pieces = (fa.total + kBlock * 4 - 1) / (kBlock * 4);
+        if (pieces > 0x7fffffffull) return BCS_EINVAL;
+        launch(kAllgather, k_allgather_tables_flat, dim3((unsigned)pieces, (pack_idx && unpack_idx) ? 2u : 1u),
+               dim3(kBlock), st, tab, fa, (const slot_t *)recvT, ld, pack_idx, unpack_idx);
     } else {
         launch(kAllgather, k_allgather_tables, dim3(bx, (unsigned)q), dim3(kBlock), st, tab, q, (uint32_t)r, x,
                (int32_t)(n - 1), R, (const slot_t *)recvT, ld, pack_idx, unpack_idx);
