@@ -322,9 +322,13 @@ def test_batch_edge_rows(bcs, oracle):
     assert torch.equal(recv2, recv)
 
 
-def gpu_allgather(bcs, p, n, r, want_pack=True, want_unpack=True, ws=None):
+def gpu_allgather(bcs, p, n, r, want_pack=True, want_unpack=True, ws=None, misalign=False):
     R = bcs.bcs_rounds(p, n)
-    pack, unpack = dev_tables(R, p, fill=555)
+    if misalign:                                         # tables that start 4 bytes past a 16-byte boundary
+        flat = [torch.full((R * p + 1,), 555, dtype=torch.int32, device="cuda") for _ in range(2)]
+        pack, unpack = (t[1:].view(R, p) for t in flat)
+    else:
+        pack, unpack = dev_tables(R, p, fill=555)
     if ws is None:
         bcs.bcs_allgather_tables(p, n, r, pack if want_pack else None, unpack if want_unpack else None)
     else:
@@ -341,9 +345,10 @@ def test_allgather_tables_against_oracle(bcs, oracle):
             opack, ounpack = oracle.allgather_tables(p, n, r)
             if opack.size == 0:
                 continue
-            pack, unpack = gpu_allgather(bcs, p, n, r)
-            assert np.array_equal(pack, opack), (p, n, r)
-            assert np.array_equal(unpack, ounpack), (p, n, r)
+            for misalign in (False, True):               # 16-byte stores / the kernel for any alignment
+                pack, unpack = gpu_allgather(bcs, p, n, r, misalign=misalign)
+                assert np.array_equal(pack, opack), (p, n, r, misalign)
+                assert np.array_equal(unpack, ounpack), (p, n, r, misalign)
         pack, unpack = gpu_allgather(bcs, p, n, p - 1, want_unpack=False)
         assert np.array_equal(pack, opack) and (unpack == 555).all()
         ws = torch.empty(bcs.bcs_allgather_workspace_bytes(p) + 256, dtype=torch.uint8, device="cuda")
