@@ -879,21 +879,23 @@ __global__ __launch_bounds__(kBlock) void k_pack_plan_finish(uint32_t p, PackPla
     if (j < p) plan.offsets[j] += plan.totals[j / kPlanRoots];
 }
 
-constexpr int kCopyIter = 4;                          // 16-byte pieces per lane
-constexpr int kCopyChunk = kCopyIter * kBlock * 4;    // message elements per workgroup
+constexpr int kCopyIter = 4;                          // 16-byte pieces per lane, long messages
+constexpr int64_t kCopyShort = 4 << 20;               // message elements below which a lane takes one piece
 
 // PACK: data -> message.  !PACK: message -> data.  `limit` = capacity (pack) or message length (unpack).
 // A wave first finds the root of its first element together (64 probes of `offsets` per step), each lane then
-// walks on from there; the roots of a lane's kCopyIter pieces are all found before any payload is touched, so
+// walks on from there; the roots of a lane's ITER pieces are all found before any payload is touched, so
 // that the payload loads of the pieces are in flight together.
-template <bool PACK>
+// Short messages (a few hundred KB in the paper's runs) take one piece a lane, which gives four times the
+// workgroups: 6 us against 16 us for 241 KB; long ones take kCopyIter (0.10 ms against 0.15 ms for 239 MB).
+template <bool PACK, int ITER>
 __global__ __launch_bounds__(kBlock) void k_pack_copy(uint32_t p, int64_t limit, const int64_t *__restrict__ offsets,
                                                       const int64_t *__restrict__ src, int32_t *data,
                                                       int32_t *message, int msg_aligned) {
     int64_t end = offsets[p];
     end = end < limit ? end : limit;
-    const int64_t e0 = (int64_t)blockIdx.x * kCopyChunk + threadIdx.x * 4;
-    const int64_t e_wave = (int64_t)blockIdx.x * kCopyChunk + (threadIdx.x & ~63u) * 4;
+    const int64_t e0 = (int64_t)blockIdx.x * (ITER * kBlock * 4) + threadIdx.x * 4;
+    const int64_t e_wave = (int64_t)blockIdx.x * (ITER * kBlock * 4) + (threadIdx.x & ~63u) * 4;
     if (e_wave >= end) return;                                      // the whole wave leaves together
     // root of the wave's first element: the last j with offsets[j] <= e_wave, answer in [lo, hi)
     uint32_t lo = 0, hi = p;
@@ -910,11 +912,11 @@ __global__ __launch_bounds__(kBlock) void k_pack_copy(uint32_t p, int64_t limit,
     }
     uint32_t j = lo;
     // the pieces of this lane: 0 = none, 1 = whole piece inside one root's block, 2 = crosses a boundary
-    int kind[kCopyIter];
-    int32_t *inner[kCopyIter];
-    uint32_t first_root[kCopyIter];
+    int kind[ITER];
+    int32_t *inner[ITER];
+    uint32_t first_root[ITER];
 #pragma unroll
-    for (int it = 0; it < kCopyIter; ++it) {
+    for (int it = 0; it < ITER; ++it) {
         const int64_t e = e0 + (int64_t)it * kBlock * 4;
         kind[it] = 0;
         inner[it] = data;
@@ -940,9 +942,9 @@ __global__ __launch_bounds__(kBlock) void k_pack_copy(uint32_t p, int64_t limit,
             kind[it] = 2;
         }
     }
-    v4i val[kCopyIter];
+    v4i val[ITER];
 #pragma unroll
-    for (int it = 0; it < kCopyIter; ++it) {
+    for (int it = 0; it < ITER; ++it) {
         if (kind[it] != 1) continue;
         const int64_t e = e0 + (int64_t)it * kBlock * 4;
         if (PACK) {
@@ -955,7 +957,7 @@ __global__ __launch_bounds__(kBlock) void k_pack_copy(uint32_t p, int64_t limit,
         }
     }
 #pragma unroll
-    for (int it = 0; it < kCopyIter; ++it) {
+    for (int it = 0; it < ITER; ++it) {
         if (kind[it] != 1) continue;
         const int64_t e = e0 + (int64_t)it * kBlock * 4;
         const v4i v = val[it];
@@ -969,7 +971,7 @@ __global__ __launch_bounds__(kBlock) void k_pack_copy(uint32_t p, int64_t limit,
     }
     // pieces that cross into other roots' blocks (or the end): element by element
 #pragma unroll
-    for (int it = 0; it < kCopyIter; ++it) {
+    for (int it = 0; it < ITER; ++it) {
         if (kind[it] != 2) continue;
         const int64_t e = e0 + (int64_t)it * kBlock * 4;
         uint32_t jj = first_root[it];
@@ -1542,15 +1544,23 @@ int bcs_pack_round(int32_t p, int32_t n, const int32_t *idx, const int64_t *disp
                    int32_t *packed, int64_t capacity, int64_t *offsets, void *workspace, size_t workspace_bytes,
                    void *stream) {
     if (!data || capacity < 0 || (!packed && capacity > 0)) return BCS_EINVAL;
-    if (((uint64_t)capacity + kCopyChunk - 1) / kCopyChunk > 0x7fffffffull) return BCS_EINVAL;
+    if (((uint64_t)capacity + kBlock * 4 - 1) / (kBlock * 4) > 0x7fffffffull) return BCS_EINVAL;
     PackPlan plan;
     const int rc = pack_plan(p, n, idx, displs, offsets, workspace, workspace_bytes, (hipStream_t)stream, plan);
     if (rc != BCS_OK || capacity == 0) return rc;
-    const uint64_t blocks = ((uint64_t)capacity + kCopyChunk - 1) / kCopyChunk;
-    if (blocks > 0x7fffffffull) return BCS_EINVAL;
-    launch(kPackCopy, k_pack_copy<true>, dim3((unsigned)blocks), dim3(kBlock), (hipStream_t)stream, (uint32_t)p,
-           capacity, (const int64_t *)offsets, (const int64_t *)plan.src, const_cast<int32_t *>(data), packed,
-           (int)((((uintptr_t)packed) & 15u) == 0));
+    const int aligned = (int)((((uintptr_t)packed) & 15u) == 0);
+    if (capacity < kCopyShort) {
+        const uint64_t blocks = ((uint64_t)capacity + kBlock * 4 - 1) / (kBlock * 4);
+        launch(kPackCopy, k_pack_copy<true, 1>, dim3((unsigned)blocks), dim3(kBlock), (hipStream_t)stream, (uint32_t)p,
+               capacity, (const int64_t *)offsets, (const int64_t *)plan.src, const_cast<int32_t *>(data), packed,
+               aligned);
+    } else {
+        const uint64_t chunk = (uint64_t)kCopyIter * kBlock * 4;
+        const uint64_t blocks = ((uint64_t)capacity + chunk - 1) / chunk;
+        launch(kPackCopy, k_pack_copy<true, kCopyIter>, dim3((unsigned)blocks), dim3(kBlock), (hipStream_t)stream,
+               (uint32_t)p, capacity, (const int64_t *)offsets, (const int64_t *)plan.src,
+               const_cast<int32_t *>(data), packed, aligned);
+    }
     hipError_t e = hipGetLastError();
     return e == hipSuccess ? BCS_OK : hip_fail(e);
 }
@@ -1559,15 +1569,23 @@ int bcs_unpack_round(int32_t p, int32_t n, const int32_t *idx, const int64_t *di
                      const int32_t *packed, int64_t length, int64_t *offsets, void *workspace, size_t workspace_bytes,
                      void *stream) {
     if (!data || length < 0 || (!packed && length > 0)) return BCS_EINVAL;
-    if (((uint64_t)length + kCopyChunk - 1) / kCopyChunk > 0x7fffffffull) return BCS_EINVAL;
+    if (((uint64_t)length + kBlock * 4 - 1) / (kBlock * 4) > 0x7fffffffull) return BCS_EINVAL;
     PackPlan plan;
     const int rc = pack_plan(p, n, idx, displs, offsets, workspace, workspace_bytes, (hipStream_t)stream, plan);
     if (rc != BCS_OK || length == 0) return rc;
-    const uint64_t blocks = ((uint64_t)length + kCopyChunk - 1) / kCopyChunk;
-    if (blocks > 0x7fffffffull) return BCS_EINVAL;
-    launch(kPackCopy, k_pack_copy<false>, dim3((unsigned)blocks), dim3(kBlock), (hipStream_t)stream, (uint32_t)p,
-           length, (const int64_t *)offsets, (const int64_t *)plan.src, data, const_cast<int32_t *>(packed),
-           (int)((((uintptr_t)packed) & 15u) == 0));
+    const int aligned = (int)((((uintptr_t)packed) & 15u) == 0);
+    if (length < kCopyShort) {
+        const uint64_t blocks = ((uint64_t)length + kBlock * 4 - 1) / (kBlock * 4);
+        launch(kPackCopy, k_pack_copy<false, 1>, dim3((unsigned)blocks), dim3(kBlock), (hipStream_t)stream, (uint32_t)p,
+               length, (const int64_t *)offsets, (const int64_t *)plan.src, data, const_cast<int32_t *>(packed),
+               aligned);
+    } else {
+        const uint64_t chunk = (uint64_t)kCopyIter * kBlock * 4;
+        const uint64_t blocks = ((uint64_t)length + chunk - 1) / chunk;
+        launch(kPackCopy, k_pack_copy<false, kCopyIter>, dim3((unsigned)blocks), dim3(kBlock), (hipStream_t)stream,
+               (uint32_t)p, length, (const int64_t *)offsets, (const int64_t *)plan.src, data,
+               const_cast<int32_t *>(packed), aligned);
+    }
     hipError_t e = hipGetLastError();
     return e == hipSuccess ? BCS_OK : hip_fail(e);
 }
