@@ -801,11 +801,10 @@ struct PackPlan {
     int64_t *totals;                                 // [ceil(p / kPlanRoots) + 1] workgroup totals, then their scan
 };
 
-__global__ __launch_bounds__(kBlock) void k_pack_plan_local(uint32_t p, uint32_t n, const int32_t *__restrict__ idx,
-                                                            const int64_t *__restrict__ displs, PackPlan plan) {
-    __shared__ int64_t wave_sum[kBlock / 64];
-    const uint64_t first = (uint64_t)blockIdx.x * kPlanRoots + threadIdx.x * 4u;
-    int64_t len[4];
+// four consecutive roots of one lane: block lengths into len[], block positions into plan.src; returns their sum
+__device__ __forceinline__ int64_t plan_roots(uint32_t p, uint32_t n, const int32_t *__restrict__ idx,
+                                              const int64_t *__restrict__ displs, const PackPlan &plan,
+                                              uint64_t first, int64_t (&len)[4]) {
     int64_t mine = 0;
 #pragma unroll
     for (int c = 0; c < 4; ++c) {
@@ -825,7 +824,12 @@ __global__ __launch_bounds__(kBlock) void k_pack_plan_local(uint32_t p, uint32_t
         }
         mine += len[c];
     }
-    // exclusive scan of `mine` over the workgroup: inside a wave by shuffles, across the four waves through LDS
+    return mine;
+}
+
+// exclusive scan of `mine` over the workgroup: inside a wave by shuffles, across the four waves through LDS
+// (wave_sum: kBlock / 64 entries; contains a barrier)
+__device__ __forceinline__ int64_t plan_scan(int64_t mine, int64_t *wave_sum) {
     int64_t incl = mine;
     const int lane = threadIdx.x & 63;
 #pragma unroll
@@ -837,6 +841,16 @@ __global__ __launch_bounds__(kBlock) void k_pack_plan_local(uint32_t p, uint32_t
     __syncthreads();
     int64_t before = incl - mine;
     for (int w = 0; w < (int)(threadIdx.x >> 6); ++w) before += wave_sum[w];
+    return before;
+}
+
+__global__ __launch_bounds__(kBlock) void k_pack_plan_local(uint32_t p, uint32_t n, const int32_t *__restrict__ idx,
+                                                            const int64_t *__restrict__ displs, PackPlan plan) {
+    __shared__ int64_t wave_sum[kBlock / 64];
+    const uint64_t first = (uint64_t)blockIdx.x * kPlanRoots + threadIdx.x * 4u;
+    int64_t len[4];
+    const int64_t mine = plan_roots(p, n, idx, displs, plan, first, len);
+    int64_t before = plan_scan(mine, wave_sum);
     if (threadIdx.x == kBlock - 1) plan.totals[blockIdx.x] = before + mine;
 #pragma unroll
     for (int c = 0; c < 4; ++c) {
@@ -844,6 +858,36 @@ __global__ __launch_bounds__(kBlock) void k_pack_plan_local(uint32_t p, uint32_t
         if (j < p) plan.offsets[j] = before;
         before += len[c];
     }
+}
+
+// The whole plan in one workgroup, for the few thousand processes of the paper's runs: one launch instead
+// of three (a round is launch-latency bound at those sizes).
+constexpr uint32_t kPlanOneMaxP = 8 * kPlanRoots;
+
+__global__ __launch_bounds__(kBlock) void k_pack_plan_one(uint32_t p, uint32_t n, const int32_t *__restrict__ idx,
+                                                          const int64_t *__restrict__ displs, PackPlan plan) {
+    __shared__ int64_t wave_sum[kBlock / 64];
+    __shared__ int64_t carry_s;
+    if (threadIdx.x == 0) carry_s = 0;
+    __syncthreads();
+    for (uint64_t base = 0; base < p; base += kPlanRoots) {
+        const uint64_t first = base + threadIdx.x * 4u;
+        int64_t len[4];
+        const int64_t mine = plan_roots(p, n, idx, displs, plan, first, len);
+        const int64_t carry = carry_s;
+        int64_t before = carry + plan_scan(mine, wave_sum);
+        const int64_t end = before + mine;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const uint64_t j = first + c;
+            if (j < p) plan.offsets[j] = before;
+            before += len[c];
+        }
+        __syncthreads();                                            // everyone has read carry_s and wave_sum
+        if (threadIdx.x == kBlock - 1) carry_s = end;
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) plan.offsets[p] = carry_s;
 }
 
 // one workgroup: exclusive scan of the workgroup totals in place; the grand total goes to offsets[p]
@@ -1532,9 +1576,15 @@ int pack_plan(int32_t p, int32_t n, const int32_t *idx, const int64_t *displs, i
     plan.offsets = offsets;
     plan.src = (int64_t *)workspace;
     plan.totals = plan.src + p;
-    launch(kPackPlan, k_pack_plan_local, dim3(groups), dim3(kBlock), st, (uint32_t)p, (uint32_t)n, idx, displs, plan);
-    launch(kPackPlan, k_pack_plan_totals, dim3(1), dim3(kBlock), st, (uint32_t)p, groups, plan);
-    launch(kPackPlan, k_pack_plan_finish, dim3(((unsigned)p + kBlock - 1) / kBlock), dim3(kBlock), st, (uint32_t)p, plan);
+    if ((uint32_t)p <= kPlanOneMaxP) {
+        launch(kPackPlan, k_pack_plan_one, dim3(1), dim3(kBlock), st, (uint32_t)p, (uint32_t)n, idx, displs, plan);
+    } else {
+        launch(kPackPlan, k_pack_plan_local, dim3(groups), dim3(kBlock), st, (uint32_t)p, (uint32_t)n, idx, displs,
+               plan);
+        launch(kPackPlan, k_pack_plan_totals, dim3(1), dim3(kBlock), st, (uint32_t)p, groups, plan);
+        launch(kPackPlan, k_pack_plan_finish, dim3(((unsigned)p + kBlock - 1) / kBlock), dim3(kBlock), st, (uint32_t)p,
+               plan);
+    }
     hipError_t e = hipGetLastError();
     return e == hipSuccess ? BCS_OK : hip_fail(e);
 }
