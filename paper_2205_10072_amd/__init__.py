@@ -18,6 +18,7 @@ MAX_Q = 31
 BATCH_STRIDE = 32
 BATCH_PAD = -(2 ** 31)
 NO_BLOCK = -1
+MAX_N = 2**31 - 1 - 64          # BCS_MAX_N
 
 # every symbol include/bcsched.h declares
 SYMBOLS = (

@@ -285,6 +285,32 @@ def test_tables_of_more_than_2_to_32_entries(bcs, oracle):
     torch.cuda.empty_cache()
 
 
+def test_expand_largest_n(bcs, oracle):
+    """n = BCS_MAX_N (2^31 - 65): rounds and blocks at the top of int32, rows of 8.6 GB, checked on the device
+    against the index arithmetic of Alg. 6 piece by piece (p = 2: the entry-by-entry kernel; p = 5: the staged one)."""
+    n = bcs.MAX_N
+    for p, both in [(2, True), (5, False)]:
+        q, R = bcs.bcs_q(p), bcs.bcs_rounds(p, n)
+        assert R == n - 1 + q and R < 2**31
+        orecv, osend = oracle.sched_range(p)
+        x = (q - R % q) % q
+        for table in ([orecv, osend] if both else [orecv]):
+            sched = torch.from_numpy(table).cuda()
+            blocks = torch.full((p, R), 4242, dtype=torch.int32, device="cuda")
+            bcs.bcs_expand(p, n, 0, p, sched, None, blocks, None)
+            torch.cuda.synchronize()
+            step = 1 << 27
+            for j0 in range(0, R, step):
+                j = torch.arange(j0, min(R, j0 + step), device="cuda", dtype=torch.int64)
+                k = (x + j) % q
+                want = (sched.long()[:, k] + (j - k)).clamp_(min=-1, max=n - 1).to(torch.int32)
+                assert torch.equal(blocks[:, j0:j0 + step], want), (p, j0)
+                del want, j, k
+            assert int(blocks[:, -1].max()) == n - 1
+            del blocks
+            torch.cuda.empty_cache()
+
+
 def test_irregular_batch(bcs, oracle):
     """Config 5: 2^20 seeded (p, r, root) triples, p log-uniform up to 2^31 - 1."""
     from paper_2205_10072_amd import synth
