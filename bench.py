@@ -32,8 +32,8 @@ INT_VALU_PEAK_GOPS = 256 * 4 * 16 * 2.4     # CUs x SIMDs x lanes x GHz = 39 321
 # HBM bytes per launch at this workload, from the rocprofv3 counter runs summarised in
 # profiles/bench_c2_kernels.md (FETCH_SIZE scaled x2.0, WRITE_SIZE x1.0 by the 1 GiB copy calibration).
 PROFILED_TRAFFIC_BYTES = {
-    "k_expand": (2 * 53089 + 1130922) * 1024,
-    "k_recv_uniform": (2 * 51 + 107521) * 1024,
+    "k_expand": (2 * 53080 + 1131015) * 1024,
+    "k_recv_uniform": (2 * 47 + 107521) * 1024,
     "k_send_lookup": (2 * 15894 + 86016) * 1024,
 }
 
