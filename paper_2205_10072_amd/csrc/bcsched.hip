@@ -96,6 +96,28 @@ __device__ __forceinline__ void stage_lowtab(uint32_t *dst, int shape) {
     for (int i = threadIdx.x; i < kLowShapeBytes / 4; i += kBlock) dst[i] = src[i];
 }
 
+// Rows of a workgroup's LDS tile (row stride Q | 1) to their place in a rank-major table.  For odd Q the tile is
+// already laid out like the table, so it leaves as 16-byte pieces with no index arithmetic.
+template <int Q>
+__device__ __forceinline__ void tile_to_rows(const int32_t *tile, uint32_t rows, int32_t *__restrict__ dst) {
+    constexpr int kStride = Q | 1;
+    const uint32_t n = rows * Q;
+    if constexpr (kStride == Q) {
+        if ((reinterpret_cast<uintptr_t>(dst) & 15u) == 0) {
+            const uint32_t n4 = n >> 2;
+            for (uint32_t g = threadIdx.x; g < n4; g += kBlock)
+                reinterpret_cast<v4i *>(dst)[g] = reinterpret_cast<const v4i *>(tile)[g];
+            const uint32_t e = (n4 << 2) + threadIdx.x;
+            if (e < n) dst[e] = tile[e];
+            return;
+        }
+    }
+    for (uint32_t e = threadIdx.x; e < n; e += kBlock) {
+        const uint32_t row = e / Q, col = e - row * Q;
+        dst[e] = tile[row * kStride + col];
+    }
+}
+
 // ----------------------------------------------------------------------------------------------
 // K1: receive rows of ranks [r0, r1), uniform p.  Lane = rank.  Rows are staged in LDS (odd stride,
 // conflict-free) and leave as contiguous dwords; optionally each entry is also stored slot-major
@@ -106,7 +128,7 @@ __global__ __launch_bounds__(kBlock) void k_recv_uniform(const SkipTab tab, uint
                                                          int32_t *__restrict__ recv_out,
                                                          slot_t *__restrict__ recvT, uint64_t ldT) {
     constexpr int kStride = Q | 1;
-    __shared__ int32_t tile[kBlock * kStride];
+    __shared__ __align__(16) int32_t tile[kBlock * kStride];
     __shared__ uint32_t lowtab[kLowShapeBytes / 4];
     Uniform<Q> pol;
 #pragma unroll
@@ -130,12 +152,7 @@ __global__ __launch_bounds__(kBlock) void k_recv_uniform(const SkipTab tab, uint
     if (!recv_out) return;
     __syncthreads();
     const uint64_t rows = (count - first) < (uint64_t)kBlock ? (count - first) : (uint64_t)kBlock;
-    const uint32_t n = (uint32_t)rows * Q;
-    int32_t *dst = recv_out + first * Q;
-    for (uint32_t e = threadIdx.x; e < n; e += kBlock) {
-        const uint32_t row = e / Q, col = e - row * Q;
-        dst[e] = tile[row * kStride + col];
-    }
+    tile_to_rows<Q>(tile, (uint32_t)rows, recv_out + first * Q);
 }
 
 // K2: send rows from the slot-major receive table of ALL ranks (Alg. 9, second loop):
@@ -144,7 +161,7 @@ template <int Q>
 __global__ __launch_bounds__(kBlock) void k_send_lookup(const SkipTab tab, const slot_t *__restrict__ recvT,
                                                         uint64_t ldT, int32_t *__restrict__ send_out) {
     constexpr int kStride = Q | 1;
-    __shared__ int32_t tile[kBlock * kStride];
+    __shared__ __align__(16) int32_t tile[kBlock * kStride];
     const uint32_t p = tab.s[Q];
     const uint64_t first = (uint64_t)blockIdx.x * kBlock;
     const uint64_t idx = first + threadIdx.x;
@@ -160,12 +177,7 @@ __global__ __launch_bounds__(kBlock) void k_send_lookup(const SkipTab tab, const
     }
     __syncthreads();
     const uint64_t rows = ((uint64_t)p - first) < (uint64_t)kBlock ? ((uint64_t)p - first) : (uint64_t)kBlock;
-    const uint32_t n = (uint32_t)rows * Q;
-    int32_t *dst = send_out + first * Q;
-    for (uint32_t e = threadIdx.x; e < n; e += kBlock) {
-        const uint32_t row = e / Q, col = e - row * Q;
-        dst[e] = tile[row * kStride + col];
-    }
+    tile_to_rows<Q>(tile, (uint32_t)rows, send_out + first * Q);
 }
 
 // K1b: send rows of ranks [r0, r1) with no neighbour rows at hand (Alg. 5): entry i is entry i of the
@@ -174,7 +186,7 @@ template <int Q>
 __global__ __launch_bounds__(kBlock) void k_send_recompute(const SkipTab tab, uint32_t root, uint32_t r0, uint32_t r1,
                                                            int32_t *__restrict__ send_out) {
     constexpr int kStride = Q | 1;
-    __shared__ int32_t tile[kBlock * kStride];
+    __shared__ __align__(16) int32_t tile[kBlock * kStride];
     __shared__ uint32_t lowtab[kLowShapeBytes / 4];
     Uniform<Q> pol;
 #pragma unroll
@@ -201,12 +213,7 @@ __global__ __launch_bounds__(kBlock) void k_send_recompute(const SkipTab tab, ui
     }
     __syncthreads();
     const uint64_t rows = (count - first) < (uint64_t)kBlock ? (count - first) : (uint64_t)kBlock;
-    const uint32_t n = (uint32_t)rows * Q;
-    int32_t *dst = send_out + first * Q;
-    for (uint32_t e = threadIdx.x; e < n; e += kBlock) {
-        const uint32_t row = e / Q, col = e - row * Q;
-        dst[e] = tile[row * kStride + col];
-    }
+    tile_to_rows<Q>(tile, (uint32_t)rows, send_out + first * Q);
 }
 
 // K3: unrelated (p, r, root) triples; rows of BCS_BATCH_STRIDE ints (one 128-byte line each), padded.
