@@ -132,13 +132,15 @@ def bench_allgather_tables(torch, bcs, args):
         "metric": "allgather pack/unpack index tables of one process, GB/s written vs HBM peak",
         "value": nbytes / (ms_per_step * 1e-3) / 1e9, "unit": "GB/s",
         "n_gpus": 1, "steps": steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "ms_per_step_with_kernel_events": ms_per_step_events,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int32", "data": "synthetic",
         "config": {"workload": "p=2^20+1 processes, n=%d blocks per buffer, process %d: receive schedules of all "
                                "ranks (slot-major), then 2 tables of %d rounds x p roots" % (N_BLOCKS, AG_PROCESS, R),
                    "p": P, "q": q, "n": N_BLOCKS, "rounds": R},
         "roofline": {"kernel": "k_allgather_tables", "bound": "hbm", "achieved": nbytes / avg_ms / 1e6,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": nbytes / avg_ms / 1e6 / HBM_PEAK_GBS,
-                     "traffic": None, "avg_ms": avg_ms},
+                     # from profiles/allgather_tables_p1048577_n256.md (FETCH_SIZE x2.0, WRITE_SIZE x1.0)
+                     "traffic": (2 * 41280 + 2261412) * 1024, "avg_ms": avg_ms},
         "kernels_ms": {k: v[0] / v[1] for k, v in timing.items()},
     }
     if not args.no_cpu_baseline:
