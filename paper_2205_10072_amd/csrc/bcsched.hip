@@ -1443,7 +1443,11 @@ int bcs_sched_expand_ws(int32_t p, int32_t root, int32_t n, int32_t *recv_out, i
 
 int bcs_sched_expand(int32_t p, int32_t root, int32_t n, int32_t *recv_out, int32_t *send_out, int32_t *recv_blocks,
                      int32_t *send_blocks, void *stream) {
-    if (p < 1) return BCS_EINVAL;
+    if (p < 1 || root < 0 || root >= p || n < 1 || n > BCS_MAX_N) return BCS_EINVAL;
+    if ((uint64_t)n - 1 + host_q(p) > 0) {         // nothing is required of an empty result
+        if (!recv_blocks || !send_blocks) return BCS_EINVAL;
+        if (p > 1 && (!recv_out || !send_out)) return BCS_EINVAL;
+    }
     const int64_t need = bcs_sched_workspace_bytes(p, 0, p, 1);
     void *ws = nullptr;
     if (need > 0) {

@@ -38,7 +38,7 @@ def test_host_helpers_and_argument_checks(oracle):
         assert L.bcs_sched_rooted_ws(p, root, r0, r1, fake, fake, None, 0, None) == bcs.EINVAL
     assert L.bcs_sched(5, 0, 5, None, None, None) == bcs.EINVAL
     assert L.bcs_sched_rooted_ws(5, 0, 0, 5, fake, fake, None, 0, None) == bcs.ENOMEM
-    assert L.bcs_sched_workspace_bytes(5, 0, 5, 1) == 3 * 64 * 4
+    assert L.bcs_sched_workspace_bytes(5, 0, 5, 1) == 3 * 256        # q rows of one byte an entry, padded to 256
     assert L.bcs_sched_workspace_bytes(5, 0, 4, 1) == 0 and L.bcs_sched_workspace_bytes(5, 0, 5, 0) == 0
     assert L.bcs_sched_workspace_bytes(5, 0, 6, 1) == bcs.EINVAL
     assert L.bcs_sched_batch(-1, fake, fake, fake, fake, fake, fake, None) == bcs.EINVAL
@@ -47,6 +47,16 @@ def test_host_helpers_and_argument_checks(oracle):
     assert L.bcs_expand(5, 0, 0, 5, fake, fake, fake, fake, None) == bcs.EINVAL
     assert L.bcs_expand(5, 3, 0, 5, fake, None, None, fake, None) == bcs.EINVAL
     assert L.bcs_expand(5, 3, 0, 5, None, None, None, None, None) == bcs.EINVAL
+    for p, root, n in [(0, 0, 3), (5, 5, 3), (5, -1, 3), (5, 0, 0), (5, 0, 2**31 - 1)]:
+        assert L.bcs_sched_expand(p, root, n, fake, fake, fake, fake, None) == bcs.EINVAL
+        assert L.bcs_sched_expand_ws(p, root, n, fake, fake, fake, fake, None, 0, None) == bcs.EINVAL
+    assert L.bcs_sched_expand(5, 0, 3, None, fake, fake, fake, None) == bcs.EINVAL
+    assert L.bcs_sched_expand(5, 0, 3, fake, fake, fake, None, None) == bcs.EINVAL
+    assert L.bcs_sched_expand_ws(5, 0, 3, fake, fake, fake, fake, None, 0, None) == bcs.ENOMEM
+    assert L.bcs_sched_expand(1, 0, 1, None, None, None, None, None) == bcs.OK      # nothing to write
+    for p, n, r in [(0, 3, 0), (5, 0, 0), (5, 3, 5), (5, 3, -1)]:
+        assert L.bcs_allgather_tables(p, n, r, fake, fake, None) == bcs.EINVAL
+    assert L.bcs_allgather_tables(5, 3, 0, None, None, None) == bcs.EINVAL
     # p = 1 and empty ranges succeed without touching the device
     assert L.bcs_sched(1, 0, 1, fake, fake, None) == bcs.OK
     assert L.bcs_sched(9, 4, 4, fake, fake, None) == bcs.OK
