@@ -32,9 +32,9 @@ INT_VALU_PEAK_GOPS = 256 * 4 * 16 * 2.4     # CUs x SIMDs x lanes x GHz = 39 321
 # HBM bytes per launch at this workload, from the rocprofv3 counter runs summarised in
 # profiles/bench_c2_kernels.md (FETCH_SIZE scaled x2.0, WRITE_SIZE x1.0 by the 1 GiB copy calibration).
 PROFILED_TRAFFIC_BYTES = {
-    "k_expand": (2 * 53080 + 1131015) * 1024,
-    "k_recv_uniform": (2 * 47 + 107521) * 1024,
-    "k_send_lookup": (2 * 15894 + 86016) * 1024,
+    "k_expand_rows": (2 * 35344 + 1130579) * 1024,
+    "k_recv_uniform": (2 * 56 + 132098) * 1024,
+    "k_send_lookup": (2 * 15919 + 110592) * 1024,
 }
 
 
@@ -366,11 +366,11 @@ def main():
     send = torch.empty((P, q), dtype=torch.int32, device="cuda")
     rb = torch.empty((P, R), dtype=torch.int32, device="cuda")
     sb = torch.empty((P, R), dtype=torch.int32, device="cuda")
-    ws = torch.empty(bcs.bcs_sched_workspace_bytes(P, 0, P), dtype=torch.uint8, device="cuda")
+    ws = torch.empty(bcs.bcs_sched_expand_workspace_bytes(P, N_BLOCKS), dtype=torch.uint8, device="cuda")
 
     def step():
-        bcs.bcs_sched_rooted_ws(P, ROOT_RANK, 0, P, recv, send, ws)
-        bcs.bcs_expand(P, N_BLOCKS, 0, P, recv, send, rb, sb)
+        # one call: receive rows, send rows by look-up, both block tables
+        bcs.bcs_sched_expand_ws(P, ROOT_RANK, N_BLOCKS, recv, send, rb, sb, ws)
 
     for _ in range(args.warmup):
         step()
@@ -409,11 +409,11 @@ def main():
     for name, (ms, cnt) in timing.items():
         avg_ms = ms / cnt
         ent = {"launches_per_step": cnt / steps, "avg_ms": avg_ms, "ms_per_step": ms / steps}
-        if name == "k_expand":
+        if name in ("k_expand", "k_expand_rows"):
             nbytes = P * R * 4                                  # one table per launch, written once
             ent.update(bound="hbm", achieved=nbytes / avg_ms / 1e6, peak=HBM_PEAK_GBS, unit="GB/s")
         elif name == "k_send_lookup":
-            nbytes = P * q * (1 + 4)                            # read the one-byte slot-major entries, write one table
+            nbytes = P * q * (1 + 4) + P * 24                   # read the slot-major bytes, write one table and its byte rows
             ent.update(bound="hbm", achieved=nbytes / avg_ms / 1e6, peak=HBM_PEAK_GBS, unit="GB/s")
         elif name == "k_recv_uniform":
             ops = valu_ops_per_rank(q) * P
@@ -437,7 +437,7 @@ def main():
         "dtype": "int32", "data": "synthetic",
         "config": {"workload": "p=2^20+1 (q=21), all ranks, root 0: recv+send schedules, then expansion n=%d "
                                "(R=%d rounds)" % (N_BLOCKS, R), "p": P, "q": q, "n": N_BLOCKS, "rounds": R},
-        "expand_gbs": kernels["k_expand"]["achieved"],
+        "expand_gbs": kernels["k_expand_rows"]["achieved"],
         "construct_rank_schedules_per_s": P / ((kernels["k_recv_uniform"]["ms_per_step"]
                                                  + kernels["k_send_lookup"]["ms_per_step"]) * 1e-3),
         "roofline": roofline,

@@ -139,11 +139,18 @@ int bcs_expand(int32_t p, int32_t n, int32_t r0, int32_t r1,
  *   recv_out, send_out: device, p x q int32 (required when q > 0).
  *   recv_blocks, send_blocks: device, p x R int32, R = n-1+q (required when
  *   R > 0; p = 1 with n = 1 has nothing to write and returns BCS_OK).
- * Scratch: bcs_sched_workspace_bytes(p, 0, p, 1) bytes; the plain call uses the
- * per-device allocation, the _ws call takes it from the caller and allocates
- * nothing.  p = 1: both block tables get n-1 columns of BCS_NO_BLOCK.
+ * For longer rows the schedule kernels also leave the rows as bytes in scratch
+ * memory, which the expansion then reads from cache instead of re-reading the
+ * int32 tables.
+ * Scratch: bcs_sched_expand_workspace_bytes(p, n) bytes (negative: BCS_EINVAL);
+ * the plain call uses the per-device allocation, the _ws call takes it from the
+ * caller (256-byte aligned) and allocates nothing.  With less than that but at
+ * least bcs_sched_workspace_bytes(p, 0, p, 1) bytes the _ws call still works
+ * (without the byte rows).  p = 1: both block tables get n-1 columns of
+ * BCS_NO_BLOCK.
  * BCS_EINVAL: p < 1, root outside [0, p), n < 1, n > BCS_MAX_N, a required
  * table NULL.  BCS_ENOMEM: workspace NULL or too small. */
+int64_t bcs_sched_expand_workspace_bytes(int32_t p, int32_t n);
 int bcs_sched_expand(int32_t p, int32_t root, int32_t n,
                      int32_t *recv_out, int32_t *send_out,
                      int32_t *recv_blocks, int32_t *send_blocks, void *stream);
@@ -234,7 +241,7 @@ int bcs_release(void);
  * 0..BCS_KERNEL_COUNT-1, the summed duration in milliseconds and the number
  * of timed launches into host arrays of BCS_KERNEL_COUNT entries.  Not
  * thread-safe; meant for one measuring thread. */
-#define BCS_KERNEL_COUNT         12
+#define BCS_KERNEL_COUNT         13
 #define BCS_TIMING_MAX_LAUNCHES  4096
 int bcs_timing_begin(void);
 int bcs_timing_end(double *ms_sum_host, int64_t *launches_host);

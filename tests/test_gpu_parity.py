@@ -280,6 +280,19 @@ def test_tables_of_more_than_2_to_32_entries(bcs, oracle):
     assert np.array_equal(send.cpu().numpy(), osend)
     _check_blocks_on_device(p, n, recv, rb, oracle, orecv, seed=1)
     _check_blocks_on_device(p, n, send, sb, oracle, osend, seed=2)
+    del rb, sb
+    n = 200                                                           # expansion from byte rows, R = 225
+    R = bcs.bcs_rounds(p, n)
+    rb = torch.full((p, R), 4242, dtype=torch.int32, device="cuda")
+    sb = torch.full((p, R), 4242, dtype=torch.int32, device="cuda")
+    recv.fill_(777)
+    send.fill_(777)
+    bcs.bcs_sched_expand(p, root, n, recv, send, rb, sb)
+    torch.cuda.synchronize()
+    assert np.array_equal(recv.cpu().numpy(), orecv)
+    assert np.array_equal(send.cpu().numpy(), osend)
+    _check_blocks_on_device(p, n, recv, rb, oracle, orecv, seed=3)
+    _check_blocks_on_device(p, n, send, sb, oracle, osend, seed=4)
     del recv, send, rb, sb
     bcs.bcs_release()
     torch.cuda.empty_cache()
@@ -405,16 +418,24 @@ def test_bench_step_configuration(bcs, oracle):
     recv, send = dev_tables(p, q)
     rb = torch.full((p, R), 4242, dtype=torch.int32, device="cuda")
     sb = torch.full((p, R), 4242, dtype=torch.int32, device="cuda")
-    ws = torch.empty(bcs.bcs_sched_workspace_bytes(p, 0, p), dtype=torch.uint8, device="cuda")
+    ws = torch.empty(bcs.bcs_sched_expand_workspace_bytes(p, n), dtype=torch.uint8, device="cuda")
     for _ in range(2):                                    # twice: scratch and tables are reused across steps
-        bcs.bcs_sched_rooted_ws(p, 0, 0, p, recv, send, ws)
-        bcs.bcs_expand(p, n, 0, p, recv, send, rb, sb)
+        bcs.bcs_sched_expand_ws(p, 0, n, recv, send, rb, sb, ws)
     torch.cuda.synchronize()
     orecv, osend = oracle.sched_range(p, threads=16)
+    oracle_rb, oracle_sb = oracle.expand(p, n, orecv, threads=16), oracle.expand(p, n, osend, threads=16)
     assert np.array_equal(recv.cpu().numpy(), orecv)
     assert np.array_equal(send.cpu().numpy(), osend)
-    assert np.array_equal(rb.cpu().numpy(), oracle.expand(p, n, orecv, threads=16))
-    assert np.array_equal(sb.cpu().numpy(), oracle.expand(p, n, osend, threads=16))
+    assert np.array_equal(rb.cpu().numpy(), oracle_rb)
+    assert np.array_equal(sb.cpu().numpy(), oracle_sb)
+    # the same step by the separate calls
+    rb.fill_(4242)
+    sb.fill_(4242)
+    bcs.bcs_sched_rooted_ws(p, 0, 0, p, recv, send, ws)
+    bcs.bcs_expand(p, n, 0, p, recv, send, rb, sb)
+    torch.cuda.synchronize()
+    assert np.array_equal(rb.cpu().numpy(), oracle_rb)
+    assert np.array_equal(sb.cpu().numpy(), oracle_sb)
 
 
 def _sched_expand_case(bcs, oracle, p, n, root, own_ws=False, misalign=False):
@@ -425,8 +446,9 @@ def _sched_expand_case(bcs, oracle, p, n, root, own_ws=False, misalign=False):
     off = 1 if misalign else 0                          # one int32 off a 16-byte boundary
     rb, sb = (t[off:off + p * R].view(p, R) for t in flat)
     args = (p, root, n, recv if q else None, send if q else None, rb, sb)
-    if own_ws:
-        ws = torch.empty(max(1, bcs.bcs_sched_workspace_bytes(p, 0, p)), dtype=torch.uint8, device="cuda")
+    if own_ws:                                          # "small": enough for the schedules, not for the byte rows
+        size = bcs.bcs_sched_workspace_bytes(p, 0, p) if own_ws == "small" else bcs.bcs_sched_expand_workspace_bytes(p, n)
+        ws = torch.empty(max(1, size), dtype=torch.uint8, device="cuda")
         bcs.bcs_sched_expand_ws(*args, ws)
     else:
         bcs.bcs_sched_expand(*args)
@@ -446,7 +468,7 @@ def _sched_expand_case(bcs, oracle, p, n, root, own_ws=False, misalign=False):
 def test_sched_expand_one_call(bcs, oracle):
     """bcs_sched_expand: schedules and both block tables of all ranks in one call.  Short rows are expanded by
     the workgroup that built them (every q from 3 to 23 here; larger q would need more than 2^23 ranks at
-    once), other sizes take the separate kernels; both are compared in full with the oracle."""
+    once), longer rows from byte rows kept in scratch memory, the rest by the separate kernels; all compared in full."""
     rng = np.random.default_rng(2205)
     for q in range(3, 22):                              # fused: R = n-1+q <= 96
         p = (1 << (q - 1)) + 1 + int(rng.integers(0, 1 << (q - 1)))
@@ -458,8 +480,12 @@ def test_sched_expand_one_call(bcs, oracle):
                        (1000, 37, 123), (65536, 145, 9), (70001, 130, 70000), (65535, 81, 3)]:
         _sched_expand_case(bcs, oracle, p, n, root)     # fused, tiles with ragged tails, both length classes
     for p, n, root in [(1, 1, 0), (1, 9, 0), (2, 40, 1), (3, 20, 2), (4, 33, 0), (9, 3, 8), (1000, 5, 1),
-                       (1000, 200, 999), (4097, 100, 5), (65535, 145, 9), (70000, 1000, 7)]:
-        _sched_expand_case(bcs, oracle, p, n, root, own_ws=(p % 2 == 0))    # the separate kernels
+                       (1000, 200, 999), (4097, 100, 5), (65535, 145, 9), (70000, 1000, 7), (5, 700, 2), (33, 14, 32),
+                       (1025, 641, 1024), (300001, 160, 7)]:
+        # longer rows: expansion from the byte rows the schedule kernels leave behind (plain call, caller's
+        # workspace of the full size), or the separate kernels (a workspace that only holds the schedules' scratch)
+        for own_ws in (False, True, "small"):
+            _sched_expand_case(bcs, oracle, p, n, root, own_ws=own_ws)
     _sched_expand_case(bcs, oracle, 1000, 37, 123, misalign=True)
     _sched_expand_case(bcs, oracle, 70001, 130, 1, own_ws=True, misalign=True)
     with pytest.raises(bcs.BcsError):
