@@ -522,7 +522,8 @@ __global__ __launch_bounds__(kBlock) void k_expand(const ExpandArgs a, const int
 // resolves row and round of its four entries by itself (exact division by R: multiply-high and one correction),
 // reads the four bytes at its slot and the four at slot x of the next row -- those serve the entries past the end
 // of its row -- and stores 16 bytes.  Measured on MI355X: 0.159 ms a table at the bench size against 0.181 ms
-// for k_expand; short workgroups dispatched in address order are what the memory system likes best.
+// for k_expand; short workgroups dispatched in address order are what the memory system likes best.  Streaming
+// stores for every row length (plain stores were 1.3 times slower from 640 rounds up).
 struct ExpandRowsArgs {
     uint64_t total;                       // rows * R
     uint64_t magic_R64;                   // floor(2^64 / R) + 1
@@ -1541,14 +1542,19 @@ int bcs_expand(int32_t p, int32_t n, int32_t r0, int32_t r1, const int32_t *recv
 namespace {
 // bytes of one rank-major byte table (p rows and one spare that the last row's lanes may read)
 inline uint64_t byte_rows_bytes(int32_t p, int q) { return round_up(((uint64_t)p + 1) * byte_row_stride(q), 256); }
-inline bool byte_rows_apply(int q, uint64_t R) { return q >= (int)kExpMinQ && R >= kExpMinR; }
+// The byte rows pay while a table of them stays in cache (measured: 25 MB at p = 2^20+1 gives 0.83-0.93 of the
+// separate kernels' time for every row length, 50 MB at p = 2^21+1 gives 1.08-1.2).
+constexpr uint64_t kByteRowsMax = 32ull << 20;
+inline bool byte_rows_apply(int32_t p, int q, uint64_t R) {
+    return q >= (int)kExpMinQ && R >= kExpMinR && byte_rows_bytes(p, q) <= kByteRowsMax;
+}
 }  // namespace
 
 int64_t bcs_sched_expand_workspace_bytes(int32_t p, int32_t n) {
     if (p < 1 || n < 1 || n > BCS_MAX_N) return BCS_EINVAL;
     const int q = host_q(p);
     const int64_t base = bcs_sched_workspace_bytes(p, 0, p, 1);
-    if (!byte_rows_apply(q, (uint64_t)n - 1 + q)) return base;
+    if (!byte_rows_apply(p, q, (uint64_t)n - 1 + q)) return base;
     return base + (int64_t)(2 * byte_rows_bytes(p, q));
 }
 
@@ -1565,7 +1571,7 @@ int bcs_sched_expand_ws(int32_t p, int32_t root, int32_t n, int32_t *recv_out, i
     if (!use_fused(p, q, R, aligned)) {
         const int64_t base = q > 0 ? bcs_sched_workspace_bytes(p, 0, p, 1) : 0;
         const uint64_t rows_bytes = q > 0 ? byte_rows_bytes(p, q) : 0;
-        if (byte_rows_apply(q, R) && aligned && workspace && workspace_bytes >= (size_t)base + 2 * rows_bytes) {
+        if (byte_rows_apply(p, q, R) && aligned && workspace && workspace_bytes >= (size_t)base + 2 * rows_bytes) {
             // long rows: the schedule kernels also leave byte rows, which the expansion then reads from cache
             SkipTab tab;
             host_skips(p, tab);
@@ -1590,12 +1596,8 @@ int bcs_sched_expand_ws(int32_t p, int32_t root, int32_t n, int32_t *recv_out, i
             int32_t *outs[2] = {recv_blocks, send_blocks};
             const int8_t *srcs[2] = {recvB, sendB};
             for (int t = 0; t < 2; ++t) {
-                if (R <= kExpNtMaxR)
-                    launch(kExpandRows, k_expand_rows<true>, dim3((unsigned)pieces), dim3(kBlock), (hipStream_t)stream, ra,
-                           srcs[t], outs[t]);
-                else
-                    launch(kExpandRows, k_expand_rows<false>, dim3((unsigned)pieces), dim3(kBlock), (hipStream_t)stream,
-                           ra, srcs[t], outs[t]);
+                launch(kExpandRows, k_expand_rows<true>, dim3((unsigned)pieces), dim3(kBlock), (hipStream_t)stream, ra,
+                       srcs[t], outs[t]);
             }
             hipError_t e = hipGetLastError();
             return e == hipSuccess ? BCS_OK : hip_fail(e);

@@ -280,15 +280,17 @@ def test_tables_of_more_than_2_to_32_entries(bcs, oracle):
     assert np.array_equal(send.cpu().numpy(), osend)
     _check_blocks_on_device(p, n, recv, rb, oracle, orecv, seed=1)
     _check_blocks_on_device(p, n, send, sb, oracle, osend, seed=2)
-    del rb, sb
-    n = 200                                                           # expansion from byte rows, R = 225
-    R = bcs.bcs_rounds(p, n)
+    del recv, send, rb, sb, orecv, osend
+    torch.cuda.empty_cache()
+    p, n, root = 1300001, 3400, 1234567                               # expansion from byte rows, R = 3421
+    q, R = bcs.bcs_q(p), bcs.bcs_rounds(p, n)
+    assert p * R > 1 << 32 and bcs.bcs_sched_expand_workspace_bytes(p, n) > bcs.bcs_sched_workspace_bytes(p, 0, p)
+    recv, send = dev_tables(p, q)
     rb = torch.full((p, R), 4242, dtype=torch.int32, device="cuda")
     sb = torch.full((p, R), 4242, dtype=torch.int32, device="cuda")
-    recv.fill_(777)
-    send.fill_(777)
     bcs.bcs_sched_expand(p, root, n, recv, send, rb, sb)
     torch.cuda.synchronize()
+    orecv, osend = oracle.sched_range(p, root=root, threads=16)
     assert np.array_equal(recv.cpu().numpy(), orecv)
     assert np.array_equal(send.cpu().numpy(), osend)
     _check_blocks_on_device(p, n, recv, rb, oracle, orecv, seed=3)
