@@ -533,7 +533,6 @@ struct ExpandRowsArgs {
     int32_t nm1;
 };
 
-template <bool NT>
 __global__ __launch_bounds__(kBlock) void k_expand_rows(const ExpandRowsArgs a, const int8_t *__restrict__ rowsB,
                                                         int32_t *__restrict__ out) {
     const uint64_t e = ((uint64_t)blockIdx.x * kBlock + threadIdx.x) * 4u;
@@ -576,8 +575,7 @@ __global__ __launch_bounds__(kBlock) void k_expand_rows(const ExpandRowsArgs a, 
     }
     if (e + 4 <= a.total) {
         const v4i pack = {v[0], v[1], v[2], v[3]};
-        if constexpr (NT) __builtin_nontemporal_store(pack, reinterpret_cast<v4i *>(out + e));
-        else *reinterpret_cast<v4i *>(out + e) = pack;
+        __builtin_nontemporal_store(pack, reinterpret_cast<v4i *>(out + e));
     } else {
 #pragma unroll
         for (int c = 0; c < 4; ++c)
@@ -1596,7 +1594,7 @@ int bcs_sched_expand_ws(int32_t p, int32_t root, int32_t n, int32_t *recv_out, i
             int32_t *outs[2] = {recv_blocks, send_blocks};
             const int8_t *srcs[2] = {recvB, sendB};
             for (int t = 0; t < 2; ++t) {
-                launch(kExpandRows, k_expand_rows<true>, dim3((unsigned)pieces), dim3(kBlock), (hipStream_t)stream, ra,
+                launch(kExpandRows, k_expand_rows, dim3((unsigned)pieces), dim3(kBlock), (hipStream_t)stream, ra,
                        srcs[t], outs[t]);
             }
             hipError_t e = hipGetLastError();
