@@ -224,6 +224,12 @@ def bench_configs(torch, bcs, args):
     ms = sum(k.values())
     res["C4 expand p=65537 n=4096"] = {"ms": ms, "kernels_ms": k, "written_GBps": 2 * p * R * 4 / ms / 1e6,
                                       "frac_of_hbm_peak": 2 * p * R * 4 / ms / 1e6 / HBM_PEAK_GBS}
+    ws = torch.empty(bcs.bcs_expand_workspace_bytes(p, n, 0, p), dtype=torch.uint8, device="cuda")
+    k = kernels(lambda: bcs.bcs_expand_ws(p, n, 0, p, recv, send, rb, sb, ws))
+    ms = sum(k.values())
+    res["C4 expand p=65537 n=4096, with workspace"] = {"ms": ms, "kernels_ms": k, "written_GBps": 2 * p * R * 4 / ms / 1e6,
+                                                      "frac_of_hbm_peak": 2 * p * R * 4 / ms / 1e6 / HBM_PEAK_GBS}
+    del ws
     del rb, sb
     # C5: 2^20 seeded triples, mixed q
     count = 1 << 20

@@ -130,6 +130,21 @@ int bcs_expand(int32_t p, int32_t n, int32_t r0, int32_t r1,
                const int32_t *recv, const int32_t *send,
                int32_t *recv_blocks, int32_t *send_blocks, void *stream);
 
+/* bcs_expand with scratch memory from the caller: for rows of 256 rounds or more
+ * (and tables of up to about a million rows) the schedule rows are first
+ * rewritten as bytes into `workspace`, which stays in cache, and the tables are
+ * expanded from there; results are those of bcs_expand, bit for bit.
+ *   workspace: device, 16-byte aligned, bcs_expand_workspace_bytes(p, n, r0, r1)
+ *   bytes (0 when the detour does not pay; negative: BCS_EINVAL); its contents
+ *   are undefined afterwards.  With less, or with outputs that are not 16-byte
+ *   aligned, the call is bcs_expand.  Performs no allocation.
+ * Errors as bcs_expand. */
+int64_t bcs_expand_workspace_bytes(int32_t p, int32_t n, int32_t r0, int32_t r1);
+int bcs_expand_ws(int32_t p, int32_t n, int32_t r0, int32_t r1,
+                  const int32_t *recv, const int32_t *send,
+                  int32_t *recv_blocks, int32_t *send_blocks,
+                  void *workspace, size_t workspace_bytes, void *stream);
+
 /* Schedules of all p ranks and both of their (rank, round) -> block tables in
  * one call: the same results as bcs_sched_rooted_ws(p, root, 0, p, ...) followed
  * by bcs_expand(p, n, 0, p, ...) (Alg. 4, Alg. 9's send look-up, index arithmetic
@@ -241,7 +256,7 @@ int bcs_release(void);
  * 0..BCS_KERNEL_COUNT-1, the summed duration in milliseconds and the number
  * of timed launches into host arrays of BCS_KERNEL_COUNT entries.  Not
  * thread-safe; meant for one measuring thread. */
-#define BCS_KERNEL_COUNT         13
+#define BCS_KERNEL_COUNT         14
 #define BCS_TIMING_MAX_LAUNCHES  4096
 int bcs_timing_begin(void);
 int bcs_timing_end(double *ms_sum_host, int64_t *launches_host);

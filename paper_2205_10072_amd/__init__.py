@@ -24,13 +24,13 @@ MAX_N = 2**31 - 1 - 64          # BCS_MAX_N
 SYMBOLS = (
     "bcs_q", "bcs_skips", "bcs_rounds", "bcs_sched", "bcs_sched_rooted", "bcs_sched_workspace_bytes",
     "bcs_sched_rooted_ws", "bcs_sched_batch", "bcs_expand", "bcs_sched_expand", "bcs_sched_expand_ws",
-    "bcs_sched_expand_workspace_bytes",
+    "bcs_sched_expand_workspace_bytes", "bcs_expand_ws", "bcs_expand_workspace_bytes",
     "bcs_release", "bcs_strerror",
     "bcs_last_hip_error", "bcs_timing_begin", "bcs_timing_end", "bcs_kernel_name", "bcs_valu_peak_launch",
     "bcs_allgather_workspace_bytes", "bcs_allgather_tables", "bcs_allgather_tables_ws",
     "bcs_pack_workspace_bytes", "bcs_pack_round", "bcs_unpack_round", "bcs_allgather_plan", "bcs_census_plan",
 )
-KERNEL_COUNT = 13
+KERNEL_COUNT = 14
 VALU_PEAK_OPS_PER_ITER = 32
 
 _lib = None
@@ -66,6 +66,9 @@ def lib():
     L.bcs_sched_rooted_ws.argtypes = [i32, i32, i32, i32, vp, vp, vp, sz, vp]
     L.bcs_sched_batch.argtypes = [i64, vp, vp, vp, vp, vp, vp, vp]
     L.bcs_expand.argtypes = [i32, i32, i32, i32, vp, vp, vp, vp, vp]
+    L.bcs_expand_workspace_bytes.argtypes = [i32, i32, i32, i32]
+    L.bcs_expand_workspace_bytes.restype = i64
+    L.bcs_expand_ws.argtypes = [i32, i32, i32, i32, vp, vp, vp, vp, vp, sz, vp]
     L.bcs_sched_expand_workspace_bytes.argtypes = [i32, i32]
     L.bcs_sched_expand_workspace_bytes.restype = i64
     L.bcs_sched_expand.argtypes = [i32, i32, i32, vp, vp, vp, vp, vp]
@@ -169,6 +172,18 @@ def bcs_sched_batch(p, r, root, recv_out, send_out, q_out, stream=None):
 def bcs_expand(p, n, r0, r1, recv, send, recv_blocks, send_blocks, stream=None):
     _check(lib().bcs_expand(p, n, r0, r1, _ptr(recv), _ptr(send), _ptr(recv_blocks), _ptr(send_blocks),
                             _stream(stream)), "bcs_expand")
+
+
+def bcs_expand_workspace_bytes(p, n, r0, r1):
+    return _check(lib().bcs_expand_workspace_bytes(p, n, r0, r1), "bcs_expand_workspace_bytes")
+
+
+def bcs_expand_ws(p, n, r0, r1, recv, send, recv_blocks, send_blocks, workspace, stream=None):
+    """`workspace`: a device tensor of any dtype (or None)."""
+    wp = ctypes.c_void_p(workspace.data_ptr()) if workspace is not None and workspace.numel() else None
+    wb = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    _check(lib().bcs_expand_ws(p, n, r0, r1, _ptr(recv), _ptr(send), _ptr(recv_blocks), _ptr(send_blocks), wp, wb,
+                               _stream(stream)), "bcs_expand_ws")
 
 
 def bcs_sched_expand_workspace_bytes(p, n):

@@ -23,6 +23,9 @@ typedef int8_t slot_t;
 // Rank-major byte rows for the expansion of long rows (scratch as well): row r holds T[k] = entry[k] - k for the q
 // slots, then T[0..2] once more, padded to a multiple of 4 bytes.  T lies in [-2q, q), q <= 31.
 constexpr int byte_row_stride(int q) { return (q + 3 + 3) & ~3; }
+// The byte rows pay while a table of them stays in cache (measured: 25 MB at p = 2^20+1 gives 0.83-0.93 of the
+// separate kernels' time for every row length, 50 MB at p = 2^21+1 gives 1.08-1.2).
+constexpr uint64_t kByteRowsMax = 32ull << 20;
 static_assert(kMaxQ == BCS_MAX_Q, "header and core disagree");
 constexpr int kBlock = 256;              // lanes (= ranks) per workgroup
 
@@ -37,13 +40,13 @@ inline int hip_fail(hipError_t e) {
 // given a start and a stop event from a fixed pool, so its duration is the device's own.
 enum KernelId {
     kRecv = 0, kSendLookup, kSendRecompute, kBatch, kExpand, kFill, kValuPeak, kAllgather, kPackPlan, kPackCopy,
-    kRecvExpand, kSendExpand, kExpandRows, kKernelCount
+    kRecvExpand, kSendExpand, kExpandRows, kRowsToBytes, kKernelCount
 };
 static_assert(kKernelCount == BCS_KERNEL_COUNT, "header and kernel list disagree");
 const char *const kKernelNames[kKernelCount] = {"k_recv_uniform", "k_send_lookup", "k_send_recompute", "k_batch",
                                                 "k_expand",       "k_fill",        "k_valu_peak",   "k_allgather_tables",
                                                 "k_pack_plan",    "k_pack_copy",   "k_recv_expand", "k_send_expand",
-                                                "k_expand_rows"};
+                                                "k_expand_rows",  "k_rows_to_bytes"};
 struct Timing {
     bool on = false;
     int used = 0;
@@ -581,6 +584,29 @@ __global__ __launch_bounds__(kBlock) void k_expand_rows(const ExpandRowsArgs a, 
         for (int c = 0; c < 4; ++c)
             if (e + c < a.total) out[e + c] = v[c];
     }
+}
+
+// int32 schedule rows -> byte rows (for an expansion whose tables come from the caller): one dword of four
+// packed bytes a lane.  Byte tables are at most kByteRowsMax bytes, so 32-bit indices do.
+__global__ __launch_bounds__(kBlock) void k_rows_to_bytes(uint32_t rows, uint32_t q, uint32_t RS, uint32_t magic_w4,
+                                                          const int32_t *__restrict__ in, int8_t *__restrict__ rowsB) {
+    const uint32_t w4 = RS >> 2;                                    // dwords per byte row
+    const uint32_t g = blockIdx.x * kBlock + threadIdx.x;
+    if (g >= rows * w4) return;
+    uint32_t row = __umulhi(g, magic_w4);                           // exact or one too large
+    int32_t w = (int32_t)(g - row * w4);
+    if (w < 0) { w += (int32_t)w4; --row; }
+    const int32_t *src = in + (uint64_t)row * q;
+    uint32_t packed = 0;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+        const uint32_t pos = 4u * (uint32_t)w + c;
+        const bool slot_ok = pos < q + 3u;                          // the row's slots and its three mirrors
+        const uint32_t slot = pos < q ? pos : (slot_ok ? pos - q : 0u);
+        const int32_t t = slot_ok ? src[slot] - (int32_t)slot : 0;
+        packed |= ((uint32_t)t & 0xffu) << (8 * c);
+    }
+    reinterpret_cast<uint32_t *>(rowsB)[g] = packed;
 }
 
 // ----------------------------------------------------------------------------------------------
@@ -1540,13 +1566,73 @@ int bcs_expand(int32_t p, int32_t n, int32_t r0, int32_t r1, const int32_t *recv
 namespace {
 // bytes of one rank-major byte table (p rows and one spare that the last row's lanes may read)
 inline uint64_t byte_rows_bytes(int32_t p, int q) { return round_up(((uint64_t)p + 1) * byte_row_stride(q), 256); }
-// The byte rows pay while a table of them stays in cache (measured: 25 MB at p = 2^20+1 gives 0.83-0.93 of the
-// separate kernels' time for every row length, 50 MB at p = 2^21+1 gives 1.08-1.2).
-constexpr uint64_t kByteRowsMax = 32ull << 20;
 inline bool byte_rows_apply(int32_t p, int q, uint64_t R) {
     return q >= (int)kExpMinQ && R >= kExpMinR && byte_rows_bytes(p, q) <= kByteRowsMax;
 }
 }  // namespace
+
+namespace {
+// rows of the caller's tables from which an expansion through byte rows pays: the conversion is one more
+// pass over the table and one more launch
+constexpr uint64_t kExpandWsMinR = 256;
+inline bool expand_ws_applies(int32_t rows, int q, uint64_t R) {
+    return q >= (int)kExpMinQ && R >= kExpandWsMinR && rows > 0 && byte_rows_bytes(rows, q) <= kByteRowsMax;
+}
+
+ExpandRowsArgs expand_rows_args(uint64_t rows, uint64_t R, int q, int32_t n) {
+    ExpandRowsArgs ra;
+    ra.total = rows * R;
+    ra.magic_R64 = ~0ull / R + 1ull;
+    ra.magic_R32 = (uint32_t)((1ull << 32) / R + 1ull);
+    ra.magic_q = (uint32_t)((1ull << 32) / (uint64_t)q + 1ull);
+    ra.R = (uint32_t)R;
+    ra.q = (uint32_t)q;
+    ra.x = (uint32_t)((q - (int)(R % (uint64_t)q)) % q);
+    ra.RS = (uint32_t)byte_row_stride(q);
+    ra.nm1 = n - 1;
+    return ra;
+}
+}  // namespace
+
+int64_t bcs_expand_workspace_bytes(int32_t p, int32_t n, int32_t r0, int32_t r1) {
+    if (check_range(p, 0, r0, r1) != BCS_OK || n < 1 || n > BCS_MAX_N) return BCS_EINVAL;
+    const int q = host_q(p);
+    if (!expand_ws_applies(r1 - r0, q, (uint64_t)n - 1 + q)) return 0;
+    return (int64_t)byte_rows_bytes(r1 - r0, q);
+}
+
+int bcs_expand_ws(int32_t p, int32_t n, int32_t r0, int32_t r1, const int32_t *recv, const int32_t *send,
+                  int32_t *recv_blocks, int32_t *send_blocks, void *workspace, size_t workspace_bytes, void *stream) {
+    if (check_range(p, 0, r0, r1) != BCS_OK || n < 1 || n > BCS_MAX_N) return BCS_EINVAL;
+    const int q = host_q(p);
+    const uint64_t R = (uint64_t)n - 1 + q;
+    const int64_t need = bcs_expand_workspace_bytes(p, n, r0, r1);
+    const bool aligned = ((recv_blocks ? (uintptr_t)recv_blocks : 0) | (send_blocks ? (uintptr_t)send_blocks : 0)) % 16 == 0;
+    const bool tables_ok = (recv == nullptr) == (recv_blocks == nullptr) && (send == nullptr) == (send_blocks == nullptr) &&
+                           (recv || send);
+    if (need <= 0 || !aligned || !tables_ok || !workspace || workspace_bytes < (size_t)need ||
+        (((uintptr_t)workspace) & 15u))
+        return bcs_expand(p, n, r0, r1, recv, send, recv_blocks, send_blocks, stream);
+    hipStream_t st = (hipStream_t)stream;
+    const uint32_t rows = (uint32_t)(r1 - r0);
+    const ExpandRowsArgs ra = expand_rows_args(rows, R, q, n);
+    const uint64_t pieces = (ra.total + kBlock * 4 - 1) / (kBlock * 4);
+    if (pieces > 0x7fffffffull) return BCS_EINVAL;
+    const uint32_t w4 = ra.RS / 4;
+    const uint32_t conv_blocks = (rows * w4 + kBlock - 1) / kBlock;
+    const int32_t *ins[2] = {recv, send};
+    int32_t *outs[2] = {recv_blocks, send_blocks};
+    for (int t = 0; t < 2; ++t) {
+        if (!ins[t]) continue;
+        // the one workspace serves both tables in turn (same stream: the second conversion follows the first expansion)
+        launch(kRowsToBytes, k_rows_to_bytes, dim3(conv_blocks), dim3(kBlock), st, rows, (uint32_t)q, ra.RS,
+               (uint32_t)((1ull << 32) / w4 + 1ull), ins[t], (int8_t *)workspace);
+        launch(kExpandRows, k_expand_rows, dim3((unsigned)pieces), dim3(kBlock), st, ra, (const int8_t *)workspace,
+               outs[t]);
+    }
+    hipError_t e = hipGetLastError();
+    return e == hipSuccess ? BCS_OK : hip_fail(e);
+}
 
 int64_t bcs_sched_expand_workspace_bytes(int32_t p, int32_t n) {
     if (p < 1 || n < 1 || n > BCS_MAX_N) return BCS_EINVAL;
@@ -1575,16 +1661,7 @@ int bcs_sched_expand_ws(int32_t p, int32_t root, int32_t n, int32_t *recv_out, i
             host_skips(p, tab);
             int rc = ensure_lowtab((hipStream_t)stream);
             if (rc != BCS_OK) return rc;
-            ExpandRowsArgs ra;
-            ra.total = (uint64_t)p * R;
-            ra.magic_R64 = ~0ull / R + 1ull;
-            ra.magic_R32 = (uint32_t)((1ull << 32) / R + 1ull);
-            ra.magic_q = (uint32_t)((1ull << 32) / (uint64_t)q + 1ull);
-            ra.R = (uint32_t)R;
-            ra.q = (uint32_t)q;
-            ra.x = (uint32_t)((q - (int)(R % (uint64_t)q)) % q);
-            ra.RS = (uint32_t)byte_row_stride(q);
-            ra.nm1 = n - 1;
+            const ExpandRowsArgs ra = expand_rows_args((uint64_t)p, R, q, n);
             const uint64_t pieces = (ra.total + kBlock * 4 - 1) / (kBlock * 4);
             if (pieces > 0x7fffffffull) return BCS_EINVAL;
             int8_t *recvB = (int8_t *)workspace + base, *sendB = recvB + rows_bytes;

@@ -215,6 +215,31 @@ def test_expand_p65537_n4096(bcs, oracle):
     assert np.array_equal(sb.cpu().numpy(), oracle.expand(p, n, osend))
 
 
+def test_expand_with_workspace(bcs, oracle):
+    """bcs_expand_ws: the caller's tables rewritten as byte rows in the workspace, then expanded from there; the
+    same results as bcs_expand whatever path the sizes take."""
+    for p, n, r0, r1 in [(65537, 4096, 0, 65537), (65537, 300, 1000, 50001), (5, 700, 0, 5), (1000, 247, 0, 1000),
+                         (1000, 246, 3, 999), (33, 251, 0, 33), (4097, 521, 4000, 4097), (1048577, 256, 0, 1048577),
+                         (9, 3, 0, 9), (2, 400, 0, 2)]:
+        q, R = bcs.bcs_q(p), bcs.bcs_rounds(p, n)
+        orecv, osend = oracle.sched_range(p, r0=r0, r1=r1, threads=16)
+        recv, send = torch.from_numpy(orecv).cuda(), torch.from_numpy(osend).cuda()
+        want_r, want_s = oracle.expand(p, n, orecv, threads=16), oracle.expand(p, n, osend, threads=16)
+        need = bcs.bcs_expand_workspace_bytes(p, n, r0, r1)
+        assert (need > 0) == (q >= 3 and R >= 256), (p, n)
+        for ws_bytes, both in [(need, True), (need, False), (max(0, need - 16), True)]:
+            ws = torch.empty(max(16, ws_bytes), dtype=torch.uint8, device="cuda")[:ws_bytes]
+            rb, sb = dev_tables(r1 - r0, R, fill=4242)
+            bcs.bcs_expand_ws(p, n, r0, r1, recv, send if both else None, rb, sb if both else None, ws)
+            torch.cuda.synchronize()
+            assert np.array_equal(rb.cpu().numpy(), want_r), (p, n, r0, r1, ws_bytes, both)
+            if both:
+                assert np.array_equal(sb.cpu().numpy(), want_s), (p, n, r0, r1, ws_bytes)
+            else:
+                assert bool((sb == 4242).all())
+            del rb, sb
+
+
 def test_expand_small_and_ragged(bcs, oracle):
     for p, n in [(1, 1), (1, 5), (2, 1), (2, 7), (3, 2), (9, 4), (20, 1), (20, 6), (33, 12), (33, 300), (1000, 37),
                  (4097, 1), (4097, 521)]:

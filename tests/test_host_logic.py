@@ -47,6 +47,14 @@ def test_host_helpers_and_argument_checks(oracle):
     assert L.bcs_expand(5, 0, 0, 5, fake, fake, fake, fake, None) == bcs.EINVAL
     assert L.bcs_expand(5, 3, 0, 5, fake, None, None, fake, None) == bcs.EINVAL
     assert L.bcs_expand(5, 3, 0, 5, None, None, None, None, None) == bcs.EINVAL
+    assert L.bcs_expand_ws(5, 0, 0, 5, fake, fake, fake, fake, None, 0, None) == bcs.EINVAL
+    assert L.bcs_expand_ws(5, 3, 0, 6, fake, fake, fake, fake, None, 0, None) == bcs.EINVAL
+    assert L.bcs_expand_ws(5, 300, 0, 5, None, None, None, None, fake, 1 << 20, None) == bcs.EINVAL
+    assert L.bcs_expand_workspace_bytes(5, 300, 0, 5) == 256         # 6 rows of 12 bytes, padded
+    assert L.bcs_expand_workspace_bytes(5, 30, 0, 5) == 0 and L.bcs_expand_workspace_bytes(2, 300, 0, 2) == 0
+    assert L.bcs_expand_workspace_bytes(5, 0, 0, 5) == bcs.EINVAL
+    assert L.bcs_sched_expand_workspace_bytes(5, 300) == 3 * 256 + 2 * 256
+    assert L.bcs_sched_expand_workspace_bytes(5, 3) == 3 * 256
     for p, root, n in [(0, 0, 3), (5, 5, 3), (5, -1, 3), (5, 0, 0), (5, 0, 2**31 - 1)]:
         assert L.bcs_sched_expand(p, root, n, fake, fake, fake, fake, None) == bcs.EINVAL
         assert L.bcs_sched_expand_ws(p, root, n, fake, fake, fake, fake, None, 0, None) == bcs.EINVAL
