@@ -131,8 +131,8 @@ int bcs_expand(int32_t p, int32_t n, int32_t r0, int32_t r1,
                int32_t *recv_blocks, int32_t *send_blocks, void *stream);
 
 /* bcs_expand with scratch memory from the caller: for rows of 256 rounds or more
- * (and tables of up to about a million rows) the schedule rows are first
- * rewritten as bytes into `workspace`, which stays in cache, and the tables are
+ * the schedule rows are first rewritten as bytes into `workspace` (about a
+ * million rows at a time, so that it stays in cache) and the tables are
  * expanded from there; results are those of bcs_expand, bit for bit.
  *   workspace: device, 16-byte aligned, bcs_expand_workspace_bytes(p, n, r0, r1)
  *   bytes (0 when the detour does not pay; negative: BCS_EINVAL); its contents

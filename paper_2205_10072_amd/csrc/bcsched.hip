@@ -1576,7 +1576,13 @@ namespace {
 // pass over the table and one more launch
 constexpr uint64_t kExpandWsMinR = 256;
 inline bool expand_ws_applies(int32_t rows, int q, uint64_t R) {
-    return q >= (int)kExpMinQ && R >= kExpandWsMinR && rows > 0 && byte_rows_bytes(rows, q) <= kByteRowsMax;
+    return q >= (int)kExpMinQ && R >= kExpandWsMinR && rows > 0;
+}
+// rows converted and expanded at a time: their byte table fits kByteRowsMax; a multiple of 4, so that every
+// chunk's piece of the output starts on a 16-byte boundary
+inline uint32_t expand_ws_chunk_rows(uint32_t rows, int q) {
+    const uint32_t fit = (uint32_t)(kByteRowsMax / (uint64_t)byte_row_stride(q) - 1) & ~3u;
+    return rows < fit ? rows : fit;
 }
 
 ExpandRowsArgs expand_rows_args(uint64_t rows, uint64_t R, int q, int32_t n) {
@@ -1598,7 +1604,7 @@ int64_t bcs_expand_workspace_bytes(int32_t p, int32_t n, int32_t r0, int32_t r1)
     if (check_range(p, 0, r0, r1) != BCS_OK || n < 1 || n > BCS_MAX_N) return BCS_EINVAL;
     const int q = host_q(p);
     if (!expand_ws_applies(r1 - r0, q, (uint64_t)n - 1 + q)) return 0;
-    return (int64_t)byte_rows_bytes(r1 - r0, q);
+    return (int64_t)byte_rows_bytes((int32_t)expand_ws_chunk_rows((uint32_t)(r1 - r0), q), q);
 }
 
 int bcs_expand_ws(int32_t p, int32_t n, int32_t r0, int32_t r1, const int32_t *recv, const int32_t *send,
@@ -1615,20 +1621,24 @@ int bcs_expand_ws(int32_t p, int32_t n, int32_t r0, int32_t r1, const int32_t *r
         return bcs_expand(p, n, r0, r1, recv, send, recv_blocks, send_blocks, stream);
     hipStream_t st = (hipStream_t)stream;
     const uint32_t rows = (uint32_t)(r1 - r0);
-    const ExpandRowsArgs ra = expand_rows_args(rows, R, q, n);
-    const uint64_t pieces = (ra.total + kBlock * 4 - 1) / (kBlock * 4);
-    if (pieces > 0x7fffffffull) return BCS_EINVAL;
-    const uint32_t w4 = ra.RS / 4;
-    const uint32_t conv_blocks = (rows * w4 + kBlock - 1) / kBlock;
+    const uint32_t chunk = expand_ws_chunk_rows(rows, q);
+    const uint32_t RS = (uint32_t)byte_row_stride(q), w4 = RS / 4;
     const int32_t *ins[2] = {recv, send};
     int32_t *outs[2] = {recv_blocks, send_blocks};
+    // the one workspace serves every chunk of both tables in turn (same stream: a conversion follows the
+    // expansion that read the previous contents)
     for (int t = 0; t < 2; ++t) {
         if (!ins[t]) continue;
-        // the one workspace serves both tables in turn (same stream: the second conversion follows the first expansion)
-        launch(kRowsToBytes, k_rows_to_bytes, dim3(conv_blocks), dim3(kBlock), st, rows, (uint32_t)q, ra.RS,
-               (uint32_t)((1ull << 32) / w4 + 1ull), ins[t], (int8_t *)workspace);
-        launch(kExpandRows, k_expand_rows, dim3((unsigned)pieces), dim3(kBlock), st, ra, (const int8_t *)workspace,
-               outs[t]);
+        for (uint32_t c0 = 0; c0 < rows; c0 += chunk) {
+            const uint32_t rc = rows - c0 < chunk ? rows - c0 : chunk;
+            const ExpandRowsArgs ra = expand_rows_args(rc, R, q, n);
+            const uint64_t pieces = (ra.total + kBlock * 4 - 1) / (kBlock * 4);
+            if (pieces > 0x7fffffffull) return BCS_EINVAL;
+            launch(kRowsToBytes, k_rows_to_bytes, dim3((rc * w4 + kBlock - 1) / kBlock), dim3(kBlock), st, rc, (uint32_t)q,
+                   RS, (uint32_t)((1ull << 32) / w4 + 1ull), ins[t] + (uint64_t)c0 * q, (int8_t *)workspace);
+            launch(kExpandRows, k_expand_rows, dim3((unsigned)pieces), dim3(kBlock), st, ra, (const int8_t *)workspace,
+                   outs[t] + (uint64_t)c0 * R);
+        }
     }
     hipError_t e = hipGetLastError();
     return e == hipSuccess ? BCS_OK : hip_fail(e);
@@ -1638,8 +1648,10 @@ int64_t bcs_sched_expand_workspace_bytes(int32_t p, int32_t n) {
     if (p < 1 || n < 1 || n > BCS_MAX_N) return BCS_EINVAL;
     const int q = host_q(p);
     const int64_t base = bcs_sched_workspace_bytes(p, 0, p, 1);
-    if (!byte_rows_apply(p, q, (uint64_t)n - 1 + q)) return base;
-    return base + (int64_t)(2 * byte_rows_bytes(p, q));
+    if (byte_rows_apply(p, q, (uint64_t)n - 1 + q)) return base + (int64_t)(2 * byte_rows_bytes(p, q));
+    // too many ranks for byte tables that stay in cache: the tables are expanded chunk by chunk (bcs_expand_ws)
+    const int64_t extra = bcs_expand_workspace_bytes(p, n, 0, p);
+    return base + (extra > 0 ? extra : 0);
 }
 
 int bcs_sched_expand_ws(int32_t p, int32_t root, int32_t n, int32_t *recv_out, int32_t *send_out,
@@ -1681,7 +1693,10 @@ int bcs_sched_expand_ws(int32_t p, int32_t root, int32_t n, int32_t *recv_out, i
             const int rc = bcs_sched_rooted_ws(p, root, 0, p, recv_out, send_out, workspace, workspace_bytes, stream);
             if (rc != BCS_OK) return rc;
         }
-        return bcs_expand(p, n, 0, p, recv_out, send_out, recv_blocks, send_blocks, stream);
+        // what the workspace holds beyond the schedules' scratch serves the expansion (chunks of byte rows)
+        const bool more = workspace && workspace_bytes > (size_t)base;
+        return bcs_expand_ws(p, n, 0, p, recv_out, send_out, recv_blocks, send_blocks,
+                             more ? (char *)workspace + base : nullptr, more ? workspace_bytes - (size_t)base : 0, stream);
     }
     const int64_t need = bcs_sched_workspace_bytes(p, 0, p, 1);
     if (!workspace || workspace_bytes < (size_t)need) return BCS_ENOMEM;

@@ -220,7 +220,7 @@ def test_expand_with_workspace(bcs, oracle):
     same results as bcs_expand whatever path the sizes take."""
     for p, n, r0, r1 in [(65537, 4096, 0, 65537), (65537, 300, 1000, 50001), (5, 700, 0, 5), (1000, 247, 0, 1000),
                          (1000, 246, 3, 999), (33, 251, 0, 33), (4097, 521, 4000, 4097), (1048577, 256, 0, 1048577),
-                         (9, 3, 0, 9), (2, 400, 0, 2)]:
+                         (9, 3, 0, 9), (2, 400, 0, 2), ((1 << 22) + 1, 300, 5, (1 << 22) - 2)]:   # the last: three chunks
         q, R = bcs.bcs_q(p), bcs.bcs_rounds(p, n)
         orecv, osend = oracle.sched_range(p, r0=r0, r1=r1, threads=16)
         recv, send = torch.from_numpy(orecv).cuda(), torch.from_numpy(osend).cuda()
