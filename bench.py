@@ -282,14 +282,17 @@ def bench_pack_round(torch, bcs, args):
                                  c["ws"])
         for _ in range(warmup):
             step()
-        torch.cuda.synchronize()
-        bcs.bcs_timing_begin()
+        # a plain region for the time per round, then the same rounds with per-kernel events for the kernel times
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         for _ in range(steps):
             step()
         torch.cuda.synchronize()
         t1 = time.perf_counter()
+        bcs.bcs_timing_begin()
+        for _ in range(steps):
+            step()
+        torch.cuda.synchronize()
         timing = bcs.bcs_timing_end()
         return (t1 - t0) * 1e3 / steps, {k: v[0] / v[1] for k, v in timing.items()}
 
