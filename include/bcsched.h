@@ -130,7 +130,8 @@ int bcs_expand(int32_t p, int32_t n, int32_t r0, int32_t r1,
                const int32_t *recv, const int32_t *send,
                int32_t *recv_blocks, int32_t *send_blocks, void *stream);
 
-/* bcs_expand with scratch memory from the caller: for rows of 256 rounds or more
+/* bcs_expand (index arithmetic of Alg. 6 and its caption) with scratch memory
+ * from the caller: for rows of 256 rounds or more
  * the schedule rows are first rewritten as bytes into `workspace` (about a
  * million rows at a time, so that it stays in cache) and the tables are
  * expanded from there; results are those of bcs_expand, bit for bit.
