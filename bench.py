@@ -410,14 +410,15 @@ def main():
         step()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
-    timing = bcs.bcs_timing_end()
+    timing = bcs.bcs_timing_stats()
     ms_per_step_events = (t1 - t0) * 1e3 / steps
 
     # per-kernel rooflines from the device-side durations of the timed region
     kernels = {}
-    for name, (ms, cnt) in timing.items():
+    for name, (ms, cnt, shortest, longest) in timing.items():
         avg_ms = ms / cnt
-        ent = {"launches_per_step": cnt / steps, "avg_ms": avg_ms, "ms_per_step": ms / steps}
+        ent = {"launches_per_step": cnt / steps, "avg_ms": avg_ms, "min_ms": shortest, "max_ms": longest,
+               "ms_per_step": ms / steps}
         if name in ("k_expand", "k_expand_rows"):
             nbytes = P * R * 4                                  # one table per launch, written once
             ent.update(bound="hbm", achieved=nbytes / avg_ms / 1e6, peak=HBM_PEAK_GBS, unit="GB/s")

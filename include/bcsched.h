@@ -261,6 +261,9 @@ int bcs_release(void);
 #define BCS_TIMING_MAX_LAUNCHES  4096
 int bcs_timing_begin(void);
 int bcs_timing_end(double *ms_sum_host, int64_t *launches_host);
+/* bcs_timing_end that also gives the shortest and the longest timed launch of
+ * each kernel (arrays of BCS_KERNEL_COUNT doubles; either may be NULL). */
+int bcs_timing_stats(double *ms_sum_host, int64_t *launches_host, double *ms_min_host, double *ms_max_host);
 /* Name of kernel `id` as a profiler shows it (without template arguments). */
 const char *bcs_kernel_name(int id);
 

@@ -26,7 +26,7 @@ SYMBOLS = (
     "bcs_sched_rooted_ws", "bcs_sched_batch", "bcs_expand", "bcs_sched_expand", "bcs_sched_expand_ws",
     "bcs_sched_expand_workspace_bytes", "bcs_expand_ws", "bcs_expand_workspace_bytes",
     "bcs_release", "bcs_strerror",
-    "bcs_last_hip_error", "bcs_timing_begin", "bcs_timing_end", "bcs_kernel_name", "bcs_valu_peak_launch",
+    "bcs_last_hip_error", "bcs_timing_begin", "bcs_timing_end", "bcs_timing_stats", "bcs_kernel_name", "bcs_valu_peak_launch",
     "bcs_allgather_workspace_bytes", "bcs_allgather_tables", "bcs_allgather_tables_ws",
     "bcs_pack_workspace_bytes", "bcs_pack_round", "bcs_unpack_round", "bcs_allgather_plan", "bcs_census_plan",
 )
@@ -79,6 +79,7 @@ def lib():
     L.bcs_last_hip_error.argtypes = []
     L.bcs_timing_begin.argtypes = []
     L.bcs_timing_end.argtypes = [vp, vp]
+    L.bcs_timing_stats.argtypes = [vp, vp, vp, vp]
     L.bcs_kernel_name.argtypes = [ctypes.c_int]
     L.bcs_kernel_name.restype = ctypes.c_char_p
     L.bcs_valu_peak_launch.argtypes = [ctypes.c_uint32, ctypes.c_uint32, vp, vp]
@@ -218,6 +219,16 @@ def bcs_timing_end():
     _check(lib().bcs_timing_end(ctypes.cast(ms, ctypes.c_void_p), ctypes.cast(cnt, ctypes.c_void_p)),
            "bcs_timing_end")
     return {lib().bcs_kernel_name(i).decode(): (ms[i], cnt[i]) for i in range(KERNEL_COUNT) if cnt[i]}
+
+
+def bcs_timing_stats():
+    """{kernel name: (summed ms, timed launches, shortest ms, longest ms)} since bcs_timing_begin()."""
+    ms = (ctypes.c_double * KERNEL_COUNT)()
+    cnt = (ctypes.c_int64 * KERNEL_COUNT)()
+    lo = (ctypes.c_double * KERNEL_COUNT)()
+    hi = (ctypes.c_double * KERNEL_COUNT)()
+    _check(lib().bcs_timing_stats(*(ctypes.cast(a, ctypes.c_void_p) for a in (ms, cnt, lo, hi))), "bcs_timing_stats")
+    return {lib().bcs_kernel_name(i).decode(): (ms[i], cnt[i], lo[i], hi[i]) for i in range(KERNEL_COUNT) if cnt[i]}
 
 
 def bcs_valu_peak_launch(blocks, iters, sink, stream=None):

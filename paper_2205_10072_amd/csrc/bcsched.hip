@@ -1932,13 +1932,15 @@ int bcs_timing_begin(void) {
     return BCS_OK;
 }
 
-int bcs_timing_end(double *ms_sum, int64_t *launches) {
+int bcs_timing_stats(double *ms_sum, int64_t *launches, double *ms_min, double *ms_max) {
     Timing &t = g_timing;
     t.on = false;
     if (!ms_sum || !launches) return BCS_EINVAL;
     for (int k = 0; k < kKernelCount; ++k) {
         ms_sum[k] = 0.0;
         launches[k] = 0;
+        if (ms_min) ms_min[k] = 0.0;
+        if (ms_max) ms_max[k] = 0.0;
     }
     for (int i = 0; i < t.used; ++i) {
         hipError_t e = hipEventSynchronize(t.stop[i]);
@@ -1946,12 +1948,17 @@ int bcs_timing_end(double *ms_sum, int64_t *launches) {
         float ms = 0.f;
         e = hipEventElapsedTime(&ms, t.start[i], t.stop[i]);
         if (e != hipSuccess) return hip_fail(e);
-        ms_sum[t.kid[i]] += (double)ms;
-        launches[t.kid[i]] += 1;
+        const int k = t.kid[i];
+        if (ms_min && (launches[k] == 0 || (double)ms < ms_min[k])) ms_min[k] = (double)ms;
+        if (ms_max && (launches[k] == 0 || (double)ms > ms_max[k])) ms_max[k] = (double)ms;
+        ms_sum[k] += (double)ms;
+        launches[k] += 1;
     }
     t.used = 0;
     return BCS_OK;
 }
+
+int bcs_timing_end(double *ms_sum, int64_t *launches) { return bcs_timing_stats(ms_sum, launches, nullptr, nullptr); }
 
 const char *bcs_kernel_name(int id) { return (id >= 0 && id < kKernelCount) ? kKernelNames[id] : "?"; }
 
