@@ -525,6 +525,40 @@ def test_sched_expand_one_call(bcs, oracle):
         bcs.bcs_sched_expand_ws(1000, 0, 37, r, s, rb, sb, torch.empty(64, dtype=torch.uint8, device="cuda"))
 
 
+def test_sched_expand_random_sizes(bcs, oracle):
+    """Seeded random (p, n, root) through the one-call entry point and through bcs_expand_ws: whatever kernels the
+    sizes select, the four tables equal the oracle's."""
+    rng = np.random.default_rng(20220510)
+    for case in range(70):
+        p = int(2 ** rng.uniform(1, 18.2))
+        n = int(2 ** rng.uniform(0, 9.6))
+        root = int(rng.integers(0, p))
+        q, R = bcs.bcs_q(p), bcs.bcs_rounds(p, n)
+        orecv, osend = oracle.sched_range(p, root=root, threads=16)
+        want_r, want_s = oracle.expand(p, n, orecv, threads=16), oracle.expand(p, n, osend, threads=16)
+        recv, send = dev_tables(p, q)
+        rb, sb = dev_tables(p, R, fill=4242)
+        if case % 2:
+            bcs.bcs_sched_expand(p, root, n, recv, send, rb, sb)
+        else:
+            ws = torch.empty(max(1, bcs.bcs_sched_expand_workspace_bytes(p, n)), dtype=torch.uint8, device="cuda")
+            bcs.bcs_sched_expand_ws(p, root, n, recv, send, rb, sb, ws)
+        torch.cuda.synchronize()
+        tag = (p, n, root)
+        assert np.array_equal(recv.cpu().numpy(), orecv) and np.array_equal(send.cpu().numpy(), osend), tag
+        assert np.array_equal(rb.cpu().numpy(), want_r) and np.array_equal(sb.cpu().numpy(), want_s), tag
+        # a ragged range of the same tables through bcs_expand_ws
+        r0 = int(rng.integers(0, p))
+        r1 = int(rng.integers(r0, p + 1))
+        if r1 > r0:
+            ws = torch.empty(max(16, bcs.bcs_expand_workspace_bytes(p, n, r0, r1)), dtype=torch.uint8, device="cuda")
+            rb2, sb2 = dev_tables(r1 - r0, R, fill=4242)
+            bcs.bcs_expand_ws(p, n, r0, r1, recv[r0:r1], send[r0:r1], rb2, sb2, ws)
+            torch.cuda.synchronize()
+            assert np.array_equal(rb2.cpu().numpy(), want_r[r0:r1]) and np.array_equal(sb2.cpu().numpy(), want_s[r0:r1]), \
+                (tag, r0, r1)
+
+
 def _pack_case(rng, p, n, kind):
     if kind == "paper":
         from paper_2205_10072_amd import synth
