@@ -422,6 +422,25 @@ def test_allgather_tables_against_oracle(bcs, oracle):
         assert np.array_equal(unpack, ounpack) and (pack == 555).all()
 
 
+def test_allgather_tables_random_sizes(bcs, oracle):
+    """Seeded random (p, n, r), aligned and unaligned outputs, one table or both, against the oracle."""
+    rng = np.random.default_rng(9042)
+    for case in range(50):
+        p = int(2 ** rng.uniform(1, 16.5))
+        n = int(2 ** rng.uniform(0, 7.5))
+        r = int(rng.integers(0, p))
+        if p * bcs.bcs_rounds(p, n) > 3e7:
+            continue
+        opack, ounpack = oracle.allgather_tables(p, n, r)
+        which = case % 3
+        pack, unpack = gpu_allgather(bcs, p, n, r, want_pack=which != 1, want_unpack=which != 2,
+                                     misalign=bool(case % 2))
+        if which != 1:
+            assert np.array_equal(pack, opack), (p, n, r, case)
+        if which != 2:
+            assert np.array_equal(unpack, ounpack), (p, n, r, case)
+
+
 def test_allgather_tables_replayed_for_all_processes(bcs):
     """The GPU's own tables, one call per process, replayed as a whole allgather."""
     from allgather_sim import simulate_allgather
