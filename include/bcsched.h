@@ -34,6 +34,10 @@
  *     code object (baseblock sets of the seven lowest levels of the circulant
  *     graph).  Until that kernel has finished, calls on other streams are made
  *     to wait for it on the device; no call waits on the host.
+ *   - Calls that allocate nothing (the *_ws entry points, bcs_expand,
+ *     bcs_sched_batch) may be recorded into a HIP graph, once one schedule-
+ *     building call has been made on the device outside the capture (that first
+ *     call also queries an event).  They enqueue kernels only.
  */
 #ifndef BCSCHED_H
 #define BCSCHED_H
