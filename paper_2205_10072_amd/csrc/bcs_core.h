@@ -311,10 +311,10 @@ BCS_HD void recv_row(const Pol &pol, uint32_t v, int last, Emit emit) {
             U = need2 ? U2 : U;
         }
         const int blk = 31 - BCS_CLZ(U);                  // largest candidate
-        if (active) {
-            if (is_home) emit(i, own);
-            else { B |= 1u << (blk & 31); emit(i, blk - q); }
-        }
+        // one emit for both kinds of round, so that a wave with lanes of both kinds does not run it twice
+        const bool take = active && !is_home;
+        B |= take ? (1u << (blk & 31)) : 0u;
+        if (active) emit(i, is_home ? own : blk - q);
         d_hi = d_lo;
         s_i = s_n;
     }
