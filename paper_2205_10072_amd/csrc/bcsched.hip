@@ -173,7 +173,7 @@ __device__ __forceinline__ void tile_to_rows(const int32_t *tile, uint32_t rows,
 // conflict-free) and leave as contiguous dwords; optionally each entry is also stored slot-major
 // (recvT[k][r - r0]) for the send look-up that follows.
 // ----------------------------------------------------------------------------------------------
-template <int Q>
+template <int Q, bool BYTES>
 __global__ __launch_bounds__(kBlock) void k_recv_uniform(const SkipTab tab, uint32_t root, uint32_t r0, uint32_t r1,
                                                          int32_t *__restrict__ recv_out,
                                                          slot_t *__restrict__ recvT, uint64_t ldT,
@@ -181,7 +181,7 @@ __global__ __launch_bounds__(kBlock) void k_recv_uniform(const SkipTab tab, uint
     constexpr int kStride = Q | 1;
     constexpr int kRS = byte_row_stride(Q);
     __shared__ __align__(16) int32_t tile[kBlock * kStride];
-    __shared__ __align__(16) int8_t tileB[kBlock * kRS];
+    __shared__ __align__(16) int8_t tileB[BYTES ? kBlock * kRS : 16];   // only the variant that leaves byte rows pays for it
     __shared__ uint32_t lowtab[kLowShapeBytes / 4];
     Uniform<Q> pol;
 #pragma unroll
@@ -198,18 +198,18 @@ __global__ __launch_bounds__(kBlock) void k_recv_uniform(const SkipTab tab, uint
     const uint32_t r = live ? (uint32_t)(r0 + idx) : root;       // idle lanes replay the root (cheap, valid)
     const uint32_t v = r >= root ? r - root : r + p - root;
     int32_t *my = tile + threadIdx.x * kStride;
-    int8_t *myB = tileB + threadIdx.x * kRS;
+    int8_t *myB = tileB + (BYTES ? threadIdx.x * kRS : 0);
     recv_row(pol, v, Q - 1, [&](int i, int val) {
         my[i] = val;
         if (recvT && live) recvT[(uint64_t)i * ldT + idx] = (slot_t)val;
-        if (rowsB) myB[i] = (int8_t)(val - i);
+        if constexpr (BYTES) myB[i] = (int8_t)(val - i);
     });
     if (!recv_out) return;
-    if (rowsB) byte_row_finish<Q>(myB);
+    if constexpr (BYTES) byte_row_finish<Q>(myB);
     __syncthreads();
     const uint64_t rows = (count - first) < (uint64_t)kBlock ? (count - first) : (uint64_t)kBlock;
     tile_to_rows<Q>(tile, (uint32_t)rows, recv_out + first * Q);
-    if (rowsB) byte_rows_out<Q>(tileB, (uint32_t)rows, rowsB + first * kRS);
+    if constexpr (BYTES) byte_rows_out<Q>(tileB, (uint32_t)rows, rowsB + first * kRS);
 }
 
 // K2: send rows from the slot-major receive table of ALL ranks (Alg. 9, second loop):
@@ -1339,8 +1339,12 @@ int launch_sched(const SkipTab &tab, uint32_t root, uint32_t r0, uint32_t r1, in
     // the slot-major copy feeds the send look-up; with neither table asked for it is the only output
     const bool want_t = full && recvT && (send_out || !recv_out);
     if (recv_out || want_t) {
-        launch(kRecv, k_recv_uniform<Q>, dim3(blocks), dim3(kBlock), st, tab, root, r0, r1, recv_out,
-               want_t ? recvT : (slot_t *)nullptr, ldT, full ? recvB : (int8_t *)nullptr);
+        if (full && recvB && recv_out)
+            launch(kRecv, k_recv_uniform<Q, true>, dim3(blocks), dim3(kBlock), st, tab, root, r0, r1, recv_out,
+                   want_t ? recvT : (slot_t *)nullptr, ldT, recvB);
+        else
+            launch(kRecv, k_recv_uniform<Q, false>, dim3(blocks), dim3(kBlock), st, tab, root, r0, r1, recv_out,
+                   want_t ? recvT : (slot_t *)nullptr, ldT, (int8_t *)nullptr);
     }
     if (send_out) {
         if (full) {
