@@ -276,11 +276,19 @@ BCS_HD uint32_t window_blocks(const Pol &pol, uint32_t d_lo, uint32_t d_hi) {
 // instances of this rule.  End points are kept as v + p - skips[i] in [0, 2p): digits of the rank plus
 // a lap digit at level q, so that every window is an increasing pair.
 template <class Pol, class Emit>
+BCS_HD void recv_row_from(const Pol &pol, uint32_t v, uint32_t dv, int last, Emit emit);
+
+template <class Pol, class Emit>
 BCS_HD void recv_row(const Pol &pol, uint32_t v, int last, Emit emit) {
+    recv_row_from(pol, v, digits(pol, v), last, emit);
+}
+
+// recv_row for a caller that already has dv = digits(pol, v)
+template <class Pol, class Emit>
+BCS_HD void recv_row_from(const Pol &pol, uint32_t v, uint32_t dv, int last, Emit emit) {
     const uint32_t p = pol.p();
     const int q = pol.q();
     const uint32_t lap = 1u << (q & 31);
-    const uint32_t dv = digits(pol, v);
     const int home = 31 - BCS_CLZ(dv);                    // -1 for the root
     const int own = dv ? __builtin_ctz(dv) : 0;
     uint32_t B = v ? (1u << own) : 0u;

@@ -267,8 +267,17 @@ __global__ __launch_bounds__(kBlock) void k_send_recompute(const SkipTab tab, ui
     for (int i = 0; i < Q; ++i) {
         uint32_t t = v + tab.s[i];
         t = t >= p ? t - p : t;
-        int32_t keep = 0;
-        recv_row(pol, t, i, [&](int j, int val) { keep = (j == i) ? val : keep; });
+        const uint32_t dt = digits(pol, t);
+        int32_t keep = dt ? __builtin_ctz(dt) : 0;
+        // Round i is the neighbour's home round when its highest digit is i: then the entry is its baseblock and
+        // none of its earlier rounds matters.  A wave of consecutive ranks below skips[i+1] - skips[i] is in that
+        // case as a whole (half of all waves for the last slot, a quarter for the one before, ...).
+        const bool home_round = dt != 0u && (31 - __clz((int)dt)) == i;
+        if (__any(!home_round)) {
+            int32_t got = 0;
+            recv_row_from(pol, t, dt, i, [&](int j, int val) { got = (j == i) ? val : got; });
+            keep = got;
+        }
         my[i] = keep;
     }
     __syncthreads();
