@@ -58,10 +58,12 @@ constexpr int kMaxQ = 31;
 
 // Low-level table: kLowShapes shapes x kLowRows rows x 128 digit patterns, one byte (a 7-bit block
 // mask) each.  Shape: skips[7] - 65 when q >= 7, else 63 + p.  Row d < 25: tail of the level-7 pattern
-// cut short by d ranks; row 25 + k: tail of the level-k pattern, k <= 7.
+// cut short by d ranks; row 25 + k: tail of the level-k pattern, k <= 7; last row: the greedy digits of
+// the ranks below skips[7] (what the walk of Alg. 2 finds on its last seven levels).
 constexpr int kLowLevels = 7;
 constexpr int kLowShapes = 128;
-constexpr int kLowRows = 25 + kLowLevels + 1;
+constexpr int kLowDigitRow = 25 + kLowLevels + 1;   // row of the low digits themselves: entry y = digits of rank y < skips[7]
+constexpr int kLowRows = kLowDigitRow + 1;
 constexpr int kLowShapeBytes = kLowRows * 128;
 constexpr int kLowTableBytes = kLowShapes * kLowShapeBytes;
 
@@ -98,6 +100,7 @@ struct Uniform {
     BCS_HD const uint8_t *lowtab() const { return low; }
     BCS_HD int q() const { return Q; }
     BCS_HD int top() const { return Q - 1; }
+    static constexpr int kTopLevel = Q - 1;
     BCS_HD uint32_t p() const { return S[Q]; }
     BCS_HD uint32_t s(int k) const { return S[k]; }          // k constant after unrolling
     BCS_HD uint32_t sdyn(int k) const { return tab->s[k]; }  // k wave-uniform
@@ -168,6 +171,18 @@ BCS_HD uint32_t low_table_entry(int shape, int row, int low) {
     pol.low = nullptr;
     int k;
     uint32_t cut;
+    if (row == kLowDigitRow) {
+        uint32_t y = (uint32_t)low, d = 0;
+        if (y >= pp) return 0u;
+        for (int j = qq - 1; j >= 0; --j) {
+            const uint32_t sj = pol.s(j);
+            if (y >= sj) {
+                y -= sj;
+                d |= 1u << j;
+            }
+        }
+        return d;
+    }
     if (row < 25) {
         if (qq < kLowLevels) return 0u;
         k = kLowLevels;
@@ -196,8 +211,11 @@ BCS_HD uint32_t digits(const Pol &pol, uint32_t y) {
     // vcc and one that reads it, hence the s_nop.
     uint32_t inv = 0;
     if constexpr (Pol::kScalarSkips) {
+        // levels 7 and up by the walk; what is left is a rank below skips[7] <= 128, whose digits are read
+        // from the table's last row
+        constexpr int kHigh = Pol::kTopLevel + 1 > kLowLevels ? Pol::kTopLevel + 1 - kLowLevels : 0;
 #pragma unroll
-        for (int k = pol.top(); k >= 0; --k) {
+        for (int k = pol.top(); k >= kLowLevels; --k) {
             uint32_t t;
             asm("v_subrev_co_u32 %0, vcc, %3, %1\n\t"
                 "s_nop 1\n\t"
@@ -207,6 +225,9 @@ BCS_HD uint32_t digits(const Pol &pol, uint32_t y) {
                 : "s"(pol.s(k))
                 : "vcc");
         }
+        const uint32_t lowd = pol.lowtab()[kLowDigitRow * 128 + (int)y];
+        const uint32_t highd = kHigh > 0 ? (~inv & (0xffffffffu >> (32 - (kHigh > 0 ? kHigh : 1)))) : 0u;
+        return (highd << kLowLevels) | lowd;
     } else {
         // Per-lane p: the lane's own levels come first, whatever the wave's bound.  Step m handles level
         // q-1-m, whose skip is ((p-1) >> (m+1)) + 1 (Alg. 1's halving), so g = skip - 1 is one shift a
