@@ -234,7 +234,9 @@ BCS_HD uint32_t digits(const Pol &pol, uint32_t y) {
         // step and "y - g - 1 with borrow-out" (borrow-in forced to one) subtracts the skip: four vector
         // ops a level.  Steps past level 0 find y = 0 below a skip of 1 and change nothing; the digits
         // are moved down to their places at the end.
-        const int steps = pol.top() + 1;
+        // The walk stops seven levels short of the wave's bound: what is left of y is then below the lane's
+        // skips[7] (or is 0, for a lane with fewer levels than steps), and its digits come from the table.
+        const int steps = pol.top() + 1 > kLowLevels ? pol.top() + 1 - kLowLevels : 0;
         const uint64_t ones = ~0ull;
         uint32_t g = pol.pm1;
 #pragma unroll 1
@@ -249,7 +251,12 @@ BCS_HD uint32_t digits(const Pol &pol, uint32_t y) {
                 : "s"(ones)
                 : "vcc");
         }
-        return steps > 0 ? ((~inv & (0xffffffffu >> (32 - steps))) >> (steps - pol.ql)) : 0u;
+        const uint32_t walked = steps > 0 ? (~inv & (0xffffffffu >> (32 - steps))) : 0u;
+        const int left = pol.ql - steps;                   // levels the walk did not reach (at most seven)
+        // A lane whose own q is below the round the wave is in gets an inert skip and with it a y that is no
+        // rank at all: its result is never used, but its table index must stay inside the row.
+        const uint32_t lowd = pol.lowtab()[kLowDigitRow * 128 + (int)(y & 127u)];
+        return (left >= 0 ? walked << left : walked >> -left) | lowd;
     }
     const int levels = pol.top() + 1;
     return levels > 0 ? (~inv & (0xffffffffu >> (32 - levels))) : 0u;
