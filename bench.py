@@ -32,17 +32,18 @@ INT_VALU_PEAK_GOPS = 256 * 4 * 16 * 2.4     # CUs x SIMDs x lanes x GHz = 39 321
 # HBM bytes per launch at this workload, from the rocprofv3 counter runs summarised in
 # profiles/bench_c2_kernels.md (FETCH_SIZE scaled x2.0, WRITE_SIZE x1.0 by the 1 GiB copy calibration).
 PROFILED_TRAFFIC_BYTES = {
-    "k_expand_rows": (2 * 35344 + 1130579) * 1024,
-    "k_recv_uniform": (2 * 56 + 132098) * 1024,
-    "k_send_lookup": (2 * 15919 + 110592) * 1024,
+    "k_expand_rows": (2 * 35344 + 1130588) * 1024,
+    "k_recv_uniform": (2 * 51 + 132099) * 1024,
+    "k_send_lookup": (2 * 15914 + 110592) * 1024,
 }
 
 
 def valu_ops_per_rank(q):
     """Vector-ALU lane-operations one receive row costs on the main path of k_recv_uniform, counted from its
-    ISA: q+2 digit walks of 3 ops a level, 55 ops of window logic and bookkeeping a round, 50 of set-up.
+    ISA: q+2 digit walks of 3 ops a level for the levels from 7 up and 3 ops around the table read that stands
+    for the seven levels below, 55 ops of window logic and bookkeeping a round, 50 of set-up.
     The wave-uniform branch for Alg. 4's second range is extra work and not counted."""
-    return 3 * q * (q + 2) + 55 * q + 50
+    return (3 * max(q - 7, 0) + 3) * (q + 2) + 55 * q + 50
 
 
 def measure_valu_peak(torch, bcs):

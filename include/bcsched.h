@@ -30,7 +30,7 @@
  *     allocation must be ordered on one stream.
  *   - The first call on a device that builds schedules (bcs_sched*,
  *     bcs_sched_batch, bcs_allgather_tables*) also enqueues, ahead of its own
- *     work, a short kernel that fills a 528 KiB table kept in the library's
+ *     work, a short kernel that fills a 544 KiB table kept in the library's
  *     code object (baseblock sets of the seven lowest levels of the circulant
  *     graph).  Until that kernel has finished, calls on other streams are made
  *     to wait for it on the device; no call waits on the host.

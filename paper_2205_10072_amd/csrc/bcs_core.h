@@ -30,7 +30,8 @@
 //     odd levels passed and the seven low digits.  The table depends on skips[7] only (64 shapes;
 //     another 64 for p <= 64) and is filled by the level walk.
 // The windows of Alg. 4 share their end points (round i ends where round i+1 begins), so a row costs
-// q+1 digit masks (3 vector ops a level) and a few bit operations per round.
+// q+1 digit masks (3 vector ops a level down to level 7; the seven low digits of what is left are one
+// more row of the table) and a few bit operations per round.
 // All of it is branch-free apart from the wave-uniform test for Alg. 4's rare second range.
 #ifndef BCS_CORE_H
 #define BCS_CORE_H
@@ -261,14 +262,17 @@ BCS_HD uint32_t digits(const Pol &pol, uint32_t y) {
     const int levels = pol.top() + 1;
     return levels > 0 ? (~inv & (0xffffffffu >> (32 - levels))) : 0u;
 #else
+    // host build: the same split as on the GPU, levels 7 and up by the walk and the rest from the table's digit
+    // row, so that the host tests check that row too
     uint32_t d = 0;
-#pragma unroll
-    for (int k = pol.top(); k >= 0; --k) {
+    const bool by_table = pol.lowtab() != nullptr;
+    for (int k = pol.top(); k >= (by_table ? kLowLevels : 0); --k) {
         const uint32_t s = pol.s(k);
         const bool take = y >= s;
         y = take ? y - s : y;
         d = (d << 1) | (take ? 1u : 0u);
     }
+    if (by_table) d = (d << kLowLevels) | pol.lowtab()[kLowDigitRow * 128 + (int)(y & 127u)];
     return d;
 #endif
 }
