@@ -348,6 +348,9 @@ def main():
                          "packing and unpacking one round's message on irregular buffers.  configs: the other "
                          "configurations of the baseline (largest p, expansion at p=65537, irregular batch, partial "
                          "ranges), one line of per-call timings")
+    ap.add_argument("--graph", action="store_true",
+                    help="step workload only: also record the timed steps into one HIP graph and time its replay "
+                         "(reported as ms_per_step_in_hip_graph; `value` stays the plain launches)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run three plain 1 GiB device copies before the timed region, so that a counter "
                          "profile of this command holds a kernel of known traffic to scale FETCH_SIZE/WRITE_SIZE by")
@@ -414,6 +417,24 @@ def main():
     timing = bcs.bcs_timing_stats()
     ms_per_step_events = (t1 - t0) * 1e3 / steps
 
+    ms_per_step_graph = None
+    if args.graph:
+        # the same steps as one HIP graph: inside a graph the kernels of consecutive steps follow each other without
+        # the few microseconds that separate two launches of a stream
+        side = torch.cuda.Stream()
+        with torch.cuda.stream(side):
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph, stream=side):
+                for _ in range(steps):
+                    step()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        graph.replay()
+        torch.cuda.synchronize()
+        ms_per_step_graph = (time.perf_counter() - t0) * 1e3 / steps
+
     # per-kernel rooflines from the device-side durations of the timed region
     kernels = {}
     for name, (ms, cnt, shortest, longest) in timing.items():
@@ -454,6 +475,8 @@ def main():
         "roofline": roofline,
         "kernels": kernels,
     }
+    if ms_per_step_graph is not None:
+        out["ms_per_step_in_hip_graph"] = ms_per_step_graph
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline()
     print(json.dumps(out))
