@@ -335,7 +335,19 @@ BCS_HD void recv_row_from(const Pol &pol, uint32_t v, uint32_t dv, int last, Emi
         const bool is_home = (i == home);
         const bool ahead = v >= s_n;
         const uint32_t y = ahead ? v - s_n : v + p - s_n;
-        const uint32_t d_lo = digits(pol, y) | (ahead ? lap : 0u);
+        // When skips[i+1] is part of v's greedy sum, taking it out leaves the greedy sum of v - skips[i+1] (the
+        // ranks below it were below skips[i+1] before and still are), and in the last round the end point is v
+        // itself: no walk.  The high digits of consecutive ranks agree, so whole waves take this path.
+        // (Lanes with unrelated p never agree on it, so the per-lane policy does not ask.)
+        uint32_t d_lo;
+        if constexpr (Pol::kScalarSkips) {
+            const uint32_t nbit = 1u << ((i + 1) & 31);
+            const bool direct = (i + 1 == q) || (dv & nbit) != 0u;
+            d_lo = (i + 1 == q) ? dv : ((dv & ~nbit) | lap);
+            if (BCS_WAVE_ANY(!direct)) d_lo = digits(pol, y) | (ahead ? lap : 0u);
+        } else {
+            d_lo = digits(pol, y) | (ahead ? lap : 0u);
+        }
         c += (odd >> i) & 1u;
         uint32_t U = window_blocks(pol, d_lo, d_hi) & ~lap & ~B;
         const bool need2 = active && !is_home && U == 0u;
