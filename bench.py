@@ -32,18 +32,42 @@ INT_VALU_PEAK_GOPS = 256 * 4 * 16 * 2.4     # CUs x SIMDs x lanes x GHz = 39 321
 # HBM bytes per launch at this workload, from the rocprofv3 counter runs summarised in
 # profiles/bench_c2_kernels.md (FETCH_SIZE scaled x2.0, WRITE_SIZE x1.0 by the 1 GiB copy calibration).
 PROFILED_TRAFFIC_BYTES = {
-    "k_expand_rows": (2 * 35344 + 1130588) * 1024,
-    "k_recv_uniform": (2 * 51 + 132099) * 1024,
-    "k_send_lookup": (2 * 15914 + 110592) * 1024,
+    "k_expand_rows": (2 * 35344 + 1130538) * 1024,
+    "k_recv_uniform": (2 * 52 + 132097) * 1024,
+    "k_send_lookup": (2 * 15921 + 110592) * 1024,
 }
 
 
-def valu_ops_per_rank(q):
-    """Vector-ALU lane-operations one receive row costs on the main path of k_recv_uniform, counted from its
-    ISA: q+2 digit walks of 3 ops a level for the levels from 7 up and 3 ops around the table read that stands
-    for the seven levels below, 55 ops of window logic and bookkeeping a round, 50 of set-up.
+def digit_walks_per_rank(p, skips):
+    """Digit walks k_recv_uniform runs per rank at root 0, averaged over all ranks: one for the rank itself, one for
+    the first window's upper end, and one per round n = 1..q-1 in which some lane of the wave lacks skips[n] among
+    its digits (when the whole wave has it, the end point's digits are the rank's with that digit taken out; the last
+    round's end point is the rank itself).  Counted here by doing the greedy sums (Alg. 2's walk) of all ranks with
+    numpy, 64 consecutive ranks a wave as the kernel lays them out."""
+    import numpy as np
+    q = len(skips) - 1
+    rest = np.arange(p, dtype=np.int64)
+    digits = np.zeros(p, dtype=np.int64)
+    for k in range(q - 1, -1, -1):
+        take = rest >= skips[k]
+        rest -= take * skips[k]
+        digits |= take.astype(np.int64) << k
+    waves = -(-p // 64)
+    padded = np.zeros(waves * 64, dtype=np.int64)        # idle lanes replay rank 0, which has no digits
+    padded[:p] = digits
+    shared = np.bitwise_and.reduce(padded.reshape(waves, 64), axis=1)
+    direct = np.zeros(waves, dtype=np.int64)
+    for n in range(1, q):
+        direct += (shared >> n) & 1
+    return float(2 + (q - 1) - direct.mean())
+
+
+def valu_ops_per_rank(q, walks):
+    """Vector-ALU lane-operations one receive row costs on the main path of k_recv_uniform, counted from its ISA:
+    `walks` digit walks of 3 ops a level for the levels from 7 up and 3 ops around the table read that stands for
+    the seven levels below, 55 ops of window logic and bookkeeping a round, 50 of set-up.
     The wave-uniform branch for Alg. 4's second range is extra work and not counted."""
-    return (3 * max(q - 7, 0) + 3) * (q + 2) + 55 * q + 50
+    return (3 * max(q - 7, 0) + 3) * walks + 55 * q + 50
 
 
 def measure_valu_peak(torch, bcs):
@@ -396,6 +420,7 @@ def main():
         torch.cuda.synchronize()
         del a, b
     valu_peak_measured = measure_valu_peak(torch, bcs)
+    walks = digit_walks_per_rank(P, bcs.bcs_skips(P))
     steps = max(1, min(args.steps, 1000))
     # Two timed regions of exactly `steps` steps each.  The first is the plain path and gives the throughput; in the
     # second every launch carries its own start/stop events (which costs a few microseconds a launch, 4-5 % of a
@@ -448,7 +473,7 @@ def main():
             nbytes = P * q * (1 + 4) + P * 24                   # read the slot-major bytes, write one table and its byte rows
             ent.update(bound="hbm", achieved=nbytes / avg_ms / 1e6, peak=HBM_PEAK_GBS, unit="GB/s")
         elif name == "k_recv_uniform":
-            ops = valu_ops_per_rank(q) * P
+            ops = valu_ops_per_rank(q, walks) * P
             ent.update(bound="alu", achieved=ops / avg_ms / 1e6, peak=INT_VALU_PEAK_GOPS, unit="Gop/s",
                        peak_measured=valu_peak_measured, frac_of_measured=ops / avg_ms / 1e6 / valu_peak_measured)
         else:
@@ -474,6 +499,7 @@ def main():
                                                  + kernels["k_send_lookup"]["ms_per_step"]) * 1e-3),
         "roofline": roofline,
         "kernels": kernels,
+        "digit_walks_per_rank": walks,
     }
     if ms_per_step_graph is not None:
         out["ms_per_step_in_hip_graph"] = ms_per_step_graph
