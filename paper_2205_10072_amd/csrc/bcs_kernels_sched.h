@@ -1,0 +1,302 @@
+// Schedule construction kernels: the low-level table, receive rows (Alg. 4), send rows by look-up (Alg. 9,
+// second loop) and by recomputation (Alg. 5), and the batch of unrelated (p, r, root) triples.
+#ifndef BCS_KERNELS_SCHED_H
+#define BCS_KERNELS_SCHED_H
+
+#include "bcs_kernels_common.h"
+
+namespace {
+
+// ----------------------------------------------------------------------------------------------
+// The low-level table of bcs_core.h lives in the code object; k_build_lowtab fills it once per device
+// and process (one thread per entry, by the level walk).
+// ----------------------------------------------------------------------------------------------
+__device__ uint8_t g_lowtab[kLowTableBytes];
+
+__global__ __launch_bounds__(kBlock) void k_build_lowtab() {
+    const int e = blockIdx.x * kBlock + threadIdx.x;
+    if (e >= kLowTableBytes) return;
+    const int shape = e / kLowShapeBytes;
+    const int rest = e - shape * kLowShapeBytes;
+    g_lowtab[e] = (uint8_t)low_table_entry(shape, rest >> 7, rest & 127);
+}
+
+// copies one shape of the table (kLowShapeBytes, a multiple of 4) into LDS; callers synchronise
+__device__ __forceinline__ void stage_lowtab(uint32_t *dst, int shape) {
+    const uint32_t *src = reinterpret_cast<const uint32_t *>(g_lowtab + (size_t)shape * kLowShapeBytes);
+    for (int i = threadIdx.x; i < kLowShapeBytes / 4; i += kBlock) dst[i] = src[i];
+}
+
+// A lane completes its byte row (the three mirrored slots and the padding) ...
+template <int Q>
+__device__ __forceinline__ void byte_row_finish(int8_t *row) {
+    constexpr int kRS = byte_row_stride(Q);
+#pragma unroll
+    for (int m = 0; m < kRS - Q; ++m) row[Q + m] = (m < 3 && m < Q) ? row[m] : (int8_t)0;
+}
+
+// ... and the workgroup's byte rows leave for the table as 16-byte pieces (after a barrier)
+template <int Q>
+__device__ __forceinline__ void byte_rows_out(const int8_t *tileB, uint32_t rows, int8_t *__restrict__ dst) {
+    constexpr int kRS = byte_row_stride(Q);
+    const uint32_t n4 = rows * (kRS / 4);                         // dwords
+    const uint32_t n16 = n4 >> 2;
+    for (uint32_t g = threadIdx.x; g < n16; g += kBlock)
+        reinterpret_cast<v4i *>(dst)[g] = reinterpret_cast<const v4i *>(tileB)[g];
+    const uint32_t e = (n16 << 2) + threadIdx.x;
+    if (e < n4) reinterpret_cast<int32_t *>(dst)[e] = reinterpret_cast<const int32_t *>(tileB)[e];
+}
+
+// The byte rows of a workgroup packed straight from its int32 tile (row stride Q | 1), four entries a dword:
+// for a kernel that has vector-ALU time to spare and should not spend LDS on a byte tile.
+template <int Q>
+__device__ __forceinline__ void byte_rows_from_tile(const int32_t *tile, uint32_t rows, int8_t *__restrict__ dst) {
+    constexpr int kStride = Q | 1;
+    constexpr int kW4 = byte_row_stride(Q) / 4;                   // dwords per byte row
+    const uint32_t n4 = rows * kW4;
+    for (uint32_t g = threadIdx.x; g < n4; g += kBlock) {
+        const uint32_t row = g / kW4, w = g - row * kW4;
+        const int32_t *src = tile + row * kStride;
+        uint32_t packed = 0;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const uint32_t pos = 4u * w + c;
+            const bool slot_ok = pos < (uint32_t)(Q + 3);          // the row's slots and its three mirrors
+            const uint32_t slot = pos < (uint32_t)Q ? pos : (slot_ok ? pos - Q : 0u);
+            const int32_t t = slot_ok ? src[slot] - (int32_t)slot : 0;
+            packed |= ((uint32_t)t & 0xffu) << (8 * c);
+        }
+        reinterpret_cast<uint32_t *>(dst)[g] = packed;
+    }
+}
+
+// Rows of a workgroup's LDS tile (row stride Q | 1) to their place in a rank-major table.  For odd Q the tile is
+// already laid out like the table, so it leaves as 16-byte pieces with no index arithmetic.
+template <int Q>
+__device__ __forceinline__ void tile_to_rows(const int32_t *tile, uint32_t rows, int32_t *__restrict__ dst) {
+    constexpr int kStride = Q | 1;
+    const uint32_t n = rows * Q;
+    if constexpr (kStride == Q) {
+        if ((reinterpret_cast<uintptr_t>(dst) & 15u) == 0) {
+            const uint32_t n4 = n >> 2;
+            for (uint32_t g = threadIdx.x; g < n4; g += kBlock)
+                reinterpret_cast<v4i *>(dst)[g] = reinterpret_cast<const v4i *>(tile)[g];
+            const uint32_t e = (n4 << 2) + threadIdx.x;
+            if (e < n) dst[e] = tile[e];
+            return;
+        }
+    }
+    for (uint32_t e = threadIdx.x; e < n; e += kBlock) {
+        const uint32_t row = e / Q, col = e - row * Q;
+        dst[e] = tile[row * kStride + col];
+    }
+}
+
+// ----------------------------------------------------------------------------------------------
+// K1: receive rows of ranks [r0, r1), uniform p.  Lane = rank.  Rows are staged in LDS (odd stride,
+// conflict-free) and leave as contiguous dwords; optionally each entry is also stored slot-major
+// (recvT[k][r - r0]) for the send look-up that follows.
+// ----------------------------------------------------------------------------------------------
+template <int Q, bool BYTES>
+__global__ __launch_bounds__(kBlock) void k_recv_uniform(const SkipTab tab, uint32_t root, uint32_t r0, uint32_t r1,
+                                                         int32_t *__restrict__ recv_out,
+                                                         slot_t *__restrict__ recvT, uint64_t ldT,
+                                                         int8_t *__restrict__ rowsB) {
+    constexpr int kStride = Q | 1;
+    constexpr int kRS = byte_row_stride(Q);
+    __shared__ __align__(16) int32_t tile[kBlock * kStride];
+    __shared__ __align__(16) int8_t tileB[BYTES ? kBlock * kRS : 16];   // only the variant that leaves byte rows pays for it
+    __shared__ uint32_t lowtab[kLowShapeBytes / 4];
+    Uniform<Q> pol;
+#pragma unroll
+    for (int k = 0; k <= Q; ++k) pol.S[k] = tab.s[k];
+    pol.tab = &tab;
+    pol.low = reinterpret_cast<const uint8_t *>(lowtab);
+    const uint32_t p = pol.p();
+    stage_lowtab(lowtab, low_shape(p, Q));
+    __syncthreads();
+    const uint64_t first = (uint64_t)blockIdx.x * kBlock;       // offset of this tile inside [r0, r1)
+    const uint64_t idx = first + threadIdx.x;
+    const uint64_t count = (uint64_t)r1 - r0;
+    const bool live = idx < count;
+    const uint32_t r = live ? (uint32_t)(r0 + idx) : root;       // idle lanes replay the root (cheap, valid)
+    const uint32_t v = r >= root ? r - root : r + p - root;
+    int32_t *my = tile + threadIdx.x * kStride;
+    int8_t *myB = tileB + (BYTES ? threadIdx.x * kRS : 0);
+    recv_row(pol, v, Q - 1, [&](int i, int val) {
+        my[i] = val;
+        if (recvT && live) recvT[(uint64_t)i * ldT + idx] = (slot_t)val;
+        if constexpr (BYTES) myB[i] = (int8_t)(val - i);
+    });
+    if (!recv_out) return;
+    if constexpr (BYTES) byte_row_finish<Q>(myB);
+    __syncthreads();
+    const uint64_t rows = (count - first) < (uint64_t)kBlock ? (count - first) : (uint64_t)kBlock;
+    tile_to_rows<Q>(tile, (uint32_t)rows, recv_out + first * Q);
+    if constexpr (BYTES) byte_rows_out<Q>(tileB, (uint32_t)rows, rowsB + first * kRS);
+}
+
+// K2: send rows from the slot-major receive table of ALL ranks (Alg. 9, second loop):
+// send[r][k] = recv[(r + skips[k]) mod p][k].  Reads are contiguous per slot, rows leave through LDS.
+template <int Q>
+__global__ __launch_bounds__(kBlock) void k_send_lookup(const SkipTab tab, const slot_t *__restrict__ recvT,
+                                                        uint64_t ldT, int32_t *__restrict__ send_out,
+                                                        int8_t *__restrict__ rowsB) {
+    constexpr int kStride = Q | 1;
+    constexpr int kRS = byte_row_stride(Q);
+    __shared__ __align__(16) int32_t tile[kBlock * kStride];
+    const uint32_t p = tab.s[Q];
+    const uint64_t first = (uint64_t)blockIdx.x * kBlock;
+    const uint64_t idx = first + threadIdx.x;
+    const bool live = idx < p;
+    int32_t *my = tile + threadIdx.x * kStride;
+    if (live) {
+#pragma unroll
+        for (int k = 0; k < Q; ++k) {
+            uint32_t t = (uint32_t)idx + tab.s[k];
+            t = t >= p ? t - p : t;
+            my[k] = recvT[(uint64_t)k * ldT + t];
+        }
+    }
+    __syncthreads();
+    const uint64_t rows = ((uint64_t)p - first) < (uint64_t)kBlock ? ((uint64_t)p - first) : (uint64_t)kBlock;
+    tile_to_rows<Q>(tile, (uint32_t)rows, send_out + first * Q);
+    if (rowsB) byte_rows_from_tile<Q>(tile, (uint32_t)rows, rowsB + first * kRS);
+}
+
+// K1b: send rows of ranks [r0, r1) with no neighbour rows at hand (Alg. 5): entry i is entry i of the
+// receive schedule of the to-neighbour, which costs that neighbour's rounds 0..i.
+template <int Q>
+__global__ __launch_bounds__(kBlock) void k_send_recompute(const SkipTab tab, uint32_t root, uint32_t r0, uint32_t r1,
+                                                           int32_t *__restrict__ send_out) {
+    constexpr int kStride = Q | 1;
+    __shared__ __align__(16) int32_t tile[kBlock * kStride];
+    __shared__ uint32_t lowtab[kLowShapeBytes / 4];
+    Uniform<Q> pol;
+#pragma unroll
+    for (int k = 0; k <= Q; ++k) pol.S[k] = tab.s[k];
+    pol.tab = &tab;
+    pol.low = reinterpret_cast<const uint8_t *>(lowtab);
+    const uint32_t p = pol.p();
+    stage_lowtab(lowtab, low_shape(p, Q));
+    __syncthreads();
+    const uint64_t first = (uint64_t)blockIdx.x * kBlock;
+    const uint64_t idx = first + threadIdx.x;
+    const uint64_t count = (uint64_t)r1 - r0;
+    const bool live = idx < count;
+    const uint32_t r = live ? (uint32_t)(r0 + idx) : root;
+    const uint32_t v = r >= root ? r - root : r + p - root;
+    int32_t *my = tile + threadIdx.x * kStride;
+#pragma unroll 1
+    for (int i = 0; i < Q; ++i) {
+        uint32_t t = v + tab.s[i];
+        t = t >= p ? t - p : t;
+        const uint32_t dt = digits(pol, t);
+        int32_t keep = dt ? __builtin_ctz(dt) : 0;
+        // Round i is the neighbour's home round when its highest digit is i: then the entry is its baseblock and
+        // none of its earlier rounds matters.  A wave of consecutive ranks below skips[i+1] - skips[i] is in that
+        // case as a whole (half of all waves for the last slot, a quarter for the one before, ...).
+        const bool home_round = dt != 0u && (31 - __clz((int)dt)) == i;
+        if (__any(!home_round)) {
+            int32_t got = 0;
+            recv_row_from(pol, t, dt, i, [&](int j, int val) { got = (j == i) ? val : got; });
+            keep = got;
+        }
+        my[i] = keep;
+    }
+    __syncthreads();
+    const uint64_t rows = (count - first) < (uint64_t)kBlock ? (count - first) : (uint64_t)kBlock;
+    tile_to_rows<Q>(tile, (uint32_t)rows, send_out + first * Q);
+}
+
+// K3: unrelated (p, r, root) triples; rows of BCS_BATCH_STRIDE ints (one 128-byte line each), padded.
+// A workgroup takes kBatchBlock triples and first orders them by q in LDS (counting sort), because a
+// wave runs its level loops to the largest q among its lanes and the work grows like q^3: after the
+// sort a wave holds neighbouring q only.  Each lane then builds the rows of its triple and stores
+// them entry by entry into the triple's own line.
+constexpr int kBatchBlock = 1024;
+
+__global__ __launch_bounds__(kBatchBlock) void k_batch(int64_t count, const int32_t *__restrict__ pv,
+                                                       const int32_t *__restrict__ rv,
+                                                       const int32_t *__restrict__ rootv,
+                                                       int32_t *__restrict__ recv_out, int32_t *__restrict__ send_out,
+                                                       int32_t *__restrict__ q_out) {
+    __shared__ uint32_t bins[33];                 // bins[q] for valid triples, bins[32] for the rest
+    __shared__ uint32_t start[33];
+    __shared__ uint32_t s_p[kBatchBlock], s_v[kBatchBlock], s_slot[kBatchBlock];
+    const int64_t first = (int64_t)blockIdx.x * kBatchBlock;
+    {
+        const int64_t idx = first + threadIdx.x;
+        const bool live = idx < count;
+        const int32_t pi = live ? pv[idx] : 1, ri = live ? rv[idx] : 0, rooti = live ? rootv[idx] : 0;
+        const bool valid = live && pi >= 1 && ri >= 0 && ri < pi && rooti >= 0 && rooti < pi;
+        const uint32_t p = valid ? (uint32_t)pi : 1u;
+        const int q = ceil_log2(p);
+        const uint32_t v = !valid ? 0u
+                           : ((uint32_t)ri >= (uint32_t)rooti ? (uint32_t)(ri - rooti)
+                                                              : (uint32_t)ri + p - (uint32_t)rooti);
+        if (threadIdx.x < 33) bins[threadIdx.x] = 0u;
+        __syncthreads();
+        const int bin = valid ? q : 32;
+        const uint32_t rank_in_bin = atomicAdd(&bins[bin], 1u);
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            uint32_t acc = 0;
+            for (int k = 0; k < 33; ++k) {
+                start[k] = acc;
+                acc += bins[k];
+            }
+        }
+        __syncthreads();
+        const uint32_t pos = start[bin] + rank_in_bin;
+        s_p[pos] = p;
+        s_v[pos] = v;
+        s_slot[pos] = threadIdx.x | (valid ? 0u : 0x80000000u) | (live ? 0u : 0x40000000u);
+        __syncthreads();
+    }
+    // from here on this lane works on the triple that the sort put at its position
+    const uint32_t p = s_p[threadIdx.x];
+    const uint32_t v = s_v[threadIdx.x];
+    const uint32_t slot = s_slot[threadIdx.x];
+    const bool valid = (slot & 0x80000000u) == 0u;
+    const bool live = (slot & 0x40000000u) == 0u;
+    const int64_t idx = first + (slot & 0xffffu);
+    const int q = ceil_log2(p);
+    if (live && q_out) q_out[idx] = valid ? q : -1;
+    // largest q in this wave bounds the level loops of all its lanes
+    int qmax = q;
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+        const int other = __shfl_xor(qmax, off, 64);
+        qmax = other > qmax ? other : qmax;
+    }
+    PerLane pol;
+    pol.pm1 = p - 1u;
+    pol.ql = q;
+    pol.wave_top = qmax - 1;
+    pol.odd = odd_levels(p, q);
+    pol.low = g_lowtab + (size_t)low_shape(p, q) * kLowShapeBytes;
+    if (recv_out) {
+        int32_t *row = recv_out + idx * BCS_BATCH_STRIDE;
+        recv_row(pol, v, qmax - 1, [&](int i, int val) { if (live) row[i] = val; });
+        if (live)
+            for (int k = q; k < BCS_BATCH_STRIDE; ++k) row[k] = BCS_BATCH_PAD;
+    }
+    if (send_out) {
+        int32_t *row = send_out + idx * BCS_BATCH_STRIDE;
+#pragma unroll 1
+        for (int i = 0; i < qmax; ++i) {
+            uint32_t t = v + (i < q ? pol.s(i) : 0u);
+            t = t >= p ? t - p : t;
+            int32_t keep = 0;
+            recv_row(pol, t, i, [&](int j, int val) { keep = (j == i) ? val : keep; });
+            if (live && i < q) row[i] = keep;
+        }
+        if (live)
+            for (int k = q; k < BCS_BATCH_STRIDE; ++k) row[k] = BCS_BATCH_PAD;
+    }
+}
+
+}  // namespace
+
+#endif  // BCS_KERNELS_SCHED_H
