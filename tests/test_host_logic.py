@@ -132,3 +132,39 @@ def test_lane_code_perlane_small_p_and_padding_lanes(oracle):
             got = hostcheck.recv_row(p, v, last=30, perlane=True, wave_q=31)
             assert (got[:q] == oracle.recvsched(p, v)).all() if q else True
             assert (got[q:] == 12345).all()
+
+
+def _greedy_digits(skips, ranks):
+    """Alg. 2's walk kept as a digit mask, for an array of ranks: bit k set when skips[k] is taken."""
+    rest = ranks.astype(np.int64).copy()
+    digits = np.zeros(len(ranks), dtype=np.int64)
+    for k in range(len(skips) - 2, -1, -1):
+        take = rest >= skips[k]
+        rest -= take * int(skips[k])
+        digits |= take.astype(np.int64) << k
+    return digits
+
+
+def test_taking_a_digit_out_of_a_greedy_sum_leaves_a_greedy_sum(oracle):
+    """What the kernels rest on when they skip the walk for an end point v - skips[n]: if skips[n] is one of the
+    digits of v, the digits of v - skips[n] are those of v without digit n.  Every rank of every p below 700, and
+    sampled ranks of large p of every bit length."""
+    rng = np.random.default_rng(2205)
+    cases = [(p, np.arange(p)) for p in range(2, 700)]
+    for bits in range(11, 32):
+        for p in {2**bits - 1, 2**(bits - 1) + 1, int(rng.integers(2**(bits - 1) + 1, 2**bits))}:
+            cases.append((p, rng.integers(0, p, size=400)))
+    for p, ranks in cases:
+        skips = oracle.skips(p)
+        d = _greedy_digits(skips, ranks)
+        # the lowest digit is the baseblock (Alg. 2), which pins the digit walk itself to the oracle
+        for idx in range(min(40, len(ranks))):
+            r, dr = int(ranks[idx]), int(d[idx])
+            if r > 0:
+                assert (dr & -dr).bit_length() - 1 == oracle.baseblock(p, r), (p, r)
+        for n in range(len(skips) - 1):
+            has = ((d >> n) & 1) == 1
+            if not has.any():
+                continue
+            lower = _greedy_digits(skips, ranks[has] - int(skips[n]))
+            assert np.array_equal(lower, d[has] & ~(1 << n)), (p, n)
