@@ -32,9 +32,10 @@ INT_VALU_PEAK_GOPS = 256 * 4 * 16 * 2.4     # CUs x SIMDs x lanes x GHz = 39 321
 # HBM bytes per launch at this workload, from the rocprofv3 counter runs summarised in
 # profiles/bench_c2_kernels.md (FETCH_SIZE scaled x2.0, WRITE_SIZE x1.0 by the 1 GiB copy calibration).
 PROFILED_TRAFFIC_BYTES = {
-    "k_expand_rows": (2 * 35344 + 1130538) * 1024,
-    "k_recv_uniform": (2 * 52 + 132097) * 1024,
-    "k_send_lookup": (2 * 15921 + 110592) * 1024,
+    "k_expand_rows": (2 * 35340 + 1130552) * 1024,
+    "k_recv_uniform": (2 * 11287 + 132103) * 1024,
+    "k_send_lookup": (2 * 15952 + 110592) * 1024,
+    "k_digits": (2 * 29 + 4096) * 1024,
 }
 
 
@@ -60,6 +61,12 @@ def digit_walks_per_rank(p, skips):
     for n in range(1, q):
         direct += (shared >> n) & 1
     return float(2 + (q - 1) - direct.mean())
+
+
+def valu_ops_per_rank_tabled(q):
+    """The same row when the digit masks of all ranks are in a table (launches over all ranks of up to 2^24 ranks):
+    55 ops a round, which include the read of the round's end point, and 50 of set-up."""
+    return 55 * q + 50
 
 
 def valu_ops_per_rank(q, walks):
@@ -420,7 +427,8 @@ def main():
         torch.cuda.synchronize()
         del a, b
     valu_peak_measured = measure_valu_peak(torch, bcs)
-    walks = digit_walks_per_rank(P, bcs.bcs_skips(P))
+    tabled = 4 * P <= bcs.DIGIT_TABLE_MAX_BYTES          # receive rows read the digit masks k_digits leaves
+    walks = 1.0 if tabled else digit_walks_per_rank(P, bcs.bcs_skips(P))
     steps = max(1, min(args.steps, 1000))
     # Two timed regions of exactly `steps` steps each.  The first is the plain path and gives the throughput; in the
     # second every launch carries its own start/stop events (which costs a few microseconds a launch, 4-5 % of a
@@ -473,9 +481,12 @@ def main():
             nbytes = P * q * (1 + 4) + P * 24                   # read the slot-major bytes, write one table and its byte rows
             ent.update(bound="hbm", achieved=nbytes / avg_ms / 1e6, peak=HBM_PEAK_GBS, unit="GB/s")
         elif name == "k_recv_uniform":
-            ops = valu_ops_per_rank(q, walks) * P
+            ops = (valu_ops_per_rank_tabled(q) if tabled else valu_ops_per_rank(q, walks)) * P
             ent.update(bound="alu", achieved=ops / avg_ms / 1e6, peak=INT_VALU_PEAK_GOPS, unit="Gop/s",
                        peak_measured=valu_peak_measured, frac_of_measured=ops / avg_ms / 1e6 / valu_peak_measured)
+        elif name == "k_digits":
+            ops = (3 * max(q - 7, 0) + 3 + 12) * P              # one walk a rank, address and store
+            ent.update(bound="alu", achieved=ops / avg_ms / 1e6, peak=INT_VALU_PEAK_GOPS, unit="Gop/s")
         else:
             continue
         ent["frac"] = ent["achieved"] / ent["peak"]
@@ -495,8 +506,9 @@ def main():
         "config": {"workload": "p=2^20+1 (q=21), all ranks, root 0: recv+send schedules, then expansion n=%d "
                                "(R=%d rounds)" % (N_BLOCKS, R), "p": P, "q": q, "n": N_BLOCKS, "rounds": R},
         "expand_gbs": kernels["k_expand_rows"]["achieved"],
-        "construct_rank_schedules_per_s": P / ((kernels["k_recv_uniform"]["ms_per_step"]
-                                                 + kernels["k_send_lookup"]["ms_per_step"]) * 1e-3),
+        "construct_rank_schedules_per_s": P / (sum(kernels[k]["ms_per_step"] for k in
+                                                   ("k_digits", "k_recv_uniform", "k_send_lookup") if k in kernels)
+                                               * 1e-3),
         "roofline": roofline,
         "kernels": kernels,
         "digit_walks_per_rank": walks,

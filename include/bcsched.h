@@ -94,13 +94,21 @@ int bcs_sched_rooted(int32_t p, int32_t root, int32_t r0, int32_t r1,
                      int32_t *recv_out, int32_t *send_out, void *stream);
 
 /* Scratch bytes bcs_sched_rooted_ws needs for these arguments (0 when none).
- * Negative: BCS_EINVAL. */
+ * Negative: BCS_EINVAL.  A call over all ranks that also wants send rows keeps
+ * there the receive entries slot by slot (one byte each) and, for p up to
+ * BCS_DIGIT_TABLE_MAX_BYTES / 4 ranks, the greedy skip sums of all ranks (the
+ * walk of Alg. 2 kept as a mask, one word a rank): every end point of a
+ * window of Alg. 4 is some rank, so the receive rows read these instead of
+ * walking q + 2 times each. */
+#define BCS_DIGIT_TABLE_MAX_BYTES (64ll << 20)
 int64_t bcs_sched_workspace_bytes(int32_t p, int32_t r0, int32_t r1, int want_send);
 
 /* bcs_sched_rooted with caller-provided scratch.  `workspace` is device
  * memory, 256-byte aligned, of at least bcs_sched_workspace_bytes(...) bytes;
  * its contents are undefined afterwards.  BCS_ENOMEM if it is too small or
- * NULL while scratch is needed.  Performs no allocation. */
+ * NULL while scratch is needed.  Performs no allocation.  A call over all
+ * ranks for receive rows alone needs none; given 4 p bytes (rounded up to 256,
+ * at most BCS_DIGIT_TABLE_MAX_BYTES) it uses them for the table of skip sums. */
 int bcs_sched_rooted_ws(int32_t p, int32_t root, int32_t r0, int32_t r1,
                         int32_t *recv_out, int32_t *send_out,
                         void *workspace, size_t workspace_bytes, void *stream);
@@ -261,7 +269,7 @@ int bcs_release(void);
  * 0..BCS_KERNEL_COUNT-1, the summed duration in milliseconds and the number
  * of timed launches into host arrays of BCS_KERNEL_COUNT entries.  Not
  * thread-safe; meant for one measuring thread. */
-#define BCS_KERNEL_COUNT         14
+#define BCS_KERNEL_COUNT         15
 #define BCS_TIMING_MAX_LAUNCHES  4096
 int bcs_timing_begin(void);
 int bcs_timing_end(double *ms_sum_host, int64_t *launches_host);

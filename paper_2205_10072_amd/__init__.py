@@ -30,7 +30,8 @@ SYMBOLS = (
     "bcs_allgather_workspace_bytes", "bcs_allgather_tables", "bcs_allgather_tables_ws",
     "bcs_pack_workspace_bytes", "bcs_pack_round", "bcs_unpack_round", "bcs_allgather_plan", "bcs_census_plan",
 )
-KERNEL_COUNT = 14
+KERNEL_COUNT = 15
+DIGIT_TABLE_MAX_BYTES = 64 << 20      # BCS_DIGIT_TABLE_MAX_BYTES
 VALU_PEAK_OPS_PER_ITER = 32
 
 _lib = None

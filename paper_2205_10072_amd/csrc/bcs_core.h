@@ -307,6 +307,38 @@ BCS_HD uint32_t window_blocks(const Pol &pol, uint32_t d_lo, uint32_t d_hi) {
 // mod p and rank 0 owns no baseblock.  The i = 0 and i = q-1 special cases printed in Alg. 4 are
 // instances of this rule.  End points are kept as v + p - skips[i] in [0, 2p): digits of the rank plus
 // a lap digit at level q, so that every window is an increasing pair.
+// One round of Alg. 4 on the digit masks of the window's end points: d_hi for v - skips[i], d_lo for
+// v - skips[i+1] (each with the lap digit when the subtraction did not wrap).  B is the set of blocks the rank
+// has, c the number of odd levels up to i; digits_of(y) gives the digit mask of a rank y < p.
+template <class Pol, class DigitsOf, class Emit>
+BCS_HD void recv_round(const Pol &pol, uint32_t v, int i, uint32_t s_n, uint32_t d_lo, uint32_t d_hi, int home,
+                       int own, uint32_t &B, uint32_t &c, DigitsOf digits_of, Emit emit) {
+    const uint32_t p = pol.p();
+    const int q = pol.q();
+    const uint32_t lap = 1u << (q & 31);
+    const bool active = i < q;                            // per-lane q may be below the wave's bound
+    const bool is_home = (i == home);
+    c += (pol.odd_mask() >> i) & 1u;
+    uint32_t U = window_blocks(pol, d_lo, d_hi) & ~lap & ~B;
+    const bool need2 = active && !is_home && U == 0u;
+    if (BCS_WAVE_ANY(need2)) {
+        // the c ranks that end where the first range begins; one more lap if that runs below 0
+        const uint32_t Y = v + p - s_n;
+        const bool under = Y < c;
+        const uint32_t Z = under ? Y + p - c : Y - c;
+        const uint32_t hi2 = under ? (d_lo | lap) : d_lo;
+        const bool zlap = Z >= p;
+        const uint32_t lo2 = digits_of(zlap ? Z - p : Z) | (zlap ? lap : 0u);
+        const uint32_t U2 = window_blocks(pol, lo2, hi2) & ~lap & ~B;
+        U = need2 ? U2 : U;
+    }
+    const int blk = 31 - BCS_CLZ(U);                      // largest candidate
+    // one emit for both kinds of round, so that a wave with lanes of both kinds does not run it twice
+    const bool take = active && !is_home;
+    B |= take ? (1u << (blk & 31)) : 0u;
+    if (active) emit(i, is_home ? own : blk - q);
+}
+
 template <class Pol, class Emit>
 BCS_HD void recv_row_from(const Pol &pol, uint32_t v, uint32_t dv, int last, Emit emit);
 
@@ -324,15 +356,12 @@ BCS_HD void recv_row_from(const Pol &pol, uint32_t v, uint32_t dv, int last, Emi
     const int home = 31 - BCS_CLZ(dv);                    // -1 for the root
     const int own = dv ? __builtin_ctz(dv) : 0;
     uint32_t B = v ? (1u << own) : 0u;
-    const uint32_t odd = pol.odd_mask();
     uint32_t s_i = pol.sdyn(0);
     uint32_t d_hi = digits(pol, v >= s_i ? v - s_i : v + p - s_i) | (v >= s_i ? lap : 0u);
     uint32_t c = 0;
 #pragma unroll 1
     for (int i = 0; i <= last; ++i) {
         const uint32_t s_n = pol.sdyn(i + 1);
-        const bool active = i < q;                        // per-lane q may be below the wave's bound
-        const bool is_home = (i == home);
         const bool ahead = v >= s_n;
         const uint32_t y = ahead ? v - s_n : v + p - s_n;
         // When skips[i+1] is part of v's greedy sum, taking it out leaves the greedy sum of v - skips[i+1] (the
@@ -348,28 +377,36 @@ BCS_HD void recv_row_from(const Pol &pol, uint32_t v, uint32_t dv, int last, Emi
         } else {
             d_lo = digits(pol, y) | (ahead ? lap : 0u);
         }
-        c += (odd >> i) & 1u;
-        uint32_t U = window_blocks(pol, d_lo, d_hi) & ~lap & ~B;
-        const bool need2 = active && !is_home && U == 0u;
-        if (BCS_WAVE_ANY(need2)) {
-            // the c ranks that end where the first range begins; one more lap if that runs below 0
-            const uint32_t Y = v + p - s_n;
-            const bool under = Y < c;
-            const uint32_t Z = under ? Y + p - c : Y - c;
-            const uint32_t hi2 = under ? (d_lo | lap) : d_lo;
-            const bool zlap = Z >= p;
-            const uint32_t lo2 = digits(pol, zlap ? Z - p : Z) | (zlap ? lap : 0u);
-            const uint32_t U2 = window_blocks(pol, lo2, hi2) & ~lap & ~B;
-            U = need2 ? U2 : U;
-        }
-        const int blk = 31 - BCS_CLZ(U);                  // largest candidate
-        // one emit for both kinds of round, so that a wave with lanes of both kinds does not run it twice
-        const bool take = active && !is_home;
-        B |= take ? (1u << (blk & 31)) : 0u;
-        if (active) emit(i, is_home ? own : blk - q);
+        recv_round(pol, v, i, s_n, d_lo, d_hi, home, own, B, c, [&](uint32_t r) { return digits(pol, r); }, emit);
         d_hi = d_lo;
-        s_i = s_n;
     }
+}
+
+// The same row with every digit mask read from a table of all ranks' masks (dtab[y] = digits of rank y, filled
+// by one walk per rank beforehand): every end point of every window is some rank.  All q rounds, unrolled, so that
+// the skips are the policy's registers and the reads of later rounds can be issued ahead of the rounds that use
+// them.
+template <class Pol, class Emit>
+BCS_HD void recv_row_tab(const Pol &pol, const uint32_t *__restrict__ dtab, uint32_t v, Emit emit) {
+    static_assert(Pol::kScalarSkips, "one p per launch: the inert skips of the per-lane policy are no table indices");
+    constexpr int kQ = Pol::kTopLevel + 1;
+    const uint32_t p = pol.p();
+    const uint32_t lap = 1u << (kQ & 31);
+    uint32_t d[kQ + 1];                                  // d[n]: digits of v - skips[n] with the lap digit
+#pragma unroll
+    for (int n = 0; n <= kQ; ++n) {
+        const uint32_t s = pol.s(n);
+        const bool ahead = v >= s;
+        d[n] = dtab[ahead ? v - s : v + p - s] | (ahead ? lap : 0u);
+    }
+    const uint32_t dv = d[kQ];                           // skips[q] = p: the rank itself, no lap
+    const int home = 31 - BCS_CLZ(dv);
+    const int own = dv ? __builtin_ctz(dv) : 0;
+    uint32_t B = v ? (1u << own) : 0u;
+    uint32_t c = 0;
+#pragma unroll
+    for (int i = 0; i < kQ; ++i)
+        recv_round(pol, v, i, pol.s(i + 1), d[i + 1], d[i], home, own, B, c, [&](uint32_t r) { return dtab[r]; }, emit);
 }
 
 }  // namespace bcs

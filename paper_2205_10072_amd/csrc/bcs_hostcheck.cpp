@@ -45,6 +45,21 @@ void row_uniform(const SkipTab &t, uint32_t v, int last, int32_t *out) {
     recv_row(pol, v, last, [&](int i, int val) { out[i] = val; });
 }
 
+// the same row from a table of all ranks' digit masks, as the kernels for whole rank ranges build it
+template <int Q>
+void row_from_table(const SkipTab &t, const uint32_t *dtab, uint32_t v, int last, int32_t *out) {
+    Uniform<Q> pol;
+    for (int k = 0; k <= Q; ++k) pol.S[k] = t.s[k];
+    pol.tab = &t;
+    pol.low = low_for((int32_t)t.s[Q]);
+    if (!dtab) {
+        *reinterpret_cast<uint32_t *>(out) = digits(pol, v);      // table entry of rank v
+        return;
+    }
+    (void)last;
+    recv_row_tab(pol, dtab, v, [&](int i, int val) { out[i] = val; });
+}
+
 template <int Q>
 uint32_t range_uniform(const SkipTab &t, uint32_t a, uint32_t b) {
     Uniform<Q> pol;
@@ -56,26 +71,29 @@ uint32_t range_uniform(const SkipTab &t, uint32_t a, uint32_t b) {
 
 typedef void (*RowFn)(const SkipTab &, uint32_t, int, int32_t *);
 typedef uint32_t (*RangeFn)(const SkipTab &, uint32_t, uint32_t);
+typedef void (*TabRowFn)(const SkipTab &, const uint32_t *, uint32_t, int, int32_t *);
 
 template <int Q>
 struct Fill {
-    static void go(RowFn *r, RangeFn *g) {
+    static void go(RowFn *r, RangeFn *g, TabRowFn *t) {
         r[Q] = &row_uniform<Q>;
         g[Q] = &range_uniform<Q>;
-        Fill<Q - 1>::go(r, g);
+        t[Q] = &row_from_table<Q>;
+        Fill<Q - 1>::go(r, g, t);
     }
 };
 template <>
 struct Fill<0> {
-    static void go(RowFn *, RangeFn *) {}
+    static void go(RowFn *, RangeFn *, TabRowFn *) {}
 };
 
 RowFn g_row[kMaxQ + 1];
 RangeFn g_range[kMaxQ + 1];
+TabRowFn g_tabrow[kMaxQ + 1];
 bool g_ready = false;
 void ready() {
     if (!g_ready) {
-        Fill<kMaxQ>::go(g_row, g_range);
+        Fill<kMaxQ>::go(g_row, g_range, g_tabrow);
         g_ready = true;
     }
 }
@@ -115,6 +133,22 @@ int hc_recv_rows_all(int32_t p, int32_t *out) {
     fill_skips(p, t);
     const int q = host_q(p);
     for (int32_t v = 0; v < p; ++v) g_row[q](t, (uint32_t)v, q - 1, out + (size_t)v * q);
+    return 0;
+}
+
+// all p receive rows through the table of digit masks: dtab (p words of scratch) is filled first, one walk a rank
+int hc_recv_rows_all_tab(int32_t p, uint32_t *dtab, int32_t *out) {
+    if (p < 2) return -1;
+    ready();
+    SkipTab t;
+    fill_skips(p, t);
+    const int q = host_q(p);
+    for (int32_t v = 0; v < p; ++v) {
+        int32_t word;
+        g_tabrow[q](t, nullptr, (uint32_t)v, 0, &word);
+        dtab[v] = (uint32_t)word;
+    }
+    for (int32_t v = 0; v < p; ++v) g_tabrow[q](t, dtab, (uint32_t)v, q - 1, out + (size_t)v * q);
     return 0;
 }
 

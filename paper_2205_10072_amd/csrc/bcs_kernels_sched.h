@@ -97,11 +97,30 @@ __device__ __forceinline__ void tile_to_rows(const int32_t *tile, uint32_t rows,
 // conflict-free) and leave as contiguous dwords; optionally each entry is also stored slot-major
 // (recvT[k][r - r0]) for the send look-up that follows.
 // ----------------------------------------------------------------------------------------------
-template <int Q, bool BYTES>
+// K0: the digit mask of every rank (one walk each), for launches over all ranks: every end point of every
+// window of Alg. 4 is some rank, so K1 then reads its digit masks instead of walking (q+2 walks a row otherwise).
+template <int Q>
+__global__ __launch_bounds__(kBlock) void k_digits(const SkipTab tab, uint32_t *__restrict__ dtab) {
+    __shared__ uint32_t lowtab[kLowShapeBytes / 4];
+    Uniform<Q> pol;
+#pragma unroll
+    for (int k = 0; k <= Q; ++k) pol.S[k] = tab.s[k];
+    pol.tab = &tab;
+    pol.low = reinterpret_cast<const uint8_t *>(lowtab);
+    const uint32_t p = pol.p();
+    stage_lowtab(lowtab, low_shape(p, Q));
+    __syncthreads();
+    const uint64_t y = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
+    const uint32_t d = digits(pol, y < p ? (uint32_t)y : 0u);
+    if (y < p) dtab[y] = d;
+}
+
+template <int Q, bool BYTES, bool TAB = false>
 __global__ __launch_bounds__(kBlock) void k_recv_uniform(const SkipTab tab, uint32_t root, uint32_t r0, uint32_t r1,
                                                          int32_t *__restrict__ recv_out,
                                                          slot_t *__restrict__ recvT, uint64_t ldT,
-                                                         int8_t *__restrict__ rowsB) {
+                                                         int8_t *__restrict__ rowsB,
+                                                         const uint32_t *__restrict__ dtab) {
     constexpr int kStride = Q | 1;
     constexpr int kRS = byte_row_stride(Q);
     __shared__ __align__(16) int32_t tile[kBlock * kStride];
@@ -123,11 +142,13 @@ __global__ __launch_bounds__(kBlock) void k_recv_uniform(const SkipTab tab, uint
     const uint32_t v = r >= root ? r - root : r + p - root;
     int32_t *my = tile + threadIdx.x * kStride;
     int8_t *myB = tileB + (BYTES ? threadIdx.x * kRS : 0);
-    recv_row(pol, v, Q - 1, [&](int i, int val) {
+    auto emit = [&](int i, int val) {
         my[i] = val;
         if (recvT && live) recvT[(uint64_t)i * ldT + idx] = (slot_t)val;
         if constexpr (BYTES) myB[i] = (int8_t)(val - i);
-    });
+    };
+    if constexpr (TAB) recv_row_tab(pol, dtab, v, emit);
+    else recv_row(pol, v, Q - 1, emit);
     if (!recv_out) return;
     if constexpr (BYTES) byte_row_finish<Q>(myB);
     __syncthreads();

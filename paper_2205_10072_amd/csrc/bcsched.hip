@@ -29,13 +29,13 @@ inline int hip_fail(hipError_t e) {
 // given a start and a stop event from a fixed pool, so its duration is the device's own.
 enum KernelId {
     kRecv = 0, kSendLookup, kSendRecompute, kBatch, kExpand, kFill, kValuPeak, kAllgather, kPackPlan, kPackCopy,
-    kRecvExpand, kSendExpand, kExpandRows, kRowsToBytes, kKernelCount
+    kRecvExpand, kSendExpand, kExpandRows, kRowsToBytes, kDigits, kKernelCount
 };
 static_assert(kKernelCount == BCS_KERNEL_COUNT, "header and kernel list disagree");
 const char *const kKernelNames[kKernelCount] = {"k_recv_uniform", "k_send_lookup", "k_send_recompute", "k_batch",
                                                 "k_expand",       "k_fill",        "k_valu_peak",   "k_allgather_tables",
                                                 "k_pack_plan",    "k_pack_copy",   "k_recv_expand", "k_send_expand",
-                                                "k_expand_rows",  "k_rows_to_bytes"};
+                                                "k_expand_rows",  "k_rows_to_bytes", "k_digits"};
 struct Timing {
     bool on = false;
     int used = 0;
@@ -226,19 +226,32 @@ inline uint64_t slot_ld(int32_t p) { return round_up((uint64_t)p, 256); }
 
 template <int Q>
 int launch_sched(const SkipTab &tab, uint32_t root, uint32_t r0, uint32_t r1, int32_t *recv_out, int32_t *send_out,
-                 slot_t *recvT, uint64_t ldT, int8_t *recvB, int8_t *sendB, hipStream_t st) {
+                 slot_t *recvT, uint64_t ldT, int8_t *recvB, int8_t *sendB, uint32_t *dtab, hipStream_t st) {
     const uint64_t count = (uint64_t)r1 - r0;
     const unsigned blocks = (unsigned)((count + kBlock - 1) / kBlock);
     const bool full = (r0 == 0 && r1 == tab.s[Q]);
     // the slot-major copy feeds the send look-up; with neither table asked for it is the only output
     const bool want_t = full && recvT && (send_out || !recv_out);
     if (recv_out || want_t) {
-        if (full && recvB && recv_out)
-            launch(kRecv, k_recv_uniform<Q, true>, dim3(blocks), dim3(kBlock), st, tab, root, r0, r1, recv_out,
-                   want_t ? recvT : (slot_t *)nullptr, ldT, recvB);
-        else
-            launch(kRecv, k_recv_uniform<Q, false>, dim3(blocks), dim3(kBlock), st, tab, root, r0, r1, recv_out,
-                   want_t ? recvT : (slot_t *)nullptr, ldT, (int8_t *)nullptr);
+        const bool tabbed = full && dtab;        // all ranks: one walk a rank into the table, the rows read it
+        if (tabbed) launch(kDigits, k_digits<Q>, dim3(blocks), dim3(kBlock), st, tab, dtab);
+        slot_t *const t_out = want_t ? recvT : (slot_t *)nullptr;
+        const uint32_t *const d_in = dtab;
+        if (full && recvB && recv_out) {
+            if (tabbed)
+                launch(kRecv, k_recv_uniform<Q, true, true>, dim3(blocks), dim3(kBlock), st, tab, root, r0, r1,
+                       recv_out, t_out, ldT, recvB, d_in);
+            else
+                launch(kRecv, k_recv_uniform<Q, true, false>, dim3(blocks), dim3(kBlock), st, tab, root, r0, r1,
+                       recv_out, t_out, ldT, recvB, d_in);
+        } else {
+            if (tabbed)
+                launch(kRecv, k_recv_uniform<Q, false, true>, dim3(blocks), dim3(kBlock), st, tab, root, r0, r1,
+                       recv_out, t_out, ldT, (int8_t *)nullptr, d_in);
+            else
+                launch(kRecv, k_recv_uniform<Q, false, false>, dim3(blocks), dim3(kBlock), st, tab, root, r0, r1,
+                       recv_out, t_out, ldT, (int8_t *)nullptr, d_in);
+        }
     }
     if (send_out) {
         if (full) {
@@ -253,7 +266,7 @@ int launch_sched(const SkipTab &tab, uint32_t root, uint32_t r0, uint32_t r1, in
 }
 
 typedef int (*LaunchFn)(const SkipTab &, uint32_t, uint32_t, uint32_t, int32_t *, int32_t *, slot_t *, uint64_t,
-                        int8_t *, int8_t *, hipStream_t);
+                        int8_t *, int8_t *, uint32_t *, hipStream_t);
 
 template <int... Qs>
 constexpr void fill_table(LaunchFn *t, std::integer_sequence<int, Qs...>) {
@@ -358,12 +371,22 @@ int64_t bcs_rounds(int32_t p, int32_t n) {
     return (int64_t)n - 1 + host_q(p);
 }
 
+// Scratch of a launch over all ranks with a send table: the slot-major receive table, then the digit masks of
+// all ranks (one word each).
+inline uint64_t slot_table_bytes(int32_t p, int q) { return slot_ld(p) * (uint64_t)q * sizeof(slot_t); }
+// The digit table pays while it stays in cache (measured on MI355X: receive rows of all ranks in 0.65-0.9 of the
+// walking kernel's time up to 2^24 ranks, table pass included; the same or worse from 2^25 ranks up): 0 beyond.
+constexpr uint64_t kDigitTableMax = (uint64_t)BCS_DIGIT_TABLE_MAX_BYTES;
+inline uint64_t digit_table_bytes(int32_t p) {
+    const uint64_t bytes = round_up((uint64_t)p * sizeof(uint32_t), 256);
+    return bytes <= kDigitTableMax ? bytes : 0;
+}
+
 int64_t bcs_sched_workspace_bytes(int32_t p, int32_t r0, int32_t r1, int want_send) {
     if (check_range(p, 0, r0, r1) != BCS_OK) return BCS_EINVAL;
     const int q = host_q(p);
     if (!want_send || q == 0 || !(r0 == 0 && r1 == p)) return 0;
-    const uint64_t ld = slot_ld(p);
-    return (int64_t)(ld * (uint64_t)q * sizeof(slot_t));
+    return (int64_t)(slot_table_bytes(p, q) + digit_table_bytes(p));
 }
 
 int bcs_sched_rooted_ws(int32_t p, int32_t root, int32_t r0, int32_t r1, int32_t *recv_out, int32_t *send_out,
@@ -380,8 +403,16 @@ int bcs_sched_rooted_ws(int32_t p, int32_t root, int32_t r0, int32_t r1, int32_t
     rc = ensure_lowtab((hipStream_t)stream);
     if (rc != BCS_OK) return rc;
     const uint64_t ld = slot_ld(p);
+    // all ranks: the digit table sits behind the slot-major table; a call for receive rows alone needs no
+    // workspace, and uses one that holds the digit table if it is given
+    uint32_t *dtab = nullptr;
+    const uint64_t dbytes = digit_table_bytes(p);
+    if (need > 0 && dbytes > 0) dtab = (uint32_t *)((char *)workspace + slot_table_bytes(p, q));
+    else if (need == 0 && dbytes > 0 && r0 == 0 && r1 == p && workspace && workspace_bytes >= dbytes &&
+             ((uintptr_t)workspace & 3u) == 0)
+        dtab = (uint32_t *)workspace;
     return launch_for_q(q)(tab, (uint32_t)root, (uint32_t)r0, (uint32_t)r1, recv_out, send_out,
-                           need > 0 ? (slot_t *)workspace : nullptr, ld, nullptr, nullptr, (hipStream_t)stream);
+                           need > 0 ? (slot_t *)workspace : nullptr, ld, nullptr, nullptr, dtab, (hipStream_t)stream);
 }
 
 int bcs_sched_rooted(int32_t p, int32_t root, int32_t r0, int32_t r1, int32_t *recv_out, int32_t *send_out,
@@ -576,7 +607,9 @@ int bcs_sched_expand_ws(int32_t p, int32_t root, int32_t n, int32_t *recv_out, i
             if (pieces > 0x7fffffffull) return BCS_EINVAL;
             int8_t *recvB = (int8_t *)workspace + base, *sendB = recvB + rows_bytes;
             rc = launch_for_q(q)(tab, (uint32_t)root, 0u, (uint32_t)p, recv_out, send_out, (slot_t *)workspace,
-                                 slot_ld(p), recvB, sendB, (hipStream_t)stream);
+                                 slot_ld(p), recvB, sendB,
+                                 digit_table_bytes(p) ? (uint32_t *)((char *)workspace + slot_table_bytes(p, q)) : nullptr,
+                                 (hipStream_t)stream);
             if (rc != BCS_OK) return rc;
             int32_t *outs[2] = {recv_blocks, send_blocks};
             const int8_t *srcs[2] = {recvB, sendB};
@@ -668,7 +701,7 @@ int bcs_allgather_tables_ws(int32_t p, int32_t n, int32_t r, int32_t *pack_idx, 
     if (rc != BCS_OK) return rc;
     const uint64_t ld = slot_ld(p);
     slot_t *recvT = (slot_t *)workspace;
-    rc = launch_for_q(q)(tab, 0u, 0u, (uint32_t)p, nullptr, nullptr, recvT, ld, nullptr, nullptr, st);
+    rc = launch_for_q(q)(tab, 0u, 0u, (uint32_t)p, nullptr, nullptr, recvT, ld, nullptr, nullptr, nullptr, st);
     if (rc != BCS_OK) return rc;
     const unsigned bx = (unsigned)(((uint64_t)p + kAgChunk - 1) / kAgChunk);
     const uint32_t x = (uint32_t)((q - (int)(R % (uint64_t)q)) % q);

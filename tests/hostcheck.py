@@ -28,6 +28,7 @@ def load():
         L.hc_range_blocks.argtypes = [ctypes.c_int32, ctypes.c_uint32, ctypes.c_uint32]
         L.hc_range_blocks.restype = ctypes.c_uint32
         L.hc_recv_rows_all.argtypes = [ctypes.c_int32, i32p]
+        L.hc_recv_rows_all_tab.argtypes = [ctypes.c_int32, ctypes.POINTER(ctypes.c_uint32), i32p]
         _lib = L
     return _lib
 
@@ -54,4 +55,14 @@ def recv_rows_all(p):
     q = (p - 1).bit_length()
     out = np.zeros((p, q), dtype=np.int32)
     assert load().hc_recv_rows_all(p, out.ctypes.data_as(ctypes.POINTER(ctypes.c_int32))) == 0
+    return out
+
+
+def recv_rows_all_tab(p):
+    """All receive rows through the table of every rank's digit mask (the path of the whole-range kernels)."""
+    q = (p - 1).bit_length()
+    out = np.zeros((p, q), dtype=np.int32)
+    dtab = np.zeros(p, dtype=np.uint32)
+    assert load().hc_recv_rows_all_tab(p, dtab.ctypes.data_as(ctypes.POINTER(ctypes.c_uint32)),
+                                       out.ctypes.data_as(ctypes.POINTER(ctypes.c_int32))) == 0
     return out

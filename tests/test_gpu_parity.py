@@ -101,6 +101,27 @@ def test_sub_ranges_roots_and_single_tables(bcs, oracle):
     assert bool((recv == 777).all()) and bool((send == 777).all())
 
 
+def test_receive_rows_with_and_without_the_digit_table(bcs, oracle):
+    """Receive rows of all ranks: by digit walks (no workspace) and from the table of all ranks' digit masks (a
+    workspace of a word a rank), at a small p, at the largest p that takes the table and at the first that does not
+    (there the workspace is ignored).  The two agree everywhere; sampled rows are the oracle's."""
+    rng = np.random.default_rng(24)
+    limit = bcs.DIGIT_TABLE_MAX_BYTES // 4
+    for p, root in [(70001, 69), (limit, 5), (limit + 1, limit)]:
+        q = bcs.bcs_q(p)
+        walked = torch.full((p, q), 777, dtype=torch.int32, device="cuda")
+        tabled = torch.full((p, q), 778, dtype=torch.int32, device="cuda")
+        ws = torch.empty(4 * p + 256, dtype=torch.uint8, device="cuda")
+        bcs.bcs_sched_rooted_ws(p, root, 0, p, walked, None, None)
+        bcs.bcs_sched_rooted_ws(p, root, 0, p, tabled, None, ws)
+        torch.cuda.synchronize()
+        assert torch.equal(walked, tabled), p
+        for r in [0, 1, root, p - 1, p // 2] + [int(x) for x in rng.integers(0, p, 150)]:
+            want = oracle.recvsched(p, (r - root) % p)
+            assert np.array_equal(tabled[r].cpu().numpy(), want), (p, r)
+        del walked, tabled, ws
+
+
 def test_every_q_from_1_to_31(bcs, oracle):
     """One kernel instance exists per q: each is run on two p of that bit length (one random, one 2^q or 2^(q-1)+1),
     over all ranks when that is cheap and over ragged chunks otherwise, with both ways of making send rows."""

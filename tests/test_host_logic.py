@@ -38,7 +38,7 @@ def test_host_helpers_and_argument_checks(oracle):
         assert L.bcs_sched_rooted_ws(p, root, r0, r1, fake, fake, None, 0, None) == bcs.EINVAL
     assert L.bcs_sched(5, 0, 5, None, None, None) == bcs.EINVAL
     assert L.bcs_sched_rooted_ws(5, 0, 0, 5, fake, fake, None, 0, None) == bcs.ENOMEM
-    assert L.bcs_sched_workspace_bytes(5, 0, 5, 1) == 3 * 256        # q rows of one byte an entry, padded to 256
+    assert L.bcs_sched_workspace_bytes(5, 0, 5, 1) == 3 * 256 + 256  # q rows of one byte an entry, padded to 256; a word a rank
     assert L.bcs_sched_workspace_bytes(5, 0, 4, 1) == 0 and L.bcs_sched_workspace_bytes(5, 0, 5, 0) == 0
     assert L.bcs_sched_workspace_bytes(5, 0, 6, 1) == bcs.EINVAL
     assert L.bcs_sched_batch(-1, fake, fake, fake, fake, fake, fake, None) == bcs.EINVAL
@@ -53,8 +53,8 @@ def test_host_helpers_and_argument_checks(oracle):
     assert L.bcs_expand_workspace_bytes(5, 300, 0, 5) == 256         # 6 rows of 12 bytes, padded
     assert L.bcs_expand_workspace_bytes(5, 30, 0, 5) == 0 and L.bcs_expand_workspace_bytes(2, 300, 0, 2) == 0
     assert L.bcs_expand_workspace_bytes(5, 0, 0, 5) == bcs.EINVAL
-    assert L.bcs_sched_expand_workspace_bytes(5, 300) == 3 * 256 + 2 * 256
-    assert L.bcs_sched_expand_workspace_bytes(5, 3) == 3 * 256
+    assert L.bcs_sched_expand_workspace_bytes(5, 300) == 3 * 256 + 256 + 2 * 256
+    assert L.bcs_sched_expand_workspace_bytes(5, 3) == 3 * 256 + 256
     for p, root, n in [(0, 0, 3), (5, 5, 3), (5, -1, 3), (5, 0, 0), (5, 0, 2**31 - 1)]:
         assert L.bcs_sched_expand(p, root, n, fake, fake, fake, fake, None) == bcs.EINVAL
         assert L.bcs_sched_expand_ws(p, root, n, fake, fake, fake, fake, None, 0, None) == bcs.EINVAL
@@ -108,6 +108,14 @@ def test_lane_code_all_rows_every_p_to_3000(oracle):
     for p in range(2, int(os.environ.get("BCS_EXHAUSTIVE_P_MAX", "3000")) + 1):
         recv, _ = oracle.sched_range(p, want_send=False, threads=4)
         assert np.array_equal(hostcheck.recv_rows_all(p), recv), p
+
+
+def test_lane_code_rows_from_the_digit_table(oracle):
+    """The path of the whole-range kernels: one digit walk per rank into a table, every window's end points read
+    from it.  Every rank of every p up to 1200 and of a few larger p."""
+    for p in list(range(2, 1201)) + [4097, 65537, 99991]:
+        recv, _ = oracle.sched_range(p, want_send=False, threads=4)
+        assert np.array_equal(hostcheck.recv_rows_all_tab(p), recv), p
 
 
 def test_lane_code_rows_equal_oracle_large_p(oracle):
