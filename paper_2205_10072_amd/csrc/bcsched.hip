@@ -306,7 +306,7 @@ ExpandArgs expand_args(uint64_t rows, uint64_t R, int q, int32_t n, const void *
 // schedule rows are a large share of the traffic, and two launches replace four); for longer rows the
 // flat stream of k_expand, whose workgroups are small and many, writes faster than a tile at a time.
 constexpr uint64_t kFusedShortR = 96;              // rows up to this length: fused for any p
-constexpr uint64_t kFusedMaxR = 160;               // rows up to this length: fused when p >= kFusedMinP
+constexpr uint64_t kFusedMaxR = 128;               // rows up to this length: fused when p >= kFusedMinP
 constexpr uint32_t kFusedMinP = 1u << 16;
 
 inline bool use_fused(int32_t p, int q, uint64_t R, bool aligned) {

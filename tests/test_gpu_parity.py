@@ -313,9 +313,9 @@ def test_tables_of_more_than_2_to_32_entries(bcs, oracle):
         _check_blocks_on_device(p, n, recv, rb, oracle, orecv, seed=p)
         del recv, rb, orecv
         torch.cuda.empty_cache()
-    p, n, root = (1 << 25) + 1, 135, 31415926                          # fused kernels, R = 160
+    p, n, root = (1 << 25) + 1, 103, 31415926                          # fused kernels, R = 128
     q, R = bcs.bcs_q(p), bcs.bcs_rounds(p, n)
-    assert R == 160 and p * R > 1 << 32
+    assert R == 128 and p * R > 1 << 32
     recv, send = dev_tables(p, q)
     rb = torch.full((p, R), 4242, dtype=torch.int32, device="cuda")
     sb = torch.full((p, R), 4242, dtype=torch.int32, device="cuda")
@@ -544,7 +544,7 @@ def test_sched_expand_one_call(bcs, oracle):
     _sched_expand_case(bcs, oracle, (1 << 21) + 77, 3, 5)               # q = 22
     _sched_expand_case(bcs, oracle, (1 << 22) + 1, 1, (1 << 22), own_ws=True)   # q = 23, n = 1
     for p, n, root in [(5, 14, 4), (255, 89, 0), (256, 89, 255), (257, 88, 1), (511, 9, 77), (513, 87, 512),
-                       (1000, 37, 123), (65536, 145, 9), (70001, 130, 70000), (65535, 81, 3)]:
+                       (1000, 37, 123), (65536, 113, 9), (70001, 100, 70000), (65535, 81, 3)]:
         _sched_expand_case(bcs, oracle, p, n, root)     # fused, tiles with ragged tails, both length classes
     for p, n, root in [(1, 1, 0), (1, 9, 0), (2, 40, 1), (3, 20, 2), (4, 33, 0), (9, 3, 8), (1000, 5, 1),
                        (1000, 200, 999), (4097, 100, 5), (65535, 145, 9), (70000, 1000, 7), (5, 700, 2), (33, 14, 32),
