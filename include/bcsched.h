@@ -99,7 +99,9 @@ int bcs_sched_rooted(int32_t p, int32_t root, int32_t r0, int32_t r1,
  * BCS_DIGIT_TABLE_MAX_BYTES / 4 ranks, the greedy skip sums of all ranks (the
  * walk of Alg. 2 kept as a mask, one word a rank): every end point of a
  * window of Alg. 4 is some rank, so the receive rows read these instead of
- * walking q + 2 times each. */
+ * walking q + 2 times each.  A call for a part of the ranks with send rows
+ * (Alg. 5) asks for the same table when filling it costs less than the walks
+ * it saves: (r1 - r0) q^2 >= 4 p. */
 #define BCS_DIGIT_TABLE_MAX_BYTES (64ll << 20)
 int64_t bcs_sched_workspace_bytes(int32_t p, int32_t r0, int32_t r1, int want_send);
 

@@ -409,5 +409,36 @@ BCS_HD void recv_row_tab(const Pol &pol, const uint32_t *__restrict__ dtab, uint
         recv_round(pol, v, i, pol.s(i + 1), d[i + 1], d[i], home, own, B, c, [&](uint32_t r) { return dtab[r]; }, emit);
 }
 
+// Rounds 0..last of the same row, for Alg. 5's neighbours (last varies, so the rounds stay a loop): the read for
+// the next round is issued before this round's work.  dv = dtab[v] comes from the caller.
+template <class Pol, class Emit>
+BCS_HD void recv_row_tab_upto(const Pol &pol, const uint32_t *__restrict__ dtab, uint32_t v, uint32_t dv, int last,
+                              Emit emit) {
+    static_assert(Pol::kScalarSkips, "one p per launch: the inert skips of the per-lane policy are no table indices");
+    const uint32_t p = pol.p();
+    const int q = pol.q();
+    const uint32_t lap = 1u << (q & 31);
+    auto end_point = [&](uint32_t s) -> uint32_t {       // digits of v - s with the lap digit, s in [1, p]
+        const bool ahead = v >= s;
+        return dtab[ahead ? v - s : v + p - s] | (ahead ? lap : 0u);
+    };
+    uint32_t d_hi = end_point(pol.sdyn(0));
+    uint32_t s_n = pol.sdyn(1);
+    uint32_t d_lo = end_point(s_n);
+    const int home = 31 - BCS_CLZ(dv);
+    const int own = dv ? __builtin_ctz(dv) : 0;
+    uint32_t B = v ? (1u << own) : 0u;
+    uint32_t c = 0;
+#pragma unroll 1
+    for (int i = 0; i <= last; ++i) {
+        const uint32_t s_next = pol.sdyn(i + 2 <= q ? i + 2 : q);
+        const uint32_t d_next = end_point(s_next);
+        recv_round(pol, v, i, s_n, d_lo, d_hi, home, own, B, c, [&](uint32_t r) { return dtab[r]; }, emit);
+        d_hi = d_lo;
+        d_lo = d_next;
+        s_n = s_next;
+    }
+}
+
 }  // namespace bcs
 #endif  // BCS_CORE_H

@@ -56,8 +56,8 @@ void row_from_table(const SkipTab &t, const uint32_t *dtab, uint32_t v, int last
         *reinterpret_cast<uint32_t *>(out) = digits(pol, v);      // table entry of rank v
         return;
     }
-    (void)last;
-    recv_row_tab(pol, dtab, v, [&](int i, int val) { out[i] = val; });
+    if (last == Q - 1) recv_row_tab(pol, dtab, v, [&](int i, int val) { out[i] = val; });
+    else recv_row_tab_upto(pol, dtab, v, dtab[v], last, [&](int i, int val) { out[i] = val; });
 }
 
 template <int Q>
@@ -149,6 +149,16 @@ int hc_recv_rows_all_tab(int32_t p, uint32_t *dtab, int32_t *out) {
         dtab[v] = (uint32_t)word;
     }
     for (int32_t v = 0; v < p; ++v) g_tabrow[q](t, dtab, (uint32_t)v, q - 1, out + (size_t)v * q);
+    return 0;
+}
+
+// entries 0..last of one row from a filled table of digit masks (what Alg. 5 asks of a neighbour's row)
+int hc_recv_row_tab(int32_t p, const uint32_t *dtab, int32_t v, int last, int32_t *out) {
+    if (p < 2 || v < 0 || v >= p || !dtab) return -1;
+    ready();
+    SkipTab t;
+    fill_skips(p, t);
+    g_tabrow[host_q(p)](t, dtab, (uint32_t)v, last, out);
     return 0;
 }
 

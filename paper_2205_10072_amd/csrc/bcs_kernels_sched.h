@@ -187,9 +187,10 @@ __global__ __launch_bounds__(kBlock) void k_send_lookup(const SkipTab tab, const
 
 // K1b: send rows of ranks [r0, r1) with no neighbour rows at hand (Alg. 5): entry i is entry i of the
 // receive schedule of the to-neighbour, which costs that neighbour's rounds 0..i.
-template <int Q>
+template <int Q, bool TAB>
 __global__ __launch_bounds__(kBlock) void k_send_recompute(const SkipTab tab, uint32_t root, uint32_t r0, uint32_t r1,
-                                                           int32_t *__restrict__ send_out) {
+                                                           int32_t *__restrict__ send_out,
+                                                           const uint32_t *__restrict__ dtab) {
     constexpr int kStride = Q | 1;
     __shared__ __align__(16) int32_t tile[kBlock * kStride];
     __shared__ uint32_t lowtab[kLowShapeBytes / 4];
@@ -212,7 +213,9 @@ __global__ __launch_bounds__(kBlock) void k_send_recompute(const SkipTab tab, ui
     for (int i = 0; i < Q; ++i) {
         uint32_t t = v + tab.s[i];
         t = t >= p ? t - p : t;
-        const uint32_t dt = digits(pol, t);
+        uint32_t dt;
+        if constexpr (TAB) dt = dtab[t];                  // digit masks of all ranks from k_digits
+        else dt = digits(pol, t);
         int32_t keep = dt ? __builtin_ctz(dt) : 0;
         // Round i is the neighbour's home round when its highest digit is i: then the entry is its baseblock and
         // none of its earlier rounds matters.  A wave of consecutive ranks below skips[i+1] - skips[i] is in that
@@ -220,7 +223,9 @@ __global__ __launch_bounds__(kBlock) void k_send_recompute(const SkipTab tab, ui
         const bool home_round = dt != 0u && (31 - __clz((int)dt)) == i;
         if (__any(!home_round)) {
             int32_t got = 0;
-            recv_row_from(pol, t, dt, i, [&](int j, int val) { got = (j == i) ? val : got; });
+            auto last_entry = [&](int j, int val) { got = (j == i) ? val : got; };
+            if constexpr (TAB) recv_row_tab_upto(pol, dtab, t, dt, i, last_entry);
+            else recv_row_from(pol, t, dt, i, last_entry);
             keep = got;
         }
         my[i] = keep;

@@ -233,8 +233,10 @@ int launch_sched(const SkipTab &tab, uint32_t root, uint32_t r0, uint32_t r1, in
     // the slot-major copy feeds the send look-up; with neither table asked for it is the only output
     const bool want_t = full && recvT && (send_out || !recv_out);
     if (recv_out || want_t) {
-        const bool tabbed = full && dtab;        // all ranks: one walk a rank into the table, the rows read it
-        if (tabbed) launch(kDigits, k_digits<Q>, dim3(blocks), dim3(kBlock), st, tab, dtab);
+        const bool tabbed = dtab != nullptr;     // one walk a rank (all p of them) into the table, the rows read it
+        if (tabbed)
+            launch(kDigits, k_digits<Q>, dim3((unsigned)(((uint64_t)tab.s[Q] + kBlock - 1) / kBlock)), dim3(kBlock), st,
+                   tab, dtab);
         slot_t *const t_out = want_t ? recvT : (slot_t *)nullptr;
         const uint32_t *const d_in = dtab;
         if (full && recvB && recv_out) {
@@ -257,8 +259,15 @@ int launch_sched(const SkipTab &tab, uint32_t root, uint32_t r0, uint32_t r1, in
         if (full) {
             launch(kSendLookup, k_send_lookup<Q>, dim3(blocks), dim3(kBlock), st, tab, (const slot_t *)recvT, ldT,
                    send_out, sendB);
+        } else if (dtab) {
+            if (!recv_out)                      // no receive rows asked for: the table has not been filled yet
+                launch(kDigits, k_digits<Q>, dim3((unsigned)(((uint64_t)tab.s[Q] + kBlock - 1) / kBlock)), dim3(kBlock),
+                       st, tab, dtab);
+            launch(kSendRecompute, k_send_recompute<Q, true>, dim3(blocks), dim3(kBlock), st, tab, root, r0, r1, send_out,
+                   (const uint32_t *)dtab);
         } else {
-            launch(kSendRecompute, k_send_recompute<Q>, dim3(blocks), dim3(kBlock), st, tab, root, r0, r1, send_out);
+            launch(kSendRecompute, k_send_recompute<Q, false>, dim3(blocks), dim3(kBlock), st, tab, root, r0, r1,
+                   send_out, (const uint32_t *)nullptr);
         }
     }
     hipError_t e = hipGetLastError();
@@ -382,10 +391,17 @@ inline uint64_t digit_table_bytes(int32_t p) {
     return bytes <= kDigitTableMax ? bytes : 0;
 }
 
+// A part of the ranks with send rows (Alg. 5) takes the digit table when filling it (p walks) costs less than the
+// walks it saves (about q^2 / 2 a rank).
+inline bool partial_range_tabled(int32_t p, int q, int32_t r0, int32_t r1) {
+    return digit_table_bytes(p) > 0 && (uint64_t)(r1 - r0) * (uint64_t)(q * q) >= 4ull * (uint64_t)p;
+}
+
 int64_t bcs_sched_workspace_bytes(int32_t p, int32_t r0, int32_t r1, int want_send) {
     if (check_range(p, 0, r0, r1) != BCS_OK) return BCS_EINVAL;
     const int q = host_q(p);
-    if (!want_send || q == 0 || !(r0 == 0 && r1 == p)) return 0;
+    if (!want_send || q == 0) return 0;
+    if (!(r0 == 0 && r1 == p)) return partial_range_tabled(p, q, r0, r1) ? (int64_t)digit_table_bytes(p) : 0;
     return (int64_t)(slot_table_bytes(p, q) + digit_table_bytes(p));
 }
 
@@ -405,14 +421,16 @@ int bcs_sched_rooted_ws(int32_t p, int32_t root, int32_t r0, int32_t r1, int32_t
     const uint64_t ld = slot_ld(p);
     // all ranks: the digit table sits behind the slot-major table; a call for receive rows alone needs no
     // workspace, and uses one that holds the digit table if it is given
+    const bool full = (r0 == 0 && r1 == p);
     uint32_t *dtab = nullptr;
     const uint64_t dbytes = digit_table_bytes(p);
-    if (need > 0 && dbytes > 0) dtab = (uint32_t *)((char *)workspace + slot_table_bytes(p, q));
-    else if (need == 0 && dbytes > 0 && r0 == 0 && r1 == p && workspace && workspace_bytes >= dbytes &&
+    if (need > 0 && dbytes > 0) dtab = (uint32_t *)((char *)workspace + (full ? slot_table_bytes(p, q) : 0));
+    else if (need == 0 && dbytes > 0 && full && workspace && workspace_bytes >= dbytes &&
              ((uintptr_t)workspace & 3u) == 0)
         dtab = (uint32_t *)workspace;
     return launch_for_q(q)(tab, (uint32_t)root, (uint32_t)r0, (uint32_t)r1, recv_out, send_out,
-                           need > 0 ? (slot_t *)workspace : nullptr, ld, nullptr, nullptr, dtab, (hipStream_t)stream);
+                           need > 0 && full ? (slot_t *)workspace : nullptr, ld, nullptr, nullptr, dtab,
+                           (hipStream_t)stream);
 }
 
 int bcs_sched_rooted(int32_t p, int32_t root, int32_t r0, int32_t r1, int32_t *recv_out, int32_t *send_out,

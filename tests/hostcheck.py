@@ -29,6 +29,7 @@ def load():
         L.hc_range_blocks.restype = ctypes.c_uint32
         L.hc_recv_rows_all.argtypes = [ctypes.c_int32, i32p]
         L.hc_recv_rows_all_tab.argtypes = [ctypes.c_int32, ctypes.POINTER(ctypes.c_uint32), i32p]
+        L.hc_recv_row_tab.argtypes = [ctypes.c_int32, ctypes.POINTER(ctypes.c_uint32), ctypes.c_int32, ctypes.c_int, i32p]
         _lib = L
     return _lib
 
@@ -58,11 +59,19 @@ def recv_rows_all(p):
     return out
 
 
-def recv_rows_all_tab(p):
+def recv_rows_all_tab(p, want_table=False):
     """All receive rows through the table of every rank's digit mask (the path of the whole-range kernels)."""
     q = (p - 1).bit_length()
     out = np.zeros((p, q), dtype=np.int32)
     dtab = np.zeros(p, dtype=np.uint32)
     assert load().hc_recv_rows_all_tab(p, dtab.ctypes.data_as(ctypes.POINTER(ctypes.c_uint32)),
                                        out.ctypes.data_as(ctypes.POINTER(ctypes.c_int32))) == 0
+    return (out, dtab) if want_table else out
+
+
+def recv_row_tab(p, dtab, v, last):
+    """Entries 0..last of one row from a filled table (the path Alg. 5's kernel takes for a neighbour's row)."""
+    out = np.full(32, 12345, dtype=np.int32)
+    assert load().hc_recv_row_tab(p, dtab.ctypes.data_as(ctypes.POINTER(ctypes.c_uint32)), v, last,
+                                  out.ctypes.data_as(ctypes.POINTER(ctypes.c_int32))) == 0
     return out

@@ -39,7 +39,9 @@ def test_host_helpers_and_argument_checks(oracle):
     assert L.bcs_sched(5, 0, 5, None, None, None) == bcs.EINVAL
     assert L.bcs_sched_rooted_ws(5, 0, 0, 5, fake, fake, None, 0, None) == bcs.ENOMEM
     assert L.bcs_sched_workspace_bytes(5, 0, 5, 1) == 3 * 256 + 256  # q rows of one byte an entry, padded to 256; a word a rank
-    assert L.bcs_sched_workspace_bytes(5, 0, 4, 1) == 0 and L.bcs_sched_workspace_bytes(5, 0, 5, 0) == 0
+    assert L.bcs_sched_workspace_bytes(5, 0, 1, 1) == 0 and L.bcs_sched_workspace_bytes(5, 0, 5, 0) == 0
+    assert L.bcs_sched_workspace_bytes(5, 0, 4, 1) == 256           # a part of the ranks large enough for the digit table
+    assert L.bcs_sched_workspace_bytes(1 << 20, 5, 105, 1) == 0
     assert L.bcs_sched_workspace_bytes(5, 0, 6, 1) == bcs.EINVAL
     assert L.bcs_sched_batch(-1, fake, fake, fake, fake, fake, fake, None) == bcs.EINVAL
     assert L.bcs_sched_batch(4, None, fake, fake, fake, fake, fake, None) == bcs.EINVAL
@@ -116,6 +118,15 @@ def test_lane_code_rows_from_the_digit_table(oracle):
     for p in list(range(2, 1201)) + [4097, 65537, 99991]:
         recv, _ = oracle.sched_range(p, want_send=False, threads=4)
         assert np.array_equal(hostcheck.recv_rows_all_tab(p), recv), p
+    # prefixes of rows, as Alg. 5 asks for them
+    rng = np.random.default_rng(5)
+    for p in [2, 3, 5, 17, 100, 1000, 4097, 99991]:
+        recv, _ = oracle.sched_range(p, want_send=False, threads=4)
+        _, dtab = hostcheck.recv_rows_all_tab(p, want_table=True)
+        q = recv.shape[1]
+        for v in [0, 1, p - 1] + [int(x) for x in rng.integers(0, p, 60)]:
+            for last in {0, q - 1, int(rng.integers(0, q))}:
+                assert np.array_equal(hostcheck.recv_row_tab(p, dtab, v, last)[:last + 1], recv[v, :last + 1]), (p, v, last)
 
 
 def test_lane_code_rows_equal_oracle_large_p(oracle):
