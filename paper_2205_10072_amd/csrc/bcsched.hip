@@ -719,7 +719,8 @@ int bcs_allgather_tables_ws(int32_t p, int32_t n, int32_t r, int32_t *pack_idx, 
     if (rc != BCS_OK) return rc;
     const uint64_t ld = slot_ld(p);
     slot_t *recvT = (slot_t *)workspace;
-    rc = launch_for_q(q)(tab, 0u, 0u, (uint32_t)p, nullptr, nullptr, recvT, ld, nullptr, nullptr, nullptr, st);
+    uint32_t *dtab = digit_table_bytes(p) ? (uint32_t *)((char *)workspace + slot_table_bytes(p, q)) : nullptr;
+    rc = launch_for_q(q)(tab, 0u, 0u, (uint32_t)p, nullptr, nullptr, recvT, ld, nullptr, nullptr, dtab, st);
     if (rc != BCS_OK) return rc;
     const unsigned bx = (unsigned)(((uint64_t)p + kAgChunk - 1) / kAgChunk);
     const uint32_t x = (uint32_t)((q - (int)(R % (uint64_t)q)) % q);
