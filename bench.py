@@ -32,10 +32,10 @@ INT_VALU_PEAK_GOPS = 256 * 4 * 16 * 2.4     # CUs x SIMDs x lanes x GHz = 39 321
 # HBM bytes per launch at this workload, from the rocprofv3 counter runs summarised in
 # profiles/bench_c2_kernels.md (FETCH_SIZE scaled x2.0, WRITE_SIZE x1.0 by the 1 GiB copy calibration).
 PROFILED_TRAFFIC_BYTES = {
-    "k_expand_rows": (2 * 35340 + 1130552) * 1024,
-    "k_recv_uniform": (2 * 11287 + 132103) * 1024,
-    "k_send_lookup": (2 * 15952 + 110592) * 1024,
-    "k_digits": (2 * 29 + 4096) * 1024,
+    "k_expand_rows": (2 * 35344 + 1130583) * 1024,
+    "k_recv_uniform": (2 * 11364 + 132103) * 1024,
+    "k_send_lookup": (2 * 15914 + 110592) * 1024,
+    "k_digits": (2 * 32 + 4096) * 1024,
 }
 
 
