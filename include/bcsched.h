@@ -24,7 +24,8 @@
  *   - Return value: BCS_OK (0) or a negative BCS_E* code.  On an error nothing
  *     has been enqueued and no output is touched.  No call throws.
  *   - No call allocates or frees its outputs.  bcs_sched* with a send table
- *     over the full rank range need scratch memory: the *_ws variants take it
+ *     over the full rank range, or over a large part of it, need scratch
+ *     memory (bcs_sched_workspace_bytes says how much): the *_ws variants take it
  *     from the caller, the plain variants keep one allocation per device that
  *     grows on demand and is released by bcs_release().  Calls that share that
  *     allocation must be ordered on one stream.
