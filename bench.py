@@ -64,7 +64,7 @@ def digit_walks_per_rank(p, skips):
 
 
 def valu_ops_per_rank_tabled(q):
-    """The same row when the digit masks of all ranks are in a table (launches over all ranks of up to 2^24 ranks):
+    """The same row when the digit masks of all ranks are in a table (launches over all ranks):
     55 ops a round, which include the read of the round's end point, and 50 of set-up."""
     return 55 * q + 50
 
@@ -427,7 +427,7 @@ def main():
         torch.cuda.synchronize()
         del a, b
     valu_peak_measured = measure_valu_peak(torch, bcs)
-    tabled = 4 * P <= bcs.DIGIT_TABLE_MAX_BYTES          # receive rows read the digit masks k_digits leaves
+    tabled = True                                        # all ranks: receive rows read the digit masks k_digits leaves
     walks = 1.0 if tabled else digit_walks_per_rank(P, bcs.bcs_skips(P))
     steps = max(1, min(args.steps, 1000))
     # Two timed regions of exactly `steps` steps each.  The first is the plain path and gives the throughput; in the

@@ -96,22 +96,21 @@ int bcs_sched_rooted(int32_t p, int32_t root, int32_t r0, int32_t r1,
 
 /* Scratch bytes bcs_sched_rooted_ws needs for these arguments (0 when none).
  * Negative: BCS_EINVAL.  A call over all ranks that also wants send rows keeps
- * there the receive entries slot by slot (one byte each) and, for p up to
- * BCS_DIGIT_TABLE_MAX_BYTES / 4 ranks, the greedy skip sums of all ranks (the
- * walk of Alg. 2 kept as a mask, one word a rank): every end point of a
+ * there the receive entries slot by slot (one byte each) and the greedy skip
+ * sums of all ranks (the walk of Alg. 2 kept as a mask, one word a rank,
+ * rounded up to 256 bytes): every end point of a
  * window of Alg. 4 is some rank, so the receive rows read these instead of
  * walking q + 2 times each.  A call for a part of the ranks with send rows
  * (Alg. 5) asks for the same table when filling it costs less than the walks
- * it saves: (r1 - r0) q^2 >= 4 p. */
-#define BCS_DIGIT_TABLE_MAX_BYTES (64ll << 20)
+ * it saves: (r1 - r0) q^2 >= 8 p. */
 int64_t bcs_sched_workspace_bytes(int32_t p, int32_t r0, int32_t r1, int want_send);
 
 /* bcs_sched_rooted with caller-provided scratch.  `workspace` is device
  * memory, 256-byte aligned, of at least bcs_sched_workspace_bytes(...) bytes;
  * its contents are undefined afterwards.  BCS_ENOMEM if it is too small or
  * NULL while scratch is needed.  Performs no allocation.  A call over all
- * ranks for receive rows alone needs none; given 4 p bytes (rounded up to 256,
- * at most BCS_DIGIT_TABLE_MAX_BYTES) it uses them for the table of skip sums. */
+ * ranks for receive rows alone needs none; given 4 p bytes (rounded up to 256)
+ * it uses them for the table of skip sums. */
 int bcs_sched_rooted_ws(int32_t p, int32_t root, int32_t r0, int32_t r1,
                         int32_t *recv_out, int32_t *send_out,
                         void *workspace, size_t workspace_bytes, void *stream);

@@ -31,7 +31,6 @@ SYMBOLS = (
     "bcs_pack_workspace_bytes", "bcs_pack_round", "bcs_unpack_round", "bcs_allgather_plan", "bcs_census_plan",
 )
 KERNEL_COUNT = 15
-DIGIT_TABLE_MAX_BYTES = 64 << 20      # BCS_DIGIT_TABLE_MAX_BYTES
 VALU_PEAK_OPS_PER_ITER = 32
 
 _lib = None

@@ -383,18 +383,15 @@ int64_t bcs_rounds(int32_t p, int32_t n) {
 // Scratch of a launch over all ranks with a send table: the slot-major receive table, then the digit masks of
 // all ranks (one word each).
 inline uint64_t slot_table_bytes(int32_t p, int q) { return slot_ld(p) * (uint64_t)q * sizeof(slot_t); }
-// The digit table pays while it stays in cache (measured on MI355X: receive rows of all ranks in 0.65-0.9 of the
-// walking kernel's time up to 2^24 ranks, table pass included; the same or worse from 2^25 ranks up): 0 beyond.
-constexpr uint64_t kDigitTableMax = (uint64_t)BCS_DIGIT_TABLE_MAX_BYTES;
-inline uint64_t digit_table_bytes(int32_t p) {
-    const uint64_t bytes = round_up((uint64_t)p * sizeof(uint32_t), 256);
-    return bytes <= kDigitTableMax ? bytes : 0;
-}
+// The digit table pays at every size (measured on MI355X: receive rows of all ranks in 0.57-0.73 of the walking
+// kernel's time from 2^18 to 2^27 ranks, table pass included), with all of a row's reads issued up front.
+inline uint64_t digit_table_bytes(int32_t p) { return round_up((uint64_t)p * sizeof(uint32_t), 256); }
 
 // A part of the ranks with send rows (Alg. 5) takes the digit table when filling it (p walks) costs less than the
-// walks it saves (about q^2 / 2 a rank).
+// walks it saves (about q^2 / 2 a rank).  Measured: 2^20 ranks of 2^20+1 gain 0.27 ms, 2^20 ranks of 2^27-1
+// (q^2 (r1 - r0) = 5.7 p) lose 0.02 ms to the 0.32 ms the table of 2^27 ranks takes.
 inline bool partial_range_tabled(int32_t p, int q, int32_t r0, int32_t r1) {
-    return digit_table_bytes(p) > 0 && (uint64_t)(r1 - r0) * (uint64_t)(q * q) >= 4ull * (uint64_t)p;
+    return (uint64_t)(r1 - r0) * (uint64_t)(q * q) >= 8ull * (uint64_t)p;
 }
 
 int64_t bcs_sched_workspace_bytes(int32_t p, int32_t r0, int32_t r1, int want_send) {

@@ -103,11 +103,10 @@ def test_sub_ranges_roots_and_single_tables(bcs, oracle):
 
 def test_receive_rows_with_and_without_the_digit_table(bcs, oracle):
     """Receive rows of all ranks: by digit walks (no workspace) and from the table of all ranks' digit masks (a
-    workspace of a word a rank), at a small p, at the largest p that takes the table and at the first that does not
-    (there the workspace is ignored).  The two agree everywhere; sampled rows are the oracle's."""
+    workspace of a word a rank), at a small p and at two large ones.  The two agree everywhere; sampled rows are
+    the oracle's."""
     rng = np.random.default_rng(24)
-    limit = bcs.DIGIT_TABLE_MAX_BYTES // 4
-    for p, root in [(70001, 69), (limit, 5), (limit + 1, limit)]:
+    for p, root in [(70001, 69), (1 << 24, 5), ((1 << 25) + 12345, 1 << 25)]:
         q = bcs.bcs_q(p)
         walked = torch.full((p, q), 777, dtype=torch.int32, device="cuda")
         tabled = torch.full((p, q), 778, dtype=torch.int32, device="cuda")

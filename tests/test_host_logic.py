@@ -40,7 +40,7 @@ def test_host_helpers_and_argument_checks(oracle):
     assert L.bcs_sched_rooted_ws(5, 0, 0, 5, fake, fake, None, 0, None) == bcs.ENOMEM
     assert L.bcs_sched_workspace_bytes(5, 0, 5, 1) == 3 * 256 + 256  # q rows of one byte an entry, padded to 256; a word a rank
     assert L.bcs_sched_workspace_bytes(5, 0, 1, 1) == 0 and L.bcs_sched_workspace_bytes(5, 0, 5, 0) == 0
-    assert L.bcs_sched_workspace_bytes(5, 0, 4, 1) == 256           # a part of the ranks large enough for the digit table
+    assert L.bcs_sched_workspace_bytes(5, 0, 4, 1) == 0 and L.bcs_sched_workspace_bytes(9, 0, 8, 1) == 256   # 8 * 16 >= 8 * 9
     assert L.bcs_sched_workspace_bytes(1 << 20, 5, 105, 1) == 0
     assert L.bcs_sched_workspace_bytes(5, 0, 6, 1) == bcs.EINVAL
     assert L.bcs_sched_batch(-1, fake, fake, fake, fake, fake, fake, None) == bcs.EINVAL
