@@ -121,6 +121,50 @@ def test_receive_rows_with_and_without_the_digit_table(bcs, oracle):
         del walked, tabled, ws
 
 
+def test_sched_random_ranges(bcs, oracle):
+    """Seeded random p, roots, rank ranges (whole, ragged, short) and choices of tables, through the plain call and the
+    one with a caller workspace: every kernel variant behind bcs_sched_rooted (digit walks, digit table, look-up,
+    recomputation) gets its share."""
+    rng = np.random.default_rng(2205_10072)
+    tabled_parts = 0
+    for case in range(400):
+        bits = int(rng.integers(1, 18))
+        p = int(rng.integers(max(2, 1 << (bits - 1)), (1 << bits) + 2))
+        root = int(rng.integers(0, p))
+        q = bcs.bcs_q(p)
+        kind = int(rng.integers(0, 4))
+        if kind == 0:
+            r0, r1 = 0, p
+        elif kind == 1:
+            r0 = int(rng.integers(0, p))
+            r1 = int(rng.integers(r0, p + 1))
+        elif kind == 2:
+            r0 = int(rng.integers(0, max(1, p // 8)))
+            r1 = p - int(rng.integers(0, max(1, p // 8)))
+        else:
+            r0 = int(rng.integers(0, p))
+            r1 = min(p, r0 + int(rng.integers(1, 700)))
+        if r1 <= r0:
+            continue
+        want = int(rng.integers(1, 4))
+        recv = torch.full((r1 - r0, q), 777, dtype=torch.int32, device="cuda") if want & 1 else None
+        send = torch.full((r1 - r0, q), 778, dtype=torch.int32, device="cuda") if want & 2 else None
+        need = bcs.bcs_sched_workspace_bytes(p, r0, r1, 1 if send is not None else 0)
+        tabled_parts += need > 0 and not (r0 == 0 and r1 == p)
+        if rng.integers(0, 2):
+            ws = torch.empty(need + (4 * p + 512) * int(rng.integers(0, 2)), dtype=torch.uint8, device="cuda")
+            bcs.bcs_sched_rooted_ws(p, root, r0, r1, recv, send, ws if ws.numel() else None)
+        else:
+            bcs.bcs_sched_rooted(p, root, r0, r1, recv, send)
+        torch.cuda.synchronize()
+        orecv, osend = oracle.sched_range(p, root=root, r0=r0, r1=r1, threads=8)
+        if recv is not None:
+            assert np.array_equal(recv.cpu().numpy(), orecv), ("recv", p, root, r0, r1, want)
+        if send is not None:
+            assert np.array_equal(send.cpu().numpy(), osend), ("send", p, root, r0, r1, want)
+    assert tabled_parts > 20
+
+
 def test_every_q_from_1_to_31(bcs, oracle):
     """One kernel instance exists per q: each is run on two p of that bit length (one random, one 2^q or 2^(q-1)+1),
     over all ranks when that is cheap and over ragged chunks otherwise, with both ways of making send rows."""
