@@ -370,8 +370,8 @@ def bench_pack_round(torch, bcs, args):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--workload", choices=["step", "allgather-tables", "pack-round", "configs"], default="step",
                     help="step (default): the hot path this benchmark is about.  allgather-tables: the first widening, "
