@@ -114,10 +114,19 @@ def cpu_baseline(budget_s=10.0):
     t1 = time.perf_counter()
     one_step(1)
     single = time.perf_counter() - t1
+    model = ""
+    try:
+        with open("/proc/cpuinfo") as f:
+            for line in f:
+                if line.startswith("model name"):
+                    model = line.split(":", 1)[1].strip()
+                    break
+    except OSError:
+        pass
     return {"value": done * P / el, "unit": "rank-schedules/s", "cores": threads, "kind": "oracle",
             "sample": "%d whole steps (all %d ranks: recv by Alg. 4, send by look-up, expansion n=%d), %.1f s"
                       % (done, P, N_BLOCKS, el),
-            "single_thread_value": P / single}
+            "single_thread_value": P / single, "host_cpus": os.cpu_count(), "cpu_model": model}
 
 
 AG_PROCESS = 777777        # the process whose tables are built in the allgather-tables workload
