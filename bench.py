@@ -39,6 +39,12 @@ PROFILED_TRAFFIC_BYTES = {
 }
 
 
+# SQ_INSTS_VALU / SQ_WAVES and SQ_THREAD_CYCLES_VALU / SQ_ACTIVE_INST_VALU of k_recv_uniform at this workload, from the
+# same profile: vector instructions a wave (one rank a lane) and lanes active per vector instruction.
+PROFILED_VALU_PER_WAVE = 1275
+PROFILED_ACTIVE_LANES = 64.0
+
+
 def digit_walks_per_rank(p, skips):
     """Digit walks k_recv_uniform runs per rank at root 0, averaged over all ranks: one for the rank itself, one for
     the first window's upper end, and one per round n = 1..q-1 in which some lane of the wave lacks skips[n] among
@@ -491,8 +497,12 @@ def main():
             ent.update(bound="hbm", achieved=nbytes / avg_ms / 1e6, peak=HBM_PEAK_GBS, unit="GB/s")
         elif name == "k_recv_uniform":
             ops = (valu_ops_per_rank_tabled(q) if tabled else valu_ops_per_rank(q, walks)) * P
+            waves = (P + 255) // 256 * 4
             ent.update(bound="alu", achieved=ops / avg_ms / 1e6, peak=INT_VALU_PEAK_GOPS, unit="Gop/s",
-                       peak_measured=valu_peak_measured, frac_of_measured=ops / avg_ms / 1e6 / valu_peak_measured)
+                       peak_measured=valu_peak_measured, frac_of_measured=ops / avg_ms / 1e6 / valu_peak_measured,
+                       # share of the kernel's time its vector instructions need on 1024 SIMDs at 4 cycles each
+                       valu_busy=PROFILED_VALU_PER_WAVE * 4 * waves / (1024 * 2.4e9) / (avg_ms * 1e-3),
+                       active_lane_fraction=PROFILED_ACTIVE_LANES / 64.0)
         elif name == "k_digits":
             ops = (3 * max(q - 7, 0) + 3 + 12) * P              # one walk a rank, address and store
             ent.update(bound="alu", achieved=ops / avg_ms / 1e6, peak=INT_VALU_PEAK_GOPS, unit="Gop/s")
