@@ -106,7 +106,7 @@ def test_lane_code_rows_equal_oracle_small_p(oracle):
 
 def test_lane_code_all_rows_every_p_to_3000(oracle):
     """The digit form's closed expressions are not proved in general: every rank of every p up to 3000
-    (BCS_EXHAUSTIVE_P_MAX in the environment raises the limit; 30000 takes about twenty minutes on 8 cores)."""
+    (BCS_EXHAUSTIVE_P_MAX in the environment raises the limit; 40000 takes eleven minutes on 8 cores)."""
     for p in range(2, int(os.environ.get("BCS_EXHAUSTIVE_P_MAX", "3000")) + 1):
         recv, _ = oracle.sched_range(p, want_send=False, threads=4)
         assert np.array_equal(hostcheck.recv_rows_all(p), recv), p
