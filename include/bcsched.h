@@ -20,15 +20,23 @@
  *     the caller, at least 4-byte aligned; "host" pointers are plain memory.
  *   - All tables are int32, row-major, one row per rank.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
- *     Work is enqueued on it; no call waits for the device.
+ *     Work is enqueued on it.  No call waits for the device, with one
+ *     exception: a plain (not *_ws) call that finds the library's per-device
+ *     scratch too small synchronises the device, frees it and allocates a
+ *     larger one (so such a call cannot be part of a stream capture).
  *   - Return value: BCS_OK (0) or a negative BCS_E* code.  On an error nothing
  *     has been enqueued and no output is touched.  No call throws.
  *   - No call allocates or frees its outputs.  bcs_sched* with a send table
  *     over the full rank range, or over a large part of it, need scratch
  *     memory (bcs_sched_workspace_bytes says how much): the *_ws variants take it
  *     from the caller, the plain variants keep one allocation per device that
- *     grows on demand and is released by bcs_release().  Calls that share that
- *     allocation must be ordered on one stream.
+ *     grows on demand and is released by bcs_release().  Plain calls on one
+ *     device share that allocation: the library orders them itself (a plain
+ *     call on another stream than the plain call before it is made to wait,
+ *     on the device, for that stream's work), so they never overlap; callers
+ *     that want overlap use the *_ws variants with a workspace per stream.
+ *     A stream handed to a plain call should stay alive until the next plain
+ *     call on the device (else that call synchronises the device instead).
  *   - The first call on a device that builds schedules (bcs_sched*,
  *     bcs_sched_batch, bcs_allgather_tables*) also enqueues, ahead of its own
  *     work, a short kernel that fills a 544 KiB table kept in the library's
@@ -88,7 +96,7 @@ int bcs_sched(int32_t p, int32_t r0, int32_t r1,
 
 /* As bcs_sched for an arbitrary root: the row of rank r is the schedule of
  * the virtual rank (r - root + p) mod p (Section 2, paragraph after Alg. 2;
- * Section 2.5 uses this for every root at once).  Neighbours are unchanged:
+ * Section 2.4 uses this for every root at once).  Neighbours are unchanged:
  * rank r still sends to (r + skips[k]) mod p.
  * Also BCS_EINVAL for root outside [0, p). */
 int bcs_sched_rooted(int32_t p, int32_t root, int32_t r0, int32_t r1,
@@ -108,7 +116,8 @@ int64_t bcs_sched_workspace_bytes(int32_t p, int32_t r0, int32_t r1, int want_se
 /* bcs_sched_rooted with caller-provided scratch.  `workspace` is device
  * memory, 256-byte aligned, of at least bcs_sched_workspace_bytes(...) bytes;
  * its contents are undefined afterwards.  BCS_ENOMEM if it is too small or
- * NULL while scratch is needed.  Performs no allocation.  A call over all
+ * NULL while scratch is needed, BCS_EINVAL if it is needed and not 256-byte
+ * aligned.  Performs no allocation.  A call over all
  * ranks for receive rows alone needs none; given 4 p bytes (rounded up to 256)
  * it uses them for the table of skip sums. */
 int bcs_sched_rooted_ws(int32_t p, int32_t root, int32_t r0, int32_t r1,
@@ -179,7 +188,8 @@ int bcs_expand_ws(int32_t p, int32_t n, int32_t r0, int32_t r1,
  * (without the byte rows).  p = 1: both block tables get n-1 columns of
  * BCS_NO_BLOCK.
  * BCS_EINVAL: p < 1, root outside [0, p), n < 1, n > BCS_MAX_N, a required
- * table NULL.  BCS_ENOMEM: workspace NULL or too small. */
+ * table NULL, a workspace that is not 256-byte aligned.  BCS_ENOMEM: workspace
+ * NULL or too small. */
 int64_t bcs_sched_expand_workspace_bytes(int32_t p, int32_t n);
 int bcs_sched_expand(int32_t p, int32_t root, int32_t n,
                      int32_t *recv_out, int32_t *send_out,
@@ -190,7 +200,7 @@ int bcs_sched_expand_ws(int32_t p, int32_t root, int32_t n,
                         void *workspace, size_t workspace_bytes, void *stream);
 
 /* Index tables of the irregular allgather for ONE process r (Alg. 9, its pack
- * and unpack loops; Section 2.5): in real round j the process packs, for every
+ * and unpack loops; Section 2.4): in real round j the process packs, for every
  * root `root`, block pack_idx[j*p + root] of buffer[root] for its to-neighbour
  * and unpacks what it receives into block unpack_idx[j*p + root] of
  * buffer[root].  Towards root `root` the process acts as virtual rank
@@ -203,8 +213,9 @@ int bcs_sched_expand_ws(int32_t p, int32_t root, int32_t n,
  * of all ranks); the plain call uses the per-device allocation of bcs_sched*,
  * the _ws call takes it from the caller (256-byte aligned) and allocates
  * nothing.  p = 1: R = n-1 entries of BCS_NO_BLOCK.
- * BCS_EINVAL: p < 1, n < 1, n > BCS_MAX_N, r outside [0, p), both outputs NULL.
- * BCS_ENOMEM: workspace NULL or too small. */
+ * BCS_EINVAL: p < 1, n < 1, n > BCS_MAX_N, r outside [0, p), both outputs NULL,
+ * a workspace that is not 256-byte aligned.  BCS_ENOMEM: workspace NULL or too
+ * small. */
 int64_t bcs_allgather_workspace_bytes(int32_t p);
 int bcs_allgather_tables(int32_t p, int32_t n, int32_t r,
                          int32_t *pack_idx, int32_t *unpack_idx, void *stream);
@@ -217,8 +228,8 @@ int bcs_allgather_tables_ws(int32_t p, int32_t n, int32_t r,
  * array `data` of int32 elements, buffer j at elements displs[j] ..
  * displs[j+1]-1 (displs: device, p+1 int64, non-decreasing; a buffer has fewer
  * than 2^31 elements).  A buffer of m elements is cut into n blocks, block b
- * being elements floor(b*m/n) .. floor((b+1)*m/n)-1 (the paper says "roughly
- * equal sized" and gives no rule for remainders).
+ * being elements floor(b*m/n) .. floor((b+1)*m/n)-1 (the paper asks for blocks of
+ * about the same size and gives no rule for remainders).
  *   idx: device, p int32: the block of each buffer that moves in this round
  *   (a row of the tables of bcs_allgather_tables); negative = none; values
  *   above n-1 are read as n-1.

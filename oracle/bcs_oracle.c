@@ -48,28 +48,22 @@ int orc_skips(int32_t p, int32_t *skips)
 {
     int q = orc_q(p);
     if (q < 0) return q;
-    int k = q;
-    int32_t v = p;
-    while (v > 1) {
-        skips[k] = v;
-        v = v / 2 + v % 2;
-        k = k - 1;
-    }
-    skips[k] = v;
+    skips[q] = p;
+    for (int k = q; k > 0; k--) skips[k - 1] = (int32_t)(((int64_t)skips[k] + 1) / 2);
     return q;
 }
 
-/* Alg. 2: baseblock of rank r, 0 < r < p.  Walk the skips downward from
- * skips[q]; whenever the next smaller skip is still below r, move r into the
- * lower copy of the pattern by subtracting it; stop when r sits on a skip. */
+/* Alg. 2: baseblock of rank r, 0 < r < p.  Go down the skips from the largest
+ * below p; a skip that is still below r is taken off r (r moves into the
+ * lower copy of the pattern); the level at which r then sits on the skip is
+ * the baseblock.  Level 0 always ends it: r has come down to skips[0] = 1. */
 static int baseblock_alg2(const int32_t *skips, int q, int32_t r)
 {
-    int k = q;
-    while (r != skips[k]) {
-        k = k - 1;
-        if (skips[k] < r) r = r - skips[k];
+    for (int k = q - 1; k > 0; k--) {
+        if (skips[k] < r) r -= skips[k];
+        if (r == skips[k]) return k;
     }
-    return k;
+    return 0;
 }
 
 int orc_baseblock(int32_t p, int32_t r)
@@ -101,10 +95,11 @@ int orc_baseblocks_linear(int32_t p, int32_t *bb)
     return q;
 }
 
-/* RangeBlocks by its definition (Section 2, paragraph before Alg. 4: "which
- * baseblocks are in that range"): the set { bb[j mod p] : a <= j <= b,
- * j mod p != 0 } as a bit mask.  a and b are plain integers and may be
- * negative (Alg. 4 "omitting the modulo computations"); empty when a > b.
+/* RangeBlocks by its definition (Section 2, paragraph before Alg. 4: the
+ * baseblocks that occur among the ranks of a range): the set
+ * { bb[j mod p] : a <= j <= b, j mod p != 0 } as a bit mask.  a and b are
+ * plain integers and may be negative (the text after Alg. 4 writes the
+ * ranges without their mod p); empty when a > b.
  * Needs the full bb[] list, so it is for small p only. */
 uint32_t orc_rangeblocks_scan(int32_t p, const int32_t *bb, int64_t a, int64_t b)
 {
@@ -315,7 +310,7 @@ int orc_sched_definition(int32_t p, int general_only, int32_t *bb_out,
 
 /* Rows of ranks [r0, r1) for broadcast root `root`: the row of rank r is the
  * schedule of virtual rank (r - root + p) mod p (Section 2, paragraph after
- * Alg. 2; Section 2.5).  Receive rows by Alg. 4 with the O(q) range routine.
+ * Alg. 2; Section 2.4).  Receive rows by Alg. 4 with the O(q) range routine.
  * Send rows: when the call covers every rank, by the look-up of Alg. 9;
  * otherwise by Alg. 5.  Output [(r - r0) * q + k]; either table may be NULL.
  * `threads` >= 1 splits the rank loop with OpenMP; results do not depend
@@ -514,8 +509,8 @@ int orc_allgather_tables(int32_t p, int32_t n, int32_t r, int32_t *pack, int32_t
 }
 
 /* Block b of a buffer of m elements cut into n blocks: elements floor(b*m/n) .. floor((b+1)*m/n) - 1.
- * Reading: the paper cuts a buffer into "n roughly equal sized blocks" (Section 2) of "the buffer size divided by
- * n" (Section 2.5) and gives no rule for remainders; this balanced cut covers the buffer exactly with block sizes
+ * Reading: the paper asks for n blocks of about the same size (Section 2), each the buffer size over n
+ * (Section 2.4), and gives no rule for remainders; this balanced cut covers the buffer exactly with block sizes
  * that differ by at most one.  m < 2^31 and b <= n < 2^31 keep the product inside 64 bits. */
 static int64_t block_begin(int64_t m, int64_t n, int64_t b) { return (b * m) / n; }
 

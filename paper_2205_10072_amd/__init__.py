@@ -110,14 +110,35 @@ def _check(code, what):
     return code
 
 
-def _ptr(t):
-    """Device pointer of an int32, contiguous CUDA/HIP tensor (None -> NULL)."""
+def _need(t, numel, what):
+    """Raises ValueError when tensor `t` (or None) holds fewer than `numel` elements: the kernels trust the sizes
+    the C ABI is given, so a table that is too small must be stopped here."""
+    if t is not None and t.numel() < numel:
+        raise ValueError("%s: tensor of %d elements, %d needed" % (what, t.numel(), numel))
+
+
+def _ptr(t, numel=0, what="tensor"):
+    """Device pointer of an int32, contiguous CUDA/HIP tensor of at least `numel` elements (None -> NULL)."""
     if t is None:
         return None
     import torch
     if not (isinstance(t, torch.Tensor) and t.is_cuda and t.dtype == torch.int32 and t.is_contiguous()):
         raise TypeError("expected a contiguous int32 tensor in device memory")
+    _need(t, numel, what)
     return ctypes.c_void_p(t.data_ptr())
+
+
+def _rows(r0, r1):
+    return max(int(r1) - int(r0), 0)
+
+
+def _ws(workspace):
+    """(pointer, bytes) of a workspace tensor of any dtype (None or empty -> NULL, 0)."""
+    if workspace is None or workspace.numel() == 0:
+        return None, 0
+    if not workspace.is_cuda or not workspace.is_contiguous():
+        raise TypeError("expected a contiguous workspace tensor in device memory")
+    return ctypes.c_void_p(workspace.data_ptr()), workspace.numel() * workspace.element_size()
 
 
 def _stream(stream):
@@ -144,12 +165,15 @@ def bcs_rounds(p, n):
 
 
 def bcs_sched(p, r0, r1, recv_out, send_out, stream=None):
-    _check(lib().bcs_sched(p, r0, r1, _ptr(recv_out), _ptr(send_out), _stream(stream)), "bcs_sched")
+    need = _rows(r0, r1) * bcs_q(p)
+    _check(lib().bcs_sched(p, r0, r1, _ptr(recv_out, need, "recv_out"), _ptr(send_out, need, "send_out"),
+                           _stream(stream)), "bcs_sched")
 
 
 def bcs_sched_rooted(p, root, r0, r1, recv_out, send_out, stream=None):
-    _check(lib().bcs_sched_rooted(p, root, r0, r1, _ptr(recv_out), _ptr(send_out), _stream(stream)),
-           "bcs_sched_rooted")
+    need = _rows(r0, r1) * bcs_q(p)
+    _check(lib().bcs_sched_rooted(p, root, r0, r1, _ptr(recv_out, need, "recv_out"), _ptr(send_out, need, "send_out"),
+                                  _stream(stream)), "bcs_sched_rooted")
 
 
 def bcs_sched_workspace_bytes(p, r0, r1, want_send=True):
@@ -158,20 +182,30 @@ def bcs_sched_workspace_bytes(p, r0, r1, want_send=True):
 
 def bcs_sched_rooted_ws(p, root, r0, r1, recv_out, send_out, workspace, stream=None):
     """`workspace`: a device tensor of any dtype (or None when no scratch is needed)."""
-    wp = ctypes.c_void_p(workspace.data_ptr()) if workspace is not None else None
-    wb = workspace.numel() * workspace.element_size() if workspace is not None else 0
-    _check(lib().bcs_sched_rooted_ws(p, root, r0, r1, _ptr(recv_out), _ptr(send_out), wp, wb, _stream(stream)),
+    wp, wb = _ws(workspace)
+    need = _rows(r0, r1) * bcs_q(p)
+    _check(lib().bcs_sched_rooted_ws(p, root, r0, r1, _ptr(recv_out, need, "recv_out"),
+                                     _ptr(send_out, need, "send_out"), wp, wb, _stream(stream)),
            "bcs_sched_rooted_ws")
 
 
 def bcs_sched_batch(p, r, root, recv_out, send_out, q_out, stream=None):
     count = p.numel()
-    _check(lib().bcs_sched_batch(count, _ptr(p), _ptr(r), _ptr(root), _ptr(recv_out), _ptr(send_out),
-                                 _ptr(q_out), _stream(stream)), "bcs_sched_batch")
+    rows = count * BATCH_STRIDE
+    _check(lib().bcs_sched_batch(count, _ptr(p), _ptr(r, count, "r"), _ptr(root, count, "root"),
+                                 _ptr(recv_out, rows, "recv_out"), _ptr(send_out, rows, "send_out"),
+                                 _ptr(q_out, count, "q_out"), _stream(stream)), "bcs_sched_batch")
+
+
+def _expand_sizes(p, n, rows):
+    q = bcs_q(p)
+    return rows * q, rows * (max(int(n), 1) - 1 + q)
 
 
 def bcs_expand(p, n, r0, r1, recv, send, recv_blocks, send_blocks, stream=None):
-    _check(lib().bcs_expand(p, n, r0, r1, _ptr(recv), _ptr(send), _ptr(recv_blocks), _ptr(send_blocks),
+    nq, nr = _expand_sizes(p, n, _rows(r0, r1))
+    _check(lib().bcs_expand(p, n, r0, r1, _ptr(recv, nq, "recv"), _ptr(send, nq, "send"),
+                            _ptr(recv_blocks, nr, "recv_blocks"), _ptr(send_blocks, nr, "send_blocks"),
                             _stream(stream)), "bcs_expand")
 
 
@@ -181,9 +215,10 @@ def bcs_expand_workspace_bytes(p, n, r0, r1):
 
 def bcs_expand_ws(p, n, r0, r1, recv, send, recv_blocks, send_blocks, workspace, stream=None):
     """`workspace`: a device tensor of any dtype (or None)."""
-    wp = ctypes.c_void_p(workspace.data_ptr()) if workspace is not None and workspace.numel() else None
-    wb = workspace.numel() * workspace.element_size() if workspace is not None else 0
-    _check(lib().bcs_expand_ws(p, n, r0, r1, _ptr(recv), _ptr(send), _ptr(recv_blocks), _ptr(send_blocks), wp, wb,
+    wp, wb = _ws(workspace)
+    nq, nr = _expand_sizes(p, n, _rows(r0, r1))
+    _check(lib().bcs_expand_ws(p, n, r0, r1, _ptr(recv, nq, "recv"), _ptr(send, nq, "send"),
+                               _ptr(recv_blocks, nr, "recv_blocks"), _ptr(send_blocks, nr, "send_blocks"), wp, wb,
                                _stream(stream)), "bcs_expand_ws")
 
 
@@ -192,16 +227,19 @@ def bcs_sched_expand_workspace_bytes(p, n):
 
 
 def bcs_sched_expand(p, root, n, recv_out, send_out, recv_blocks, send_blocks, stream=None):
-    _check(lib().bcs_sched_expand(p, root, n, _ptr(recv_out), _ptr(send_out), _ptr(recv_blocks),
-                                  _ptr(send_blocks), _stream(stream)), "bcs_sched_expand")
+    nq, nr = _expand_sizes(p, n, max(int(p), 0))
+    _check(lib().bcs_sched_expand(p, root, n, _ptr(recv_out, nq, "recv_out"), _ptr(send_out, nq, "send_out"),
+                                  _ptr(recv_blocks, nr, "recv_blocks"), _ptr(send_blocks, nr, "send_blocks"),
+                                  _stream(stream)), "bcs_sched_expand")
 
 
 def bcs_sched_expand_ws(p, root, n, recv_out, send_out, recv_blocks, send_blocks, workspace, stream=None):
     """`workspace`: a device tensor of any dtype (or None when no scratch is needed)."""
-    wp = ctypes.c_void_p(workspace.data_ptr()) if workspace is not None else None
-    wb = workspace.numel() * workspace.element_size() if workspace is not None else 0
-    _check(lib().bcs_sched_expand_ws(p, root, n, _ptr(recv_out), _ptr(send_out), _ptr(recv_blocks),
-                                     _ptr(send_blocks), wp, wb, _stream(stream)), "bcs_sched_expand_ws")
+    wp, wb = _ws(workspace)
+    nq, nr = _expand_sizes(p, n, max(int(p), 0))
+    _check(lib().bcs_sched_expand_ws(p, root, n, _ptr(recv_out, nq, "recv_out"), _ptr(send_out, nq, "send_out"),
+                                     _ptr(recv_blocks, nr, "recv_blocks"), _ptr(send_blocks, nr, "send_blocks"),
+                                     wp, wb, _stream(stream)), "bcs_sched_expand_ws")
 
 
 def bcs_release():
@@ -233,7 +271,8 @@ def bcs_timing_stats():
 
 def bcs_valu_peak_launch(blocks, iters, sink, stream=None):
     """`sink`: int32 device tensor of at least blocks * 256 entries."""
-    _check(lib().bcs_valu_peak_launch(blocks, iters, _ptr(sink), _stream(stream)), "bcs_valu_peak_launch")
+    _check(lib().bcs_valu_peak_launch(blocks, iters, _ptr(sink, blocks * 256, "sink"), _stream(stream)),
+           "bcs_valu_peak_launch")
 
 
 def bcs_allgather_workspace_bytes(p):
@@ -241,22 +280,25 @@ def bcs_allgather_workspace_bytes(p):
 
 
 def bcs_allgather_tables(p, n, r, pack_idx, unpack_idx, stream=None):
-    _check(lib().bcs_allgather_tables(p, n, r, _ptr(pack_idx), _ptr(unpack_idx), _stream(stream)),
-           "bcs_allgather_tables")
+    need = _expand_sizes(p, n, max(int(p), 0))[1]                 # R x p entries
+    _check(lib().bcs_allgather_tables(p, n, r, _ptr(pack_idx, need, "pack_idx"), _ptr(unpack_idx, need, "unpack_idx"),
+                                      _stream(stream)), "bcs_allgather_tables")
 
 
 def bcs_allgather_tables_ws(p, n, r, pack_idx, unpack_idx, workspace, stream=None):
-    wp = ctypes.c_void_p(workspace.data_ptr()) if workspace is not None else None
-    wb = workspace.numel() * workspace.element_size() if workspace is not None else 0
-    _check(lib().bcs_allgather_tables_ws(p, n, r, _ptr(pack_idx), _ptr(unpack_idx), wp, wb, _stream(stream)),
+    wp, wb = _ws(workspace)
+    need = _expand_sizes(p, n, max(int(p), 0))[1]
+    _check(lib().bcs_allgather_tables_ws(p, n, r, _ptr(pack_idx, need, "pack_idx"),
+                                         _ptr(unpack_idx, need, "unpack_idx"), wp, wb, _stream(stream)),
            "bcs_allgather_tables_ws")
 
 
-def _dev(t, dtype):
-    """Device pointer of a contiguous device tensor of the given torch dtype."""
+def _dev(t, dtype, numel=0, what="tensor"):
+    """Device pointer of a contiguous device tensor of the given torch dtype and at least `numel` elements."""
     import torch
     if not (isinstance(t, torch.Tensor) and t.is_cuda and t.dtype == dtype and t.is_contiguous()):
         raise TypeError("expected a contiguous %s tensor in device memory" % dtype)
+    _need(t, numel, what)
     return ctypes.c_void_p(t.data_ptr())
 
 
@@ -265,20 +307,24 @@ def bcs_pack_workspace_bytes(p):
 
 
 def bcs_pack_round(n, idx, displs, data, packed, offsets, workspace, stream=None):
-    """idx int32[p], displs int64[p+1], data int32, packed int32 (its numel is the capacity), offsets int64[p+1]."""
+    """idx int32[p], displs int64[p+1], data int32, packed int32 (its numel is the capacity), offsets int64[p+1].
+    `data` must hold displs[p] elements: that value lives on the device, so it is the caller's to guarantee."""
     import torch
     p = idx.numel()
-    _check(lib().bcs_pack_round(p, n, _ptr(idx), _dev(displs, torch.int64), _ptr(data), _ptr(packed), packed.numel(),
-                                _dev(offsets, torch.int64), ctypes.c_void_p(workspace.data_ptr()),
-                                workspace.numel() * workspace.element_size(), _stream(stream)), "bcs_pack_round")
+    wp, wb = _ws(workspace)
+    _check(lib().bcs_pack_round(p, n, _ptr(idx), _dev(displs, torch.int64, p + 1, "displs"), _ptr(data), _ptr(packed),
+                                packed.numel(), _dev(offsets, torch.int64, p + 1, "offsets"), wp, wb,
+                                _stream(stream)), "bcs_pack_round")
 
 
 def bcs_unpack_round(n, idx, displs, data, packed, length, offsets, workspace, stream=None):
     import torch
     p = idx.numel()
-    _check(lib().bcs_unpack_round(p, n, _ptr(idx), _dev(displs, torch.int64), _ptr(data), _ptr(packed), length,
-                                  _dev(offsets, torch.int64), ctypes.c_void_p(workspace.data_ptr()),
-                                  workspace.numel() * workspace.element_size(), _stream(stream)), "bcs_unpack_round")
+    wp, wb = _ws(workspace)
+    _check(lib().bcs_unpack_round(p, n, _ptr(idx), _dev(displs, torch.int64, p + 1, "displs"), _ptr(data),
+                                  _ptr(packed, max(int(length), 0), "packed"), length,
+                                  _dev(offsets, torch.int64, p + 1, "offsets"), wp, wb, _stream(stream)),
+           "bcs_unpack_round")
 
 
 def _host_plan(fn, what, p, r, arrays):

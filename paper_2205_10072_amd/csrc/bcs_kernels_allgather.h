@@ -1,4 +1,4 @@
-// Irregular allgather (Alg. 9; Section 2.5): the pack / unpack index tables of one process and the packing and
+// Irregular allgather (Alg. 9; Section 2.4): the pack / unpack index tables of one process and the packing and
 // unpacking of one round's message.
 #ifndef BCS_KERNELS_ALLGATHER_H
 #define BCS_KERNELS_ALLGATHER_H

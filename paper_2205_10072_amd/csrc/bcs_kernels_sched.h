@@ -11,7 +11,7 @@ namespace {
 // The low-level table of bcs_core.h lives in the code object; k_build_lowtab fills it once per device
 // and process (one thread per entry, by the level walk).
 // ----------------------------------------------------------------------------------------------
-__device__ uint8_t g_lowtab[kLowTableBytes];
+__device__ __align__(16) uint8_t g_lowtab[kLowTableBytes];   // read a dword at a time by stage_lowtab
 
 __global__ __launch_bounds__(kBlock) void k_build_lowtab() {
     const int e = blockIdx.x * kBlock + threadIdx.x;

@@ -123,17 +123,10 @@ int host_q(int32_t p) {
     return q;
 }
 
-// Alg. 1
+// The skips of Alg. 1 by the closed form its halving produces: skips[k] = ceil(p / 2^(q-k)).
 int host_skips(int32_t p, SkipTab &t) {
     const int q = host_q(p);
-    int k = q;
-    uint32_t v = (uint32_t)p;
-    while (v > 1u) {
-        t.s[k] = v;
-        v = v / 2u + v % 2u;
-        --k;
-    }
-    t.s[k] = v;
+    for (int k = 0; k <= q; ++k) t.s[k] = (((uint32_t)p - 1u) >> (q - k)) + 1u;
     for (int j = q + 1; j < kMaxQ + 2; ++j) t.s[j] = (uint32_t)p;
     t.odd = odd_levels((uint32_t)p, q);
     return q;
@@ -183,14 +176,21 @@ int ensure_lowtab(hipStream_t st) {
     return BCS_OK;
 }
 
+// The per-device scratch of the plain calls.  One allocation serves every plain call on the device, so two of
+// them on different streams must not overlap: when a call comes on another stream than the one before it, that
+// earlier stream's work is made a dependency of the new one (an event recorded there now covers everything
+// the earlier call enqueued).
 struct Scratch {
     void *ptr = nullptr;
     size_t bytes = 0;
+    bool used = false;
+    hipStream_t last = nullptr;
+    hipEvent_t order = nullptr;
 };
 Scratch g_scratch[kMaxDevices];
 std::mutex g_scratch_mutex;
 
-int scratch_get(size_t bytes, void **out) {
+int scratch_get(size_t bytes, hipStream_t st, void **out) {
     int dev = 0;
     hipError_t e = hipGetDevice(&dev);
     if (e != hipSuccess) return hip_fail(e);
@@ -199,11 +199,12 @@ int scratch_get(size_t bytes, void **out) {
     Scratch &s = g_scratch[dev];
     if (s.bytes < bytes) {
         if (s.ptr) {
-            e = hipDeviceSynchronize();
+            e = hipDeviceSynchronize();            // the one place a call waits: work may still use the old block
             if (e != hipSuccess) return hip_fail(e);
             e = hipFree(s.ptr);
             s.ptr = nullptr;
             s.bytes = 0;
+            s.used = false;
             if (e != hipSuccess) return hip_fail(e);
         }
         e = hipMalloc(&s.ptr, bytes);
@@ -215,6 +216,22 @@ int scratch_get(size_t bytes, void **out) {
         }
         s.bytes = bytes;
     }
+    if (s.used && s.last != st) {
+        if (!s.order) {
+            e = hipEventCreateWithFlags(&s.order, hipEventDisableTiming);
+            if (e != hipSuccess) return hip_fail(e);
+        }
+        e = hipEventRecord(s.order, s.last);
+        if (e == hipSuccess) {
+            e = hipStreamWaitEvent(st, s.order, 0);
+        } else {                                   // the earlier stream is gone: wait for whatever it left behind
+            (void)hipGetLastError();
+            e = hipDeviceSynchronize();
+        }
+        if (e != hipSuccess) return hip_fail(e);
+    }
+    s.used = true;
+    s.last = st;
     *out = s.ptr;
     return BCS_OK;
 }
@@ -411,6 +428,7 @@ int bcs_sched_rooted_ws(int32_t p, int32_t root, int32_t r0, int32_t r1, int32_t
     if (q == 0 || r0 == r1) return BCS_OK;
     const int64_t need = bcs_sched_workspace_bytes(p, r0, r1, send_out != nullptr);
     if (need > 0 && (!workspace || workspace_bytes < (size_t)need)) return BCS_ENOMEM;
+    if (need > 0 && (((uintptr_t)workspace) & 255u)) return BCS_EINVAL;     // tables are read 4 and 16 bytes at a time
     SkipTab tab;
     host_skips(p, tab);
     rc = ensure_lowtab((hipStream_t)stream);
@@ -438,7 +456,7 @@ int bcs_sched_rooted(int32_t p, int32_t root, int32_t r0, int32_t r1, int32_t *r
     const int64_t need = bcs_sched_workspace_bytes(p, r0, r1, send_out != nullptr);
     void *ws = nullptr;
     if (need > 0 && r0 != r1) {
-        rc = scratch_get((size_t)need, &ws);
+        rc = scratch_get((size_t)need, (hipStream_t)stream, &ws);
         if (rc != BCS_OK) return rc;
     }
     return bcs_sched_rooted_ws(p, root, r0, r1, recv_out, send_out, ws, (size_t)need, stream);
@@ -607,6 +625,7 @@ int bcs_sched_expand_ws(int32_t p, int32_t root, int32_t n, int32_t *recv_out, i
     if (R == 0) return BCS_OK;                     // one process, one block: every table is empty
     if (!recv_blocks || !send_blocks) return BCS_EINVAL;
     if (q > 0 && (!recv_out || !send_out)) return BCS_EINVAL;
+    if (workspace && workspace_bytes > 0 && (((uintptr_t)workspace) & 255u)) return BCS_EINVAL;
     const bool aligned = ((((uintptr_t)recv_blocks) | ((uintptr_t)send_blocks)) & 15u) == 0;
     if (!use_fused(p, q, R, aligned)) {
         const int64_t base = q > 0 ? bcs_sched_workspace_bytes(p, 0, p, 1) : 0;
@@ -665,7 +684,7 @@ int bcs_sched_expand(int32_t p, int32_t root, int32_t n, int32_t *recv_out, int3
     const int64_t need = bcs_sched_expand_workspace_bytes(p, n);
     void *ws = nullptr;
     if (need > 0) {
-        const int rc = scratch_get((size_t)need, &ws);
+        const int rc = scratch_get((size_t)need, (hipStream_t)stream, &ws);
         if (rc != BCS_OK) return rc;
     }
     return bcs_sched_expand_ws(p, root, n, recv_out, send_out, recv_blocks, send_blocks, ws, (size_t)need, stream);
@@ -684,6 +703,7 @@ int bcs_release(void) {
         e = hipFree(s.ptr);
         s.ptr = nullptr;
         s.bytes = 0;
+        s.used = false;
         if (e != hipSuccess) return hip_fail(e);
     }
     return BCS_OK;
@@ -710,6 +730,7 @@ int bcs_allgather_tables_ws(int32_t p, int32_t n, int32_t r, int32_t *pack_idx, 
     }
     const int64_t need = bcs_allgather_workspace_bytes(p);
     if (!workspace || workspace_bytes < (size_t)need) return BCS_ENOMEM;
+    if (((uintptr_t)workspace) & 255u) return BCS_EINVAL;
     SkipTab tab;
     host_skips(p, tab);
     int rc = ensure_lowtab(st);
@@ -750,7 +771,7 @@ int bcs_allgather_tables(int32_t p, int32_t n, int32_t r, int32_t *pack_idx, int
     const int64_t need = bcs_allgather_workspace_bytes(p);
     void *ws = nullptr;
     if (need > 0) {
-        const int rc = scratch_get((size_t)need, &ws);
+        const int rc = scratch_get((size_t)need, (hipStream_t)stream, &ws);
         if (rc != BCS_OK) return rc;
     }
     return bcs_allgather_tables_ws(p, n, r, pack_idx, unpack_idx, ws, (size_t)need, stream);

@@ -5,22 +5,30 @@ import subprocess
 
 import numpy as np
 
-ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-SRC = os.path.join(ROOT, "paper_2205_10072_amd", "csrc", "bcs_hostcheck.cpp")
-CORE = os.path.join(ROOT, "paper_2205_10072_amd", "csrc", "bcs_core.h")
-LIB = os.path.join(ROOT, "paper_2205_10072_amd", "libbcs_hostcheck.so")
+HERE = os.path.dirname(os.path.abspath(__file__))
+ROOT = os.path.dirname(HERE)
+SRC = os.path.join(HERE, "bcs_hostcheck.cpp")
+CSRC = os.path.join(ROOT, "paper_2205_10072_amd", "csrc")
+CORE = os.path.join(CSRC, "bcs_core.h")
+LIB = os.path.join(HERE, "libbcs_hostcheck.so")
 
 _lib = None
+
+
+def build(lib=LIB, extra=(), force=True):
+    """Compiles the host build of the lane code (g++); `extra` adds flags, e.g. sanitizers."""
+    stale = (force or not os.path.exists(lib)
+             or os.path.getmtime(lib) < max(os.path.getmtime(SRC), os.path.getmtime(CORE)))
+    if stale:
+        subprocess.run(["g++", "-O2", "-std=c++17", "-fPIC", "-shared", "-Wno-unknown-pragmas", "-I", CSRC]
+                       + list(extra) + ["-o", lib, SRC], check=True)
+    return lib
 
 
 def load():
     global _lib
     if _lib is None:
-        stale = (not os.path.exists(LIB)
-                 or os.path.getmtime(LIB) < max(os.path.getmtime(SRC), os.path.getmtime(CORE)))
-        if stale:
-            subprocess.run(["g++", "-O2", "-std=c++17", "-fPIC", "-shared", "-Wno-unknown-pragmas",
-                            "-o", LIB, SRC], check=True)
+        build(force=False)
         L = ctypes.CDLL(LIB)
         i32p = ctypes.POINTER(ctypes.c_int32)
         L.hc_recv_row.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int, i32p]

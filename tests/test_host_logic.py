@@ -83,6 +83,36 @@ def test_binding_refuses_host_tensors():
         bcs.bcs_sched(2, 0, 2, t, t)
 
 
+def test_binding_size_checks():
+    """The kernels trust the sizes they are given, so the binding must stop a table that is too small.  The check
+    itself needs no device; the sizes it is given per call are covered on the GPU (test_gpu_parity)."""
+    import torch
+    import paper_2205_10072_amd as bcs
+    t = torch.zeros(10, dtype=torch.int32)
+    bcs._need(t, 10, "t")
+    bcs._need(None, 10**12, "absent")
+    with pytest.raises(ValueError):
+        bcs._need(t, 11, "t")
+    assert bcs._rows(3, 9) == 6 and bcs._rows(9, 3) == 0
+    assert bcs._expand_sizes(65537, 4096, 65537) == (65537 * 17, 65537 * 4112)
+    assert bcs._expand_sizes(1, 5, 1) == (0, 4)
+    assert bcs._ws(None) == (None, 0) and bcs._ws(torch.zeros(0)) == (None, 0)
+    with pytest.raises(TypeError):
+        bcs._ws(torch.zeros(4))                  # host memory is no workspace
+
+
+def test_misaligned_workspaces_are_refused():
+    import paper_2205_10072_amd as bcs
+    L = bcs.lib()
+    fake = ctypes.c_void_p(4096)
+    odd = ctypes.c_void_p(4096 + 64)             # 64-byte aligned only; never dereferenced
+    big = 1 << 30
+    assert L.bcs_sched_rooted_ws(5, 0, 0, 5, fake, fake, odd, big, None) == bcs.EINVAL
+    assert L.bcs_sched_expand_ws(5, 0, 3, fake, fake, fake, fake, odd, big, None) == bcs.EINVAL
+    assert L.bcs_allgather_tables_ws(5, 3, 0, fake, fake, odd, big, None) == bcs.EINVAL
+    assert L.bcs_allgather_tables_ws(5, 3, 0, fake, fake, None, 0, None) == bcs.ENOMEM
+
+
 def test_lane_code_range_blocks_equals_scan(oracle):
     rng = np.random.default_rng(11)
     for p in list(range(2, 80)) + [127, 128, 129, 255, 257, 1000, 1023, 1025]:
@@ -141,6 +171,28 @@ def test_lane_code_rows_equal_oracle_large_p(oracle):
             assert (hostcheck.recv_row(p, v, perlane=True, wave_q=31)[:q] == want).all(), (p, v)
             k = int(rng.integers(0, q))          # a prefix, as Alg. 5 asks for
             assert (hostcheck.recv_row(p, v, last=k)[:k + 1] == want[:k + 1]).all()
+
+
+def test_lane_code_rows_that_read_the_high_rows_of_the_low_table(oracle):
+    """The rows of the low-level table for many odd levels passed (14 and up) are reached only when q >= 22 and p
+    lies just above a power of two; ranks at and around skips and sums of skips are where windows straddle them."""
+    rng = np.random.default_rng(1417)
+    for k in range(17, 31):
+        for p in [2**k + 1, 2**k + 2, 2**k + 3, 2**(k + 1) - 1, int(rng.integers(2**k + 1, 2**k + 2**(k - 8)))]:
+            skips = oracle.skips(p).astype(np.int64)
+            q = len(skips) - 1
+            ranks = {0, 1, p - 1}
+            for i in range(q + 1):
+                for d in (-3, -2, -1, 0, 1, 2, 3):
+                    ranks.add(int(skips[i]) + d)
+            for _ in range(24):
+                pick = rng.random(q) < 0.5
+                ranks.add(int(skips[:q][pick].sum()) + int(rng.integers(-3, 4)))
+            ranks |= {int(x) for x in rng.integers(0, p, 16)}
+            for v in sorted(r for r in ranks if 0 <= r < p):
+                want = oracle.recvsched(p, v)
+                assert (hostcheck.recv_row(p, v)[:q] == want).all(), (p, v)
+                assert (hostcheck.recv_row(p, v, perlane=True, wave_q=min(q + 2, 31))[:q] == want).all(), (p, v)
 
 
 def test_lane_code_perlane_small_p_and_padding_lanes(oracle):

@@ -19,7 +19,7 @@ def test_allgather_completes_for_every_process(oracle, p):
 
 
 def test_allgather_tables_are_rotated_broadcast_tables(oracle):
-    """Process r treats root j as the virtual rank (r - j + p) mod p of a broadcast rooted at 0 (Section 2.5)."""
+    """Process r treats root j as the virtual rank (r - j + p) mod p of a broadcast rooted at 0 (Section 2.4)."""
     for p, n in [(9, 4), (20, 7), (33, 2), (100, 11)]:
         recv, send = oracle.sched_range(p)
         er, es = oracle.expand(p, n, recv), oracle.expand(p, n, send)
