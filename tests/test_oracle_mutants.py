@@ -22,8 +22,8 @@ SRC = os.path.join(os.path.dirname(HERE), "oracle", "bcs_oracle.c")
 
 MUTANTS = [
     # (name, text in the source, replacement)
-    ("skips_floor_halving", "v = v / 2 + v % 2;", "v = v / 2;"),
-    ("baseblock_le_instead_of_lt", "if (skips[k] < r) r = r - skips[k];", "if (skips[k] <= r) r = r - skips[k];"),
+    ("skips_floor_halving", "skips[k - 1] = (int32_t)(((int64_t)skips[k] + 1) / 2);", "skips[k - 1] = skips[k] / 2;"),
+    ("baseblock_le_instead_of_lt", "if (skips[k] < r) r -= skips[k];", "if (skips[k] <= r) r -= skips[k];"),
     ("linear_recipe_skips_rank_1", "for (int32_t r = 1; r < skips[i]; r++) {", "for (int32_t r = 2; r < skips[i]; r++) {"),
     ("range_rec_shift_wrong_level", "return rangeblocks_rec(skips, a - skips[k], b - skips[k], k - 1);",
      "return rangeblocks_rec(skips, a - skips[k - 1], b - skips[k - 1], k - 1);"),
