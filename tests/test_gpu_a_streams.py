@@ -38,3 +38,28 @@ def test_first_calls_on_two_streams_and_side_stream_use(oracle):
         bcs.bcs_expand(p, n, 0, p, rb, None, eb, None)                    # binding picks up the current stream
     sb.synchronize()
     assert np.array_equal(eb.cpu().numpy(), oracle.expand(p, n, o5r, threads=8))
+
+
+def test_plain_calls_on_two_streams_share_the_scratch_in_order(oracle):
+    """Plain calls keep one scratch allocation per device.  Two of them on different streams, enqueued back to
+    back with no synchronisation in between, must not overwrite each other's tables: the library makes the
+    second wait for the first on the device."""
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_2205_10072_amd as bcs
+    bcs.lib()
+    pa, pb = 300007, 299993                     # same q, different skips: a mixed-up scratch cannot go unnoticed
+    q = bcs.bcs_q(pa)
+    assert bcs.bcs_q(pb) == q
+    sa, sb = torch.cuda.Stream(), torch.cuda.Stream()
+    ra, xa = (torch.full((pa, q), 1, dtype=torch.int32, device="cuda") for _ in range(2))
+    rb, xb = (torch.full((pb, q), 2, dtype=torch.int32, device="cuda") for _ in range(2))
+    torch.cuda.synchronize()
+    for _ in range(3):
+        bcs.bcs_sched_rooted(pa, 11, 0, pa, ra, xa, stream=sa)
+        bcs.bcs_sched_rooted(pb, 0, 0, pb, rb, xb, stream=sb)
+    torch.cuda.synchronize()
+    oar, oas = oracle.sched_range(pa, root=11, threads=8)
+    obr, obs = oracle.sched_range(pb, threads=8)
+    assert np.array_equal(ra.cpu().numpy(), oar) and np.array_equal(xa.cpu().numpy(), oas)
+    assert np.array_equal(rb.cpu().numpy(), obr) and np.array_equal(xb.cpu().numpy(), obs)
