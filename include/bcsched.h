@@ -62,6 +62,7 @@ extern "C" {
 #define BCS_EINVAL  (-1)  /* an argument is outside its domain (see each call)        */
 #define BCS_EHIP    (-2)  /* a HIP call failed; bcs_last_hip_error() has its code      */
 #define BCS_ENOMEM  (-3)  /* scratch allocation failed, or the given workspace is small */
+#define BCS_ETOOBIG (-4)  /* bcs_sched_rooted_static: needs more than its fixed scratch  */
 
 #define BCS_MAX_Q         31           /* p <= 2^31 - 1                                */
 #define BCS_BATCH_STRIDE  32           /* ints per row of the batch tables             */
@@ -123,6 +124,26 @@ int64_t bcs_sched_workspace_bytes(int32_t p, int32_t r0, int32_t r1, int want_se
 int bcs_sched_rooted_ws(int32_t p, int32_t root, int32_t r0, int32_t r1,
                         int32_t *recv_out, int32_t *send_out,
                         void *workspace, size_t workspace_bytes, void *stream);
+
+/* For callers that cannot allocate device memory (code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc):
+ * bcs_sched_rooted with its scratch in a fixed array of
+ * BCS_STATIC_SCRATCH_BYTES that lives in the library's code object, one copy
+ * on every GPU the library runs on, held until the process ends.  Arguments,
+ * results and errors are those of bcs_sched_rooted, bit for bit.  The call
+ * allocates and frees nothing; the first call on a device looks the array's
+ * address up (and, as every schedule-building call, may enqueue the fill of the
+ * low-level table), later calls enqueue kernels only.
+ * Limit: bcs_sched_workspace_bytes(p, r0, r1, send_out != NULL) must not
+ * exceed BCS_STATIC_SCRATCH_BYTES, else BCS_ETOOBIG and nothing is enqueued
+ * (all ranks with send rows: p up to 1 342 016).  Every call on a
+ * GPU shares that GPU's array: calls that overlap on one GPU (two streams, or
+ * two threads) race and must be ordered by the caller.  Nothing in the array
+ * has to start at zero: each call overwrites what it reads, so the contents
+ * the last call left behind do no harm. */
+#define BCS_STATIC_SCRATCH_BYTES (32u << 20)
+int bcs_sched_rooted_static(int32_t p, int32_t root, int32_t r0, int32_t r1,
+                            int32_t *recv_out, int32_t *send_out, void *stream);
 
 /* `count` unrelated problems: problem i is rank r[i] of a p[i]-rank graph with
  * broadcast root root[i].  p, r, root: device arrays of `count` int32.

@@ -13,7 +13,8 @@ import os
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libbcsched.so")
 
-OK, EINVAL, EHIP, ENOMEM = 0, -1, -2, -3
+OK, EINVAL, EHIP, ENOMEM, ETOOBIG = 0, -1, -2, -3, -4
+STATIC_SCRATCH_BYTES = 32 << 20  # BCS_STATIC_SCRATCH_BYTES
 MAX_Q = 31
 BATCH_STRIDE = 32
 BATCH_PAD = -(2 ** 31)
@@ -23,7 +24,7 @@ MAX_N = 2**31 - 1 - 64          # BCS_MAX_N
 # every symbol include/bcsched.h declares
 SYMBOLS = (
     "bcs_q", "bcs_skips", "bcs_rounds", "bcs_sched", "bcs_sched_rooted", "bcs_sched_workspace_bytes",
-    "bcs_sched_rooted_ws", "bcs_sched_batch", "bcs_expand", "bcs_sched_expand", "bcs_sched_expand_ws",
+    "bcs_sched_rooted_ws", "bcs_sched_rooted_static", "bcs_sched_batch", "bcs_expand", "bcs_sched_expand", "bcs_sched_expand_ws",
     "bcs_sched_expand_workspace_bytes", "bcs_expand_ws", "bcs_expand_workspace_bytes",
     "bcs_release", "bcs_strerror",
     "bcs_last_hip_error", "bcs_timing_begin", "bcs_timing_end", "bcs_timing_stats", "bcs_kernel_name", "bcs_valu_peak_launch",
@@ -64,6 +65,7 @@ def lib():
     L.bcs_sched_workspace_bytes.argtypes = [i32, i32, i32, ctypes.c_int]
     L.bcs_sched_workspace_bytes.restype = i64
     L.bcs_sched_rooted_ws.argtypes = [i32, i32, i32, i32, vp, vp, vp, sz, vp]
+    L.bcs_sched_rooted_static.argtypes = [i32, i32, i32, i32, vp, vp, vp]
     L.bcs_sched_batch.argtypes = [i64, vp, vp, vp, vp, vp, vp, vp]
     L.bcs_expand.argtypes = [i32, i32, i32, i32, vp, vp, vp, vp, vp]
     L.bcs_expand_workspace_bytes.argtypes = [i32, i32, i32, i32]
@@ -187,6 +189,14 @@ def bcs_sched_rooted_ws(p, root, r0, r1, recv_out, send_out, workspace, stream=N
     _check(lib().bcs_sched_rooted_ws(p, root, r0, r1, _ptr(recv_out, need, "recv_out"),
                                      _ptr(send_out, need, "send_out"), wp, wb, _stream(stream)),
            "bcs_sched_rooted_ws")
+
+
+def bcs_sched_rooted_static(p, root, r0, r1, recv_out, send_out, stream=None):
+    """bcs_sched_rooted on the library's fixed scratch array: allocates nothing (raises ETOOBIG beyond its size)."""
+    need = _rows(r0, r1) * bcs_q(p)
+    _check(lib().bcs_sched_rooted_static(p, root, r0, r1, _ptr(recv_out, need, "recv_out"),
+                                         _ptr(send_out, need, "send_out"), _stream(stream)),
+           "bcs_sched_rooted_static")
 
 
 def bcs_sched_batch(p, r, root, recv_out, send_out, q_out, stream=None):

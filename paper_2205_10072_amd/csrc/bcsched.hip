@@ -462,6 +462,59 @@ int bcs_sched_rooted(int32_t p, int32_t root, int32_t r0, int32_t r1, int32_t *r
     return bcs_sched_rooted_ws(p, root, r0, r1, recv_out, send_out, ws, (size_t)need, stream);
 }
 
+}  // extern "C"
+
+namespace {
+// Scratch of bcs_sched_rooted_static: a fixed array in the code object, one copy per GPU.  In host code the
+// array's name is only a handle for hipGetSymbolAddress; kernels and every other use take the address that
+// call returns for the current device.
+static __device__ __align__(256) unsigned char scratch[BCS_STATIC_SCRATCH_BYTES];
+
+struct StaticScratch {
+    void *ptr = nullptr;
+    bool ready = false;
+};
+StaticScratch g_static[kMaxDevices];
+std::mutex g_static_mutex;
+
+int static_scratch(void **out) {
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return hip_fail(e);
+    if (dev < 0 || dev >= kMaxDevices) return BCS_EINVAL;
+    std::lock_guard<std::mutex> lock(g_static_mutex);
+    StaticScratch &s = g_static[dev];
+    if (!s.ready) {
+        void *ptr = nullptr;
+        e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));      // this device's copy
+        if (e != hipSuccess) return hip_fail(e);
+        if (!ptr || (((uintptr_t)ptr) & 255u)) return BCS_EINVAL;
+        s.ptr = ptr;
+        s.ready = true;
+    }
+    *out = s.ptr;
+    return BCS_OK;
+}
+}  // namespace
+
+extern "C" {
+
+int bcs_sched_rooted_static(int32_t p, int32_t root, int32_t r0, int32_t r1, int32_t *recv_out, int32_t *send_out,
+                            void *stream) {
+    int rc = check_range(p, root, r0, r1);
+    if (rc != BCS_OK) return rc;
+    if (!recv_out && !send_out) return BCS_EINVAL;
+    const int64_t need = bcs_sched_workspace_bytes(p, r0, r1, send_out != nullptr);
+    if (need < 0) return (int)need;
+    if ((uint64_t)need > (uint64_t)BCS_STATIC_SCRATCH_BYTES) return BCS_ETOOBIG;
+    void *ws = nullptr;
+    if (need > 0 && r0 != r1) {
+        rc = static_scratch(&ws);
+        if (rc != BCS_OK) return rc;
+    }
+    return bcs_sched_rooted_ws(p, root, r0, r1, recv_out, send_out, ws, ws ? (size_t)need : 0, stream);
+}
+
 int bcs_sched(int32_t p, int32_t r0, int32_t r1, int32_t *recv_out, int32_t *send_out, void *stream) {
     return bcs_sched_rooted(p, 0, r0, r1, recv_out, send_out, stream);
 }
@@ -936,6 +989,7 @@ const char *bcs_strerror(int code) {
         case BCS_EINVAL: return "invalid argument";
         case BCS_EHIP: return "HIP call failed (see bcs_last_hip_error)";
         case BCS_ENOMEM: return "scratch memory unavailable or workspace too small";
+        case BCS_ETOOBIG: return "problem needs more scratch than the fixed array of the no-allocation call holds";
         default: return "unknown bcsched error code";
     }
 }

@@ -30,6 +30,40 @@ def gpu_sched(bcs, p, root=0, r0=0, r1=None, want_recv=True, want_send=True):
     return recv.cpu().numpy(), send.cpu().numpy()
 
 
+def test_binding_refuses_tables_that_are_too_small(bcs):
+    """Sizes are checked before the C call: a kernel writing past a short table would fault the device."""
+    p, n = 1000, 40
+    q, R = bcs.bcs_q(p), bcs.bcs_rounds(p, n)
+    ok, short = dev_tables(p, q)[0], dev_tables(p - 1, q)[0]
+    blocks, blocks_short = dev_tables(p, R)[0], dev_tables(p, R - 1)[0]
+    ws = torch.empty(1 << 20, dtype=torch.uint8, device="cuda")
+    calls = [
+        lambda: bcs.bcs_sched(p, 0, p, short, ok),
+        lambda: bcs.bcs_sched_rooted(p, 3, 0, p, ok, short),
+        lambda: bcs.bcs_sched_rooted_ws(p, 3, 0, p, short, ok, ws),
+        lambda: bcs.bcs_sched_rooted_static(p, 3, 0, p, ok, short),
+        lambda: bcs.bcs_expand(p, n, 0, p, short, None, blocks, None),
+        lambda: bcs.bcs_expand(p, n, 0, p, ok, None, blocks_short, None),
+        lambda: bcs.bcs_expand_ws(p, n, 0, p, None, ok, None, blocks_short, ws),
+        lambda: bcs.bcs_sched_expand(p, 0, n, ok, ok, blocks, blocks_short),
+        lambda: bcs.bcs_sched_expand_ws(p, 0, n, ok, short, blocks, blocks, ws),
+        lambda: bcs.bcs_allgather_tables(p, n, 5, blocks_short, blocks),
+        lambda: bcs.bcs_allgather_tables_ws(p, n, 5, blocks, blocks_short, ws),
+    ]
+    trip = torch.ones(8, dtype=torch.int32, device="cuda")
+    calls += [
+        lambda: bcs.bcs_sched_batch(trip, trip[:7], trip, dev_tables(8, 32)[0], None, None),
+        lambda: bcs.bcs_sched_batch(trip, trip, trip, dev_tables(7, 32)[0], None, None),
+        lambda: bcs.bcs_sched_batch(trip, trip, trip, None, None, trip[:7]),
+    ]
+    for i, call in enumerate(calls):
+        with pytest.raises(ValueError):
+            call()
+    # a sub-range needs its rows only
+    bcs.bcs_sched(p, 10, 20, short[:10], ok[:10])
+    torch.cuda.synchronize()
+
+
 def test_sweep_every_p_to_1024(bcs, oracle):
     """Config 1: every p in 2..1024, every rank, root 0; then the GPU's own tables are replayed."""
     from bcast_sim import simulate
