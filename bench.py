@@ -1,17 +1,20 @@
 #!/usr/bin/env python3
 """Benchmark of the schedule-construction hot path on one MI355X.
 
-One step = one pass of the whole path over one batch: receive and send schedules of all
-p = 2^20 + 1 ranks (skips, baseblocks, range search, Alg. 4, send by neighbour look-up,
-root rotation) followed by their expansion into (rank, round) -> block tables for n = 256
-blocks (Alg. 6 index arithmetic).  Inputs are just (p, root, n): synthetic by construction.
-Outputs are preallocated; nothing crosses PCIe inside the timed region.
-
-Prints ONE JSON line: rank-schedules per second over the whole step, the roofline of the
-kernel that takes most of the step (plus one entry per kernel), the expansion's write rate,
-and the CPU oracle timed on the host cores next to it (a baseline, not a target).
+Headline (`value`, `ms_per_step`, `roofline`): one step = the receive and send schedules of ALL ranks of the
+largest configuration, p = 2^27 - 1 (q = 27): skips, baseblocks, range search, Alg. 4 for every rank, send rows by
+neighbour look-up (Alg. 9's second loop); 29 GB of int32 tables are written per step.  The same JSON line carries
+one record per baseline configuration under `configs`, each with its own roofline block and CPU-oracle baseline:
+  C2  p = 2^20 + 1: schedules of all ranks, then their expansion for n = 256 blocks (one library call a step);
+  C3  the headline itself;
+  C4  p = 65 537, n = 4096: expansion of both tables (2.156 GB), through bcs_expand and through bcs_expand_ws;
+  C5  2^20 seeded (p, r, root) triples of mixed q: receive rows, and send rows by Alg. 5.
+Inputs are just (p, root, n) and the seeded triples: synthetic by construction.  Outputs are preallocated; nothing
+crosses PCIe inside a timed region.  Kernel durations are device-side: the library gives every launch its own pair
+of HIP events on the stream the kernel runs on, in a second timed region of the same steps.
 """
 import argparse
+import hashlib
 import json
 import os
 import sys
@@ -21,66 +24,90 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-P = (1 << 20) + 1          # the headline configuration: non-power-of-two, q = 21
+P = (1 << 20) + 1          # C2: non-power-of-two, q = 21
 ROOT_RANK = 0
-N_BLOCKS = 256             # expansion of the same tables; R = 276 rounds, x = 18 dummy rounds
+N_BLOCKS = 256             # C2's expansion; R = 276 rounds, x = 18 dummy rounds
+P_C3 = (1 << 27) - 1       # C3, the headline: q = 27, 2 x 14.5 GB of tables
+P_C4, N_C4 = 65537, 4096   # C4: q = 17, R = 4112 rounds, 2 x 1.078 GB of block tables
+COUNT_C5 = 1 << 20         # C5: seeded triples, p log-uniform in [2, 2^31 - 1]
 
 HBM_PEAK_GBS = 8000.0                       # MI355X HBM3E
 INT_VALU_PEAK_GOPS = 256 * 4 * 16 * 2.4     # CUs x SIMDs x lanes x GHz = 39 321.6 G lane-ops/s (32-bit, full rate)
 
 
-# HBM bytes per launch at this workload, from the rocprofv3 counter runs summarised in
-# profiles/bench_c2_kernels.md (FETCH_SIZE scaled x2.0, WRITE_SIZE x1.0 by the 1 GiB copy calibration).
-PROFILED_TRAFFIC_BYTES = {
-    "k_expand_rows": (2 * 35344 + 1130583) * 1024,
-    "k_recv_uniform": (2 * 11364 + 132103) * 1024,
-    "k_send_lookup": (2 * 15914 + 110592) * 1024,
-    "k_digits": (2 * 32 + 4096) * 1024,
+def csrc_digest():
+    """Short hash of the kernel sources: counter figures below are tied to the sources they were profiled on."""
+    h = hashlib.sha256()
+    d = os.path.join(ROOT, "paper_2205_10072_amd", "csrc")
+    for name in sorted(os.listdir(d)):
+        if name.endswith((".h", ".hip")):
+            with open(os.path.join(d, name), "rb") as f:
+                h.update(name.encode() + b"\0" + f.read())
+    return h.hexdigest()[:16]
+
+
+# Counter figures that this run does not measure itself: rocprofv3 --pmc runs of this same file, summarised under
+# profiles/ (FETCH_SIZE scaled x2.0 and WRITE_SIZE x1.0 by the 1 GiB copy calibration; KiB per dispatch).
+# Key: (config, kernel).  `csrc`: csrc_digest() of the sources that were profiled; when the sources have changed
+# since, the record is still printed but marked "stale": true, and a warning goes to stderr.
+PROFILED = {
+    "csrc": "9f1a67ccba4318ad",
+    "source": "profiles/bench_c2_kernels.md, profiles/allgather_tables_p1048577_n256.md",
+    "counters": {
+        # valu_per_wave = SQ_INSTS_VALU / SQ_WAVES; active_lanes = SQ_THREAD_CYCLES_VALU / SQ_ACTIVE_INST_VALU (of 64)
+        ("C2", "k_expand_rows"): {"fetch_kib": 35344, "write_kib": 1130583, "valu_per_wave": 69.0, "active_lanes": 64.0, "waves": 1130500},
+        ("C2", "k_recv_uniform"): {"fetch_kib": 11364, "write_kib": 132103, "valu_per_wave": 1275.0, "active_lanes": 64.0, "waves": 16388},
+        ("C2", "k_send_lookup"): {"fetch_kib": 15914, "write_kib": 110592, "valu_per_wave": 359.9, "active_lanes": 64.0, "waves": 16388},
+        ("C2", "k_digits"): {"fetch_kib": 32, "write_kib": 4096, "valu_per_wave": 72.0, "active_lanes": 64.0, "waves": 16388},
+        ("AG", "k_allgather_tables"): {"fetch_kib": 41280, "write_kib": 2261412},
+    },
 }
 
 
-# SQ_INSTS_VALU / SQ_WAVES and SQ_THREAD_CYCLES_VALU / SQ_ACTIVE_INST_VALU of k_recv_uniform at this workload, from the
-# same profile: vector instructions a wave (one rank a lane) and lanes active per vector instruction.
-PROFILED_VALU_PER_WAVE = 1275
-PROFILED_ACTIVE_LANES = 64.0
+def profiled(config, kernel, digest):
+    ent = PROFILED["counters"].get((config, kernel))
+    if ent is None:
+        return None
+    out = dict(ent)
+    out["source"] = PROFILED["source"]
+    out["profiled_at_csrc"] = PROFILED["csrc"]
+    out["stale"] = PROFILED["csrc"] != digest
+    return out
 
 
-def digit_walks_per_rank(p, skips):
-    """Digit walks k_recv_uniform runs per rank at root 0, averaged over all ranks: one for the rank itself, one for
-    the first window's upper end, and one per round n = 1..q-1 in which some lane of the wave lacks skips[n] among
-    its digits (when the whole wave has it, the end point's digits are the rank's with that digit taken out; the last
-    round's end point is the rank itself).  Counted here by doing the greedy sums (Alg. 2's walk) of all ranks with
-    numpy, 64 consecutive ranks a wave as the kernel lays them out."""
-    import numpy as np
-    q = len(skips) - 1
-    rest = np.arange(p, dtype=np.int64)
-    digits = np.zeros(p, dtype=np.int64)
-    for k in range(q - 1, -1, -1):
-        take = rest >= skips[k]
-        rest -= take * skips[k]
-        digits |= take.astype(np.int64) << k
-    waves = -(-p // 64)
-    padded = np.zeros(waves * 64, dtype=np.int64)        # idle lanes replay rank 0, which has no digits
-    padded[:p] = digits
-    shared = np.bitwise_and.reduce(padded.reshape(waves, 64), axis=1)
-    direct = np.zeros(waves, dtype=np.int64)
-    for n in range(1, q):
-        direct += (shared >> n) & 1
-    return float(2 + (q - 1) - direct.mean())
+# ----------------------------------------------------------------------------------------------------------------
+# One model of the vector-ALU work of the construction, counted on the main path of the kernels' ISA and used for
+# every `alu` roofline below.  "Useful" lane-operations of one rank with its OWN q (a wave of the batch kernel runs
+# its loops to the largest q among its lanes; that excess, the second-range branch of Alg. 4, the byte copies of a
+# row and the sort of the batch kernel are not counted).  So `frac` = useful lane-ops/s / peak is at most the share
+# of time the vector ALUs are busy, and falls below it by divergence and by everything that is not the method.
+#   a round of Alg. 4 on two digit masks            55 ops (window masks, candidate, bookkeeping; reads its end point)
+#   set-up of a row                                 50 ops
+#   a digit walk, one p per launch                  3 ops a level from level 7 up, 3 around the low-digit table read
+#   a digit walk, p per lane (batch kernel)         4 ops a level from level 7 up, 10 around it
+#   a row whose end points come from the table      55 q + 50
+#   a row by walks                                  (q + 2) walks + 55 q + 50
+#   a send row by Alg. 5: entry i = rounds 0..i of the to-neighbour's row: sum over i of (i + 3) walks (or table
+#   reads) + 55 (i + 1) + 30
+# ----------------------------------------------------------------------------------------------------------------
+def ops_walk(q, per_lane):
+    return (4 * max(q - 7, 0) + 10) if per_lane else (3 * max(q - 7, 0) + 3)
 
 
-def valu_ops_per_rank_tabled(q):
-    """The same row when the digit masks of all ranks are in a table (launches over all ranks):
-    55 ops a round, which include the read of the round's end point, and 50 of set-up."""
+def ops_recv_tabled(q):
     return 55 * q + 50
 
 
-def valu_ops_per_rank(q, walks):
-    """Vector-ALU lane-operations one receive row costs on the main path of k_recv_uniform, counted from its ISA:
-    `walks` digit walks of 3 ops a level for the levels from 7 up and 3 ops around the table read that stands for
-    the seven levels below, 55 ops of window logic and bookkeeping a round, 50 of set-up.
-    The wave-uniform branch for Alg. 4's second range is extra work and not counted."""
-    return (3 * max(q - 7, 0) + 3) * walks + 55 * q + 50
+def ops_recv_walks(q, per_lane, walks=None):
+    walks = (q + 2) if walks is None else walks
+    return walks * ops_walk(q, per_lane) + 55 * q + 50
+
+
+def ops_send_alg5(q, per_lane, tabled=False):
+    total = 0
+    for i in range(q):
+        total += (0 if tabled else (i + 3) * ops_walk(q, per_lane)) + 55 * (i + 1) + 30
+    return total
 
 
 def measure_valu_peak(torch, bcs):
@@ -98,28 +125,7 @@ def measure_valu_peak(torch, bcs):
     return ops / (ms / cnt) / 1e6
 
 
-def cpu_baseline(budget_s=10.0):
-    """The oracle, as it stands, on the host cores: whole steps of the same workload until the budget is spent;
-    then one more step on a single thread."""
-    import oracle
-
-    def one_step(threads):
-        recv, send = oracle.sched_range(P, root=ROOT_RANK, threads=threads)
-        oracle.expand(P, N_BLOCKS, recv, threads=threads)
-        oracle.expand(P, N_BLOCKS, send, threads=threads)
-
-    threads = min(16, os.cpu_count() or 1)
-    done = 0
-    t0 = time.perf_counter()
-    while True:
-        one_step(threads)
-        done += 1
-        el = time.perf_counter() - t0
-        if el >= budget_s or done >= 1000:
-            break
-    t1 = time.perf_counter()
-    one_step(1)
-    single = time.perf_counter() - t1
+def cpu_info():
     model = ""
     try:
         with open("/proc/cpuinfo") as f:
@@ -129,10 +135,251 @@ def cpu_baseline(budget_s=10.0):
                     break
     except OSError:
         pass
-    return {"value": done * P / el, "unit": "rank-schedules/s", "cores": threads, "kind": "oracle",
-            "sample": "%d whole steps (all %d ranks: recv by Alg. 4, send by look-up, expansion n=%d), %.1f s"
-                      % (done, P, N_BLOCKS, el),
-            "single_thread_value": P / single, "host_cpus": os.cpu_count(), "cpu_model": model}
+    return {"host_cpus": os.cpu_count(), "cpu_model": model}
+
+
+def cpu_threads():
+    return min(16, os.cpu_count() or 1)
+
+
+def cpu_repeat(fn, budget_s):
+    """Runs fn() until the budget is spent (at least once); returns (calls, seconds)."""
+    done = 0
+    t0 = time.perf_counter()
+    while True:
+        fn()
+        done += 1
+        el = time.perf_counter() - t0
+        if el >= budget_s or done >= 1000:
+            return done, el
+
+
+def timed_steps(torch, bcs, step, steps, warmup):
+    """`warmup` untimed steps, then two regions of exactly `steps` steps each: the plain launches (throughput), and
+    the same steps with every launch carrying its own start/stop events (device time per kernel; the events cost a
+    few microseconds a launch).  Returns (ms per step, ms per step with events, {kernel: (sum ms, launches, min, max)})."""
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    bcs.bcs_timing_begin()
+    torch.cuda.synchronize()
+    t2 = time.perf_counter()
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    t3 = time.perf_counter()
+    timing = bcs.bcs_timing_stats()
+    return (t1 - t0) * 1e3 / steps, (t3 - t2) * 1e3 / steps, timing
+
+
+def kernel_records(timing, steps, models, config, digest):
+    """Per-kernel entries from the device-side durations.  `models`: {kernel: ("hbm", bytes per launch) or
+    ("alu", useful lane-ops per launch)}; kernels without a model are listed with their times only."""
+    out = {}
+    for name, (ms, cnt, shortest, longest) in timing.items():
+        avg_ms = ms / cnt
+        ent = {"launches_per_step": cnt / steps, "avg_ms": avg_ms, "min_ms": shortest, "max_ms": longest,
+               "ms_per_step": ms / steps}
+        if name in models:
+            bound, amount = models[name]
+            if bound == "hbm":
+                ent.update(bound="hbm", achieved=amount / avg_ms / 1e6, peak=HBM_PEAK_GBS, unit="GB/s",
+                           algorithmic_bytes=amount)
+            else:
+                ent.update(bound="alu", achieved=amount / avg_ms / 1e6, peak=INT_VALU_PEAK_GOPS, unit="Gop/s",
+                           useful_lane_ops=amount)
+            ent["frac"] = ent["achieved"] / ent["peak"]
+            prof = profiled(config, name, digest)
+            ent["traffic"] = None
+            if prof is not None:
+                if "fetch_kib" in prof and "write_kib" in prof:
+                    ent["traffic"] = (2 * prof["fetch_kib"] + prof["write_kib"]) * 1024
+                if "valu_per_wave" in prof and "waves" in prof:
+                    # share of the kernel's time that its vector instructions need on 1024 SIMDs at 4 cycles each
+                    prof["valu_busy"] = prof["valu_per_wave"] * prof["waves"] * 4 / (1024 * 2.4e9) / (avg_ms * 1e-3)
+                if "active_lanes" in prof:
+                    prof["active_lane_fraction"] = prof["active_lanes"] / 64.0
+                ent["counters"] = prof
+        out[name] = ent
+    return out
+
+
+def dominant(kernels):
+    name = max((k for k in kernels if "frac" in kernels[k]), key=lambda k: kernels[k]["ms_per_step"])
+    return dict(kernels[name], kernel=name)
+
+
+# ----------------------------------------------------------------------------------------------------------------
+# The configurations
+# ----------------------------------------------------------------------------------------------------------------
+def run_c3(torch, bcs, steps, warmup, digest):
+    p = P_C3
+    q = bcs.bcs_q(p)
+    recv = torch.empty((p, q), dtype=torch.int32, device="cuda")
+    send = torch.empty((p, q), dtype=torch.int32, device="cuda")
+    ws = torch.empty(bcs.bcs_sched_workspace_bytes(p, 0, p), dtype=torch.uint8, device="cuda")
+
+    def step():
+        bcs.bcs_sched_rooted_ws(p, ROOT_RANK, 0, p, recv, send, ws)
+
+    ms, ms_ev, timing = timed_steps(torch, bcs, step, steps, warmup)
+    models = {"k_recv_uniform": ("alu", ops_recv_tabled(q) * p),
+              "k_digits": ("alu", (ops_walk(q, False) + 12) * p),
+              "k_send_lookup": ("hbm", p * q * (1 + 4))}          # reads the slot-major bytes, writes one int32 table
+    kernels = kernel_records(timing, steps, models, "C3", digest)
+    del recv, send, ws
+    torch.cuda.empty_cache()
+    return {"workload": "C3: p=2^27-1 (q=27), all ranks, root 0: int32 recv rows (Alg. 4) and send rows (look-up), "
+                        "2 x 14.5 GB written per step", "p": p, "q": q,
+            "steps": steps, "ms_per_step": ms, "ms_per_step_with_kernel_events": ms_ev,
+            "value": p / (ms * 1e-3), "unit": "rank-schedules/s",
+            "written_GBps": 2 * p * q * 4 / ms / 1e6,
+            "roofline": dominant(kernels), "kernels": kernels}
+
+
+def cpu_c3(budget_s):
+    import oracle
+    p, rows, threads = P_C3, 1 << 22, cpu_threads()
+    calls, el = cpu_repeat(lambda: oracle.sched_range(p, r0=12345, r1=12345 + rows, want_send=False, threads=threads),
+                           budget_s)
+    return dict({"value": calls * rows / el, "unit": "rank-schedules/s", "cores": threads, "kind": "oracle",
+                 "sample": "receive rows (Alg. 4) of %d x 2^22 ranks of p=2^27-1, from rank 12345, %.1f s; the send rows "
+                           "by look-up are a gather of receive rows and are not in the sample" % (calls, el)},
+                **cpu_info())
+
+
+def run_c2(torch, bcs, steps, warmup, digest):
+    q = bcs.bcs_q(P)
+    R = bcs.bcs_rounds(P, N_BLOCKS)
+    recv = torch.empty((P, q), dtype=torch.int32, device="cuda")
+    send = torch.empty((P, q), dtype=torch.int32, device="cuda")
+    rb = torch.empty((P, R), dtype=torch.int32, device="cuda")
+    sb = torch.empty((P, R), dtype=torch.int32, device="cuda")
+    ws = torch.empty(bcs.bcs_sched_expand_workspace_bytes(P, N_BLOCKS), dtype=torch.uint8, device="cuda")
+
+    def step():
+        # one call: receive rows, send rows by look-up, both block tables
+        bcs.bcs_sched_expand_ws(P, ROOT_RANK, N_BLOCKS, recv, send, rb, sb, ws)
+
+    ms, ms_ev, timing = timed_steps(torch, bcs, step, steps, warmup)
+    models = {"k_expand_rows": ("hbm", P * R * 4), "k_expand": ("hbm", P * R * 4),
+              "k_send_lookup": ("hbm", P * q * (1 + 4) + P * 24),   # slot-major bytes in; one table and its byte rows out
+              "k_recv_uniform": ("alu", ops_recv_tabled(q) * P),
+              "k_digits": ("alu", (ops_walk(q, False) + 12) * P)}
+    kernels = kernel_records(timing, steps, models, "C2", digest)
+    construct_ms = sum(kernels[k]["ms_per_step"] for k in ("k_digits", "k_recv_uniform", "k_send_lookup") if k in kernels)
+    exp = kernels.get("k_expand_rows") or kernels.get("k_expand")
+    return {"workload": "C2: p=2^20+1 (q=21), all ranks, root 0: recv+send schedules, then expansion n=%d (R=%d "
+                        "rounds), one call a step" % (N_BLOCKS, R), "p": P, "q": q, "n": N_BLOCKS, "rounds": R,
+            "steps": steps, "ms_per_step": ms, "ms_per_step_with_kernel_events": ms_ev,
+            "value": P / (ms * 1e-3), "unit": "rank-schedules/s (schedules and both block tables)",
+            "construct_rank_schedules_per_s": P / (construct_ms * 1e-3),
+            "expand_gbs": exp["achieved"] if exp else None,
+            "roofline": dominant(kernels), "kernels": kernels}
+
+
+def cpu_c2(budget_s):
+    import oracle
+    threads = cpu_threads()
+
+    def one_step():
+        recv, send = oracle.sched_range(P, root=ROOT_RANK, threads=threads)
+        oracle.expand(P, N_BLOCKS, recv, threads=threads)
+        oracle.expand(P, N_BLOCKS, send, threads=threads)
+
+    calls, el = cpu_repeat(one_step, budget_s)
+    return {"value": calls * P / el, "unit": "rank-schedules/s (schedules and both block tables)", "cores": threads,
+            "kind": "oracle", "sample": "%d whole steps (all %d ranks: recv by Alg. 4, send by look-up, expansion "
+                                        "n=%d), %.1f s" % (calls, P, N_BLOCKS, el)}
+
+
+def run_c4(torch, bcs, steps, warmup, digest):
+    p, n = P_C4, N_C4
+    q, R = bcs.bcs_q(p), bcs.bcs_rounds(p, n)
+    recv = torch.empty((p, q), dtype=torch.int32, device="cuda")
+    send = torch.empty((p, q), dtype=torch.int32, device="cuda")
+    bcs.bcs_sched(p, 0, p, recv, send)
+    rb = torch.empty((p, R), dtype=torch.int32, device="cuda")
+    sb = torch.empty((p, R), dtype=torch.int32, device="cuda")
+    ws = torch.empty(bcs.bcs_expand_workspace_bytes(p, n, 0, p), dtype=torch.uint8, device="cuda")
+    nbytes = 2 * p * R * 4
+    models = {"k_expand": ("hbm", p * R * 4), "k_expand_rows": ("hbm", p * R * 4),
+              "k_rows_to_bytes": ("hbm", p * q * 4 + p * 24)}
+    out = {"workload": "C4: p=65537 (q=17), n=4096 blocks (R=%d rounds): both (rank, round) -> block tables from "
+                       "the schedule tables, 2 x %.3f GB written per step" % (R, p * R * 4 / 1e9),
+           "p": p, "q": q, "n": n, "rounds": R, "steps": steps}
+    for key, step in (("bcs_expand", lambda: bcs.bcs_expand(p, n, 0, p, recv, send, rb, sb)),
+                      ("bcs_expand_ws", lambda: bcs.bcs_expand_ws(p, n, 0, p, recv, send, rb, sb, ws))):
+        ms, ms_ev, timing = timed_steps(torch, bcs, step, steps, warmup)
+        kernels = kernel_records(timing, steps, models, "C4", digest)
+        dev_ms = sum(k["ms_per_step"] for k in kernels.values())
+        out[key] = {"ms_per_step": ms, "ms_per_step_with_kernel_events": ms_ev, "device_ms_per_step": dev_ms,
+                    "value": nbytes / ms / 1e6, "unit": "GB/s written (wall)",
+                    "expand_gbs": nbytes / dev_ms / 1e6, "expand_frac": nbytes / dev_ms / 1e6 / HBM_PEAK_GBS,
+                    "roofline": dominant(kernels), "kernels": kernels}
+    out["roofline"] = out["bcs_expand_ws"]["roofline"]
+    out["expand_gbs"] = out["bcs_expand_ws"]["expand_gbs"]
+    out["expand_frac"] = out["bcs_expand_ws"]["expand_frac"]
+    return out
+
+
+def cpu_c4(budget_s):
+    import oracle
+    p, n, threads = P_C4, N_C4, cpu_threads()
+    recv, send = oracle.sched_range(p, threads=threads)
+    R = n - 1 + recv.shape[1]
+
+    def both():
+        oracle.expand(p, n, recv, threads=threads)
+        oracle.expand(p, n, send, threads=threads)
+
+    calls, el = cpu_repeat(both, budget_s)
+    return {"value": calls * 2 * p * R * 4 / el / 1e9, "unit": "GB/s written", "cores": threads, "kind": "oracle",
+            "sample": "%d whole expansions of both tables (p=65537, n=4096), %.1f s" % (calls, el)}
+
+
+def run_c5(torch, bcs, steps, warmup, digest):
+    import numpy as np
+    from paper_2205_10072_amd import synth
+    count = COUNT_C5
+    hp, hr, hroot = synth.batch_triples(count)
+    pp, rr, ro = (torch.from_numpy(a).cuda() for a in (hp, hr, hroot))
+    brecv = torch.empty((count, 32), dtype=torch.int32, device="cuda")
+    bsend = torch.empty((count, 32), dtype=torch.int32, device="cuda")
+    qv = torch.empty(count, dtype=torch.int32, device="cuda")
+    qs = np.array([int(v - 1).bit_length() for v in hp.tolist()], dtype=np.int64)
+    hist = np.bincount(qs, minlength=32)
+    ops_recv = sum(int(hist[q]) * ops_recv_walks(q, True) for q in range(32))
+    ops_send = sum(int(hist[q]) * ops_send_alg5(q, True) for q in range(32))
+    out = {"workload": "C5: 2^20 seeded (p, r, root) triples, p log-uniform in [2, 2^31-1] (mixed q), rows of stride 32: "
+                       "receive rows by Alg. 4, send rows by Alg. 5 (no neighbour rows exist)",
+           "count": count, "steps": steps, "mean_q": float(qs.mean())}
+    for key, step, ops in (("recv_and_send", lambda: bcs.bcs_sched_batch(pp, rr, ro, brecv, bsend, qv), ops_recv + ops_send),
+                           ("recv_only", lambda: bcs.bcs_sched_batch(pp, rr, ro, brecv, None, qv), ops_recv)):
+        ms, ms_ev, timing = timed_steps(torch, bcs, step, steps, warmup)
+        kernels = kernel_records(timing, steps, {"k_batch": ("alu", ops)}, "C5 " + key, digest)
+        out[key] = {"ms_per_step": ms, "ms_per_step_with_kernel_events": ms_ev,
+                    "value": count / (ms * 1e-3), "unit": "rank-schedules/s" if key == "recv_and_send" else "receive rows/s",
+                    "useful_lane_ops_per_rank": ops / count, "roofline": dominant(kernels), "kernels": kernels}
+    out["value"] = out["recv_and_send"]["value"]
+    out["unit"] = "rank-schedules/s"
+    out["roofline"] = out["recv_and_send"]["roofline"]
+    return out
+
+
+def cpu_c5(budget_s):
+    import oracle
+    from paper_2205_10072_amd import synth
+    sample, threads = 1 << 17, cpu_threads()
+    hp, hr, hroot = synth.batch_triples(COUNT_C5)
+    calls, el = cpu_repeat(lambda: oracle.sched_batch(hp[:sample], hr[:sample], hroot[:sample], threads=threads), budget_s)
+    return {"value": calls * sample / el, "unit": "rank-schedules/s", "cores": threads, "kind": "oracle",
+            "sample": "%d x the first 2^17 of the 2^20 triples (recv by Alg. 4, send by Alg. 5), %.1f s" % (calls, el)}
 
 
 AG_PROCESS = 777777        # the process whose tables are built in the allgather-tables workload
@@ -186,10 +433,14 @@ def bench_allgather_tables(torch, bcs, args):
                    "p": P, "q": q, "n": N_BLOCKS, "rounds": R},
         "roofline": {"kernel": "k_allgather_tables", "bound": "hbm", "achieved": nbytes / avg_ms / 1e6,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": nbytes / avg_ms / 1e6 / HBM_PEAK_GBS,
-                     # from profiles/allgather_tables_p1048577_n256.md (FETCH_SIZE x2.0, WRITE_SIZE x1.0)
-                     "traffic": (2 * 41280 + 2261412) * 1024, "avg_ms": avg_ms},
+                     "traffic": None, "avg_ms": avg_ms},
         "kernels_ms": {k: v[0] / v[1] for k, v in timing.items()},
+        "csrc": csrc_digest(),
     }
+    prof = profiled("AG", "k_allgather_tables", out["csrc"])
+    if prof is not None:
+        out["roofline"]["traffic"] = (2 * prof["fetch_kib"] + prof["write_kib"]) * 1024
+        out["roofline"]["counters"] = prof
     if not args.no_cpu_baseline:
         import oracle
         t0 = time.perf_counter()
@@ -197,98 +448,6 @@ def bench_allgather_tables(torch, bcs, args):
         el = time.perf_counter() - t0
         out["cpu_baseline"] = {"value": nbytes / el / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
                                "sample": "one whole call (full schedule of all ranks, then both tables), %.1f s" % el}
-    return out
-
-
-def bench_configs(torch, bcs, args):
-    """Per-call device time of the baseline's other configurations (each parity-tested in tests/)."""
-    from paper_2205_10072_amd import synth
-    reps = max(3, min(args.steps, 20))
-
-    def kernels(fn):
-        fn()
-        torch.cuda.synchronize()
-        bcs.bcs_timing_begin()
-        for _ in range(reps):
-            fn()
-        torch.cuda.synchronize()
-        t = bcs.bcs_timing_end()
-        return {k: v[0] / v[1] * (v[1] / reps) for k, v in t.items()}      # ms per call, summed over its launches
-
-    out = {"metric": "per-call device time of the other baseline configurations", "unit": "ms", "n_gpus": 1,
-           "steps": reps, "data": "synthetic", "dtype": "int32", "results": {}}
-    res = out["results"]
-    # C3: p = 2^27 - 1, all ranks, recv + send by look-up
-    p = (1 << 27) - 1
-    q = bcs.bcs_q(p)
-    recv = torch.empty((p, q), dtype=torch.int32, device="cuda")
-    send = torch.empty((p, q), dtype=torch.int32, device="cuda")
-    k = kernels(lambda: bcs.bcs_sched(p, 0, p, recv, send))
-    ms = sum(k.values())
-    res["C3 p=2^27-1 all ranks recv+send"] = {"ms": ms, "kernels_ms": k, "rank_schedules_per_s": p / ms * 1e3,
-                                              "written_GBps": 2 * p * q * 4 / ms / 1e6}
-    # partial range of the same p: send rows by Alg. 5
-    n_part = 1 << 20
-    k = kernels(lambda: bcs.bcs_sched(p, 12345, 12345 + n_part, recv[:n_part], send[:n_part]))
-    ms = sum(k.values())
-    res["p=2^27-1, 2^20 ranks, send by Alg. 5"] = {"ms": ms, "kernels_ms": k, "rank_schedules_per_s": n_part / ms * 1e3}
-    del recv, send
-    bcs.bcs_release()
-    torch.cuda.empty_cache()
-    # C2 partial
-    p = (1 << 20) + 1
-    q = bcs.bcs_q(p)
-    recv = torch.empty((n_part, q), dtype=torch.int32, device="cuda")
-    send = torch.empty((n_part, q), dtype=torch.int32, device="cuda")
-    k = kernels(lambda: bcs.bcs_sched(p, 1, 1 + n_part, recv, send))
-    ms = sum(k.values())
-    res["p=2^20+1, 2^20 ranks, send by Alg. 5"] = {"ms": ms, "kernels_ms": k, "rank_schedules_per_s": n_part / ms * 1e3}
-    # short rows, all four tables of all ranks: one call (fused kernels) against the separate calls
-    n = 64
-    R = bcs.bcs_rounds(p, n)
-    recv = torch.empty((p, q), dtype=torch.int32, device="cuda")
-    send = torch.empty((p, q), dtype=torch.int32, device="cuda")
-    rb = torch.empty((p, R), dtype=torch.int32, device="cuda")
-    sb = torch.empty((p, R), dtype=torch.int32, device="cuda")
-    ws = torch.empty(bcs.bcs_sched_workspace_bytes(p, 0, p), dtype=torch.uint8, device="cuda")
-    k = kernels(lambda: bcs.bcs_sched_expand_ws(p, 0, n, recv, send, rb, sb, ws))
-    ms = sum(k.values())
-    res["p=2^20+1 n=64 schedules+tables, one call"] = {"ms": ms, "kernels_ms": k, "rank_schedules_per_s": p / ms * 1e3}
-    k = kernels(lambda: (bcs.bcs_sched_rooted_ws(p, 0, 0, p, recv, send, ws), bcs.bcs_expand(p, n, 0, p, recv, send, rb, sb)))
-    ms = sum(k.values())
-    res["p=2^20+1 n=64 schedules+tables, separate calls"] = {"ms": ms, "kernels_ms": k,
-                                                             "rank_schedules_per_s": p / ms * 1e3}
-    del rb, sb, ws
-    # C4: expansion p = 65537, n = 4096
-    p, n = 65537, 4096
-    q, R = bcs.bcs_q(p), bcs.bcs_rounds(p, n)
-    recv = torch.empty((p, q), dtype=torch.int32, device="cuda")
-    send = torch.empty((p, q), dtype=torch.int32, device="cuda")
-    bcs.bcs_sched(p, 0, p, recv, send)
-    rb = torch.empty((p, R), dtype=torch.int32, device="cuda")
-    sb = torch.empty((p, R), dtype=torch.int32, device="cuda")
-    k = kernels(lambda: bcs.bcs_expand(p, n, 0, p, recv, send, rb, sb))
-    ms = sum(k.values())
-    res["C4 expand p=65537 n=4096"] = {"ms": ms, "kernels_ms": k, "written_GBps": 2 * p * R * 4 / ms / 1e6,
-                                      "frac_of_hbm_peak": 2 * p * R * 4 / ms / 1e6 / HBM_PEAK_GBS}
-    ws = torch.empty(bcs.bcs_expand_workspace_bytes(p, n, 0, p), dtype=torch.uint8, device="cuda")
-    k = kernels(lambda: bcs.bcs_expand_ws(p, n, 0, p, recv, send, rb, sb, ws))
-    ms = sum(k.values())
-    res["C4 expand p=65537 n=4096, with workspace"] = {"ms": ms, "kernels_ms": k, "written_GBps": 2 * p * R * 4 / ms / 1e6,
-                                                      "frac_of_hbm_peak": 2 * p * R * 4 / ms / 1e6 / HBM_PEAK_GBS}
-    del ws
-    del rb, sb
-    # C5: 2^20 seeded triples, mixed q
-    count = 1 << 20
-    pp, rr, ro = (torch.from_numpy(a).cuda() for a in synth.batch_triples(count))
-    brecv = torch.empty((count, 32), dtype=torch.int32, device="cuda")
-    bsend = torch.empty((count, 32), dtype=torch.int32, device="cuda")
-    qv = torch.empty(count, dtype=torch.int32, device="cuda")
-    k = kernels(lambda: bcs.bcs_sched_batch(pp, rr, ro, brecv, bsend, qv))
-    ms = sum(k.values())
-    res["C5 batch 2^20 triples recv+send"] = {"ms": ms, "kernels_ms": k, "rank_schedules_per_s": count / ms * 1e3}
-    k = kernels(lambda: bcs.bcs_sched_batch(pp, rr, ro, brecv, None, qv))
-    res["C5 batch 2^20 triples recv only"] = {"ms": sum(k.values()), "rank_schedules_per_s": count / sum(k.values()) * 1e3}
     return out
 
 
@@ -385,20 +544,22 @@ def bench_pack_round(torch, bcs, args):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--steps", type=int, default=100,
+                    help="timed steps of the headline configuration (C3); the other configurations time min(steps, 100)")
+    ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--workload", choices=["step", "allgather-tables", "pack-round", "configs"], default="step",
-                    help="step (default): the hot path this benchmark is about.  allgather-tables: the first widening, "
-                         "Alg. 9's pack/unpack index tables of one process, reported as its own line.  pack-round: the second, "
-                         "packing and unpacking one round's message on irregular buffers.  configs: the other "
-                         "configurations of the baseline (largest p, expansion at p=65537, irregular batch, partial "
-                         "ranges), one line of per-call timings")
+    ap.add_argument("--workload", choices=["configs", "allgather-tables", "pack-round"], default="configs",
+                    help="configs (default): the hot path on the baseline's configurations C2..C5, headline on C3.  "
+                         "allgather-tables: the first widening, Alg. 9's pack/unpack index tables of one process, "
+                         "reported as its own line.  pack-round: the second, packing and unpacking one round's message "
+                         "on irregular buffers")
+    ap.add_argument("--only", default="C3,C2,C4,C5",
+                    help="comma-separated subset of C2,C3,C4,C5 to run (for profiler runs; the headline needs C3)")
     ap.add_argument("--graph", action="store_true",
-                    help="step workload only: also record the timed steps into one HIP graph and time its replay "
-                         "(reported as ms_per_step_in_hip_graph; `value` stays the plain launches)")
+                    help="also record the C2 steps into one HIP graph and time its replay "
+                         "(reported as ms_per_step_in_hip_graph in the C2 record)")
     ap.add_argument("--copy-calibration", action="store_true",
-                    help="also run three plain 1 GiB device copies before the timed region, so that a counter "
+                    help="also run three plain 1 GiB device copies before the timed regions, so that a counter "
                          "profile of this command holds a kernel of known traffic to scale FETCH_SIZE/WRITE_SIZE by")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -416,24 +577,14 @@ def main():
     if args.workload == "pack-round":
         print(json.dumps(bench_pack_round(torch, bcs, args)))
         return
-    if args.workload == "configs":
-        print(json.dumps(bench_configs(torch, bcs, args)))
-        return
-    q = bcs.bcs_q(P)
-    R = bcs.bcs_rounds(P, N_BLOCKS)
-    recv = torch.empty((P, q), dtype=torch.int32, device="cuda")
-    send = torch.empty((P, q), dtype=torch.int32, device="cuda")
-    rb = torch.empty((P, R), dtype=torch.int32, device="cuda")
-    sb = torch.empty((P, R), dtype=torch.int32, device="cuda")
-    ws = torch.empty(bcs.bcs_sched_expand_workspace_bytes(P, N_BLOCKS), dtype=torch.uint8, device="cuda")
-
-    def step():
-        # one call: receive rows, send rows by look-up, both block tables
-        bcs.bcs_sched_expand_ws(P, ROOT_RANK, N_BLOCKS, recv, send, rb, sb, ws)
-
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
+    only = [c.strip().upper() for c in args.only.split(",") if c.strip()]
+    for c in only:
+        if c not in ("C2", "C3", "C4", "C5"):
+            sys.exit("bench.py: unknown configuration %r in --only" % c)
+    digest = csrc_digest()
+    if PROFILED["counters"] and PROFILED["csrc"] != digest:
+        print("bench.py: kernel sources changed since the counter profiles were taken (%s -> %s): counter fields "
+              "are marked stale" % (PROFILED["csrc"], digest), file=sys.stderr)
     if args.copy_calibration:
         a = torch.zeros(1 << 28, dtype=torch.int32, device="cuda")      # 1 GiB read + 1 GiB written per copy
         b = torch.empty_like(a)
@@ -441,102 +592,79 @@ def main():
             b.copy_(a)
         torch.cuda.synchronize()
         del a, b
-    valu_peak_measured = measure_valu_peak(torch, bcs)
-    tabled = True                                        # all ranks: receive rows read the digit masks k_digits leaves
-    walks = 1.0 if tabled else digit_walks_per_rank(P, bcs.bcs_skips(P))
+        torch.cuda.empty_cache()
     steps = max(1, min(args.steps, 1000))
-    # Two timed regions of exactly `steps` steps each.  The first is the plain path and gives the throughput; in the
-    # second every launch carries its own start/stop events (which costs a few microseconds a launch, 4-5 % of a
-    # step here) and gives the per-kernel device times for the rooflines.
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(steps):
-        step()
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    ms_per_step = (t1 - t0) * 1e3 / steps
-    bcs.bcs_timing_begin()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(steps):
-        step()
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    timing = bcs.bcs_timing_stats()
-    ms_per_step_events = (t1 - t0) * 1e3 / steps
-
-    ms_per_step_graph = None
-    if args.graph:
-        # the same steps as one HIP graph: inside a graph the kernels of consecutive steps follow each other without
-        # the few microseconds that separate two launches of a stream
-        side = torch.cuda.Stream()
-        with torch.cuda.stream(side):
-            graph = torch.cuda.CUDAGraph()
-            with torch.cuda.graph(graph, stream=side):
-                for _ in range(steps):
-                    step()
-        torch.cuda.synchronize()
-        graph.replay()
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        graph.replay()
-        torch.cuda.synchronize()
-        ms_per_step_graph = (time.perf_counter() - t0) * 1e3 / steps
-
-    # per-kernel rooflines from the device-side durations of the timed region
-    kernels = {}
-    for name, (ms, cnt, shortest, longest) in timing.items():
-        avg_ms = ms / cnt
-        ent = {"launches_per_step": cnt / steps, "avg_ms": avg_ms, "min_ms": shortest, "max_ms": longest,
-               "ms_per_step": ms / steps}
-        if name in ("k_expand", "k_expand_rows"):
-            nbytes = P * R * 4                                  # one table per launch, written once
-            ent.update(bound="hbm", achieved=nbytes / avg_ms / 1e6, peak=HBM_PEAK_GBS, unit="GB/s")
-        elif name == "k_send_lookup":
-            nbytes = P * q * (1 + 4) + P * 24                   # read the slot-major bytes, write one table and its byte rows
-            ent.update(bound="hbm", achieved=nbytes / avg_ms / 1e6, peak=HBM_PEAK_GBS, unit="GB/s")
-        elif name == "k_recv_uniform":
-            ops = (valu_ops_per_rank_tabled(q) if tabled else valu_ops_per_rank(q, walks)) * P
-            waves = (P + 255) // 256 * 4
-            ent.update(bound="alu", achieved=ops / avg_ms / 1e6, peak=INT_VALU_PEAK_GOPS, unit="Gop/s",
-                       peak_measured=valu_peak_measured, frac_of_measured=ops / avg_ms / 1e6 / valu_peak_measured,
-                       # share of the kernel's time its vector instructions need on 1024 SIMDs at 4 cycles each
-                       valu_busy=PROFILED_VALU_PER_WAVE * 4 * waves / (1024 * 2.4e9) / (avg_ms * 1e-3),
-                       active_lane_fraction=PROFILED_ACTIVE_LANES / 64.0)
-        elif name == "k_digits":
-            ops = (3 * max(q - 7, 0) + 3 + 12) * P              # one walk a rank, address and store
-            ent.update(bound="alu", achieved=ops / avg_ms / 1e6, peak=INT_VALU_PEAK_GOPS, unit="Gop/s")
-        else:
-            continue
-        ent["frac"] = ent["achieved"] / ent["peak"]
-        ent["traffic"] = PROFILED_TRAFFIC_BYTES.get(name)
-        kernels[name] = ent
-    dominant = max(kernels, key=lambda k: kernels[k]["ms_per_step"])
-    roofline = dict(kernels[dominant], kernel=dominant)
-
+    sub_steps = min(steps, 100)
+    sub_warm = min(args.warmup, 5)
+    valu_peak_measured = measure_valu_peak(torch, bcs)
+    runners = {"C3": lambda: run_c3(torch, bcs, steps, args.warmup, digest),
+               "C2": lambda: run_c2(torch, bcs, sub_steps, sub_warm, digest),
+               "C4": lambda: run_c4(torch, bcs, sub_steps, sub_warm, digest),
+               "C5": lambda: run_c5(torch, bcs, sub_steps, sub_warm, digest)}
+    cpu = {"C3": (cpu_c3, 7.0), "C2": (cpu_c2, 5.0), "C4": (cpu_c4, 4.0), "C5": (cpu_c5, 5.0)}
+    configs = {}
+    for c in only:
+        configs[c] = runners[c]()
+        torch.cuda.empty_cache()
+    if args.graph and "C2" in configs:
+        configs["C2"]["ms_per_step_in_hip_graph"] = c2_in_graph(torch, bcs, sub_steps)
+    for rec in configs.values():                          # every alu roofline also against the measured ceiling
+        for k in [rec.get("roofline")] + list(rec.get("kernels", {}).values()) + \
+                 [sub.get("roofline") for sub in rec.values() if isinstance(sub, dict) and "roofline" in sub]:
+            if k and k.get("bound") == "alu":
+                k["peak_measured"] = valu_peak_measured
+                k["frac_of_measured"] = k["achieved"] / valu_peak_measured
+    if not args.no_cpu_baseline:
+        for c in only:
+            fn, budget = cpu[c]
+            configs[c]["cpu_baseline"] = fn(budget)
+    head = configs.get("C3") or configs[only[0]]
     out = {
         "metric": "rank-schedules constructed/s (int32, bit-exact) + expand GB/s vs HBM peak",
-        "value": P / (ms_per_step * 1e-3),
-        "unit": "rank-schedules/s",
-        "n_gpus": 1, "steps": steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
-        "ms_per_step_with_kernel_events": ms_per_step_events,
+        "value": head["value"], "unit": head["unit"],
+        "n_gpus": 1, "steps": head["steps"], "warmup": args.warmup if head is configs.get("C3") else sub_warm,
+        "ms_per_step": head.get("ms_per_step", head.get("recv_and_send", head.get("bcs_expand_ws", {})).get("ms_per_step")),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "int32", "data": "synthetic",
-        "config": {"workload": "p=2^20+1 (q=21), all ranks, root 0: recv+send schedules, then expansion n=%d "
-                               "(R=%d rounds)" % (N_BLOCKS, R), "p": P, "q": q, "n": N_BLOCKS, "rounds": R},
-        "expand_gbs": kernels["k_expand_rows"]["achieved"],
-        "construct_rank_schedules_per_s": P / (sum(kernels[k]["ms_per_step"] for k in
-                                                   ("k_digits", "k_recv_uniform", "k_send_lookup") if k in kernels)
-                                               * 1e-3),
-        "roofline": roofline,
-        "kernels": kernels,
-        "digit_walks_per_rank": walks,
+        "config": {"workload": head["workload"]},
+        "roofline": head["roofline"],
+        "csrc": digest,
     }
-    if ms_per_step_graph is not None:
-        out["ms_per_step_in_hip_graph"] = ms_per_step_graph
-    if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline()
+    if "C4" in configs:
+        out["expand_gbs"] = configs["C4"]["expand_gbs"]
+        out["expand_frac_of_hbm_peak"] = configs["C4"]["expand_frac"]
+        out["expand_config"] = configs["C4"]["workload"]
+    if "cpu_baseline" in head:
+        out["cpu_baseline"] = head["cpu_baseline"]
+    out["configs"] = configs
     print(json.dumps(out))
+
+
+def c2_in_graph(torch, bcs, steps):
+    """The C2 steps as one HIP graph: inside a graph the kernels of consecutive steps follow each other without the
+    few microseconds that separate two launches of a stream."""
+    q = bcs.bcs_q(P)
+    R = bcs.bcs_rounds(P, N_BLOCKS)
+    recv = torch.empty((P, q), dtype=torch.int32, device="cuda")
+    send = torch.empty((P, q), dtype=torch.int32, device="cuda")
+    rb = torch.empty((P, R), dtype=torch.int32, device="cuda")
+    sb = torch.empty((P, R), dtype=torch.int32, device="cuda")
+    ws = torch.empty(bcs.bcs_sched_expand_workspace_bytes(P, N_BLOCKS), dtype=torch.uint8, device="cuda")
+    bcs.bcs_sched_expand_ws(P, ROOT_RANK, N_BLOCKS, recv, send, rb, sb, ws)
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            for _ in range(steps):
+                bcs.bcs_sched_expand_ws(P, ROOT_RANK, N_BLOCKS, recv, send, rb, sb, ws)
+    torch.cuda.synchronize()
+    graph.replay()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    graph.replay()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) * 1e3 / steps
 
 
 if __name__ == "__main__":
