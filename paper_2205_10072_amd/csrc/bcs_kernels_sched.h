@@ -47,29 +47,6 @@ __device__ __forceinline__ void byte_rows_out(const int8_t *tileB, uint32_t rows
     if (e < n4) reinterpret_cast<int32_t *>(dst)[e] = reinterpret_cast<const int32_t *>(tileB)[e];
 }
 
-// The byte rows of a workgroup packed straight from its int32 tile (row stride Q | 1), four entries a dword:
-// for a kernel that has vector-ALU time to spare and should not spend LDS on a byte tile.
-template <int Q>
-__device__ __forceinline__ void byte_rows_from_tile(const int32_t *tile, uint32_t rows, int8_t *__restrict__ dst) {
-    constexpr int kStride = Q | 1;
-    constexpr int kW4 = byte_row_stride(Q) / 4;                   // dwords per byte row
-    const uint32_t n4 = rows * kW4;
-    for (uint32_t g = threadIdx.x; g < n4; g += kBlock) {
-        const uint32_t row = g / kW4, w = g - row * kW4;
-        const int32_t *src = tile + row * kStride;
-        uint32_t packed = 0;
-#pragma unroll
-        for (int c = 0; c < 4; ++c) {
-            const uint32_t pos = 4u * w + c;
-            const bool slot_ok = pos < (uint32_t)(Q + 3);          // the row's slots and its three mirrors
-            const uint32_t slot = pos < (uint32_t)Q ? pos : (slot_ok ? pos - Q : 0u);
-            const int32_t t = slot_ok ? src[slot] - (int32_t)slot : 0;
-            packed |= ((uint32_t)t & 0xffu) << (8 * c);
-        }
-        reinterpret_cast<uint32_t *>(dst)[g] = packed;
-    }
-}
-
 // Rows of a workgroup's LDS tile (row stride Q | 1) to their place in a rank-major table.  For odd Q the tile is
 // already laid out like the table, so it leaves as 16-byte pieces with no index arithmetic.
 template <int Q>
@@ -158,31 +135,121 @@ __global__ __launch_bounds__(kBlock) void k_recv_uniform(const SkipTab tab, uint
 }
 
 // K2: send rows from the slot-major receive table of ALL ranks (Alg. 9, second loop):
-// send[r][k] = recv[(r + skips[k]) mod p][k].  Reads are contiguous per slot, rows leave through LDS.
-template <int Q>
-__global__ __launch_bounds__(kBlock) void k_send_lookup(const SkipTab tab, const slot_t *__restrict__ recvT,
-                                                        uint64_t ldT, int32_t *__restrict__ send_out,
-                                                        int8_t *__restrict__ rowsB) {
-    constexpr int kStride = Q | 1;
-    constexpr int kRS = byte_row_stride(Q);
-    __shared__ __align__(16) int32_t tile[kBlock * kStride];
+// send[r][k] = recv[(r + skips[k]) mod p][k].
+// One wave (a workgroup of 64 lanes) takes G consecutive ranks.  Reading: a lane fetches the entries of FOUR
+// consecutive ranks in one slot with one (unaligned) 4-byte load -- the table is slot-major bytes, so the four
+// neighbours' entries are adjacent -- and the 64 lanes cover 64 / (G/4) slots at a time; all loads of a wave are in
+// flight together.  Byte loads, one rank a lane, cost the address path of the memory pipeline four times as many
+// instructions for the same bytes, and that path, not the HBM, was the limit (measured on MI355X at p = 2^27-1:
+// 3.8 ms against 18.1 GB / 8 TB/s = 2.3 ms).  The words go to an LDS tile of bytes, slot-major with padded rows;
+// then the wave writes its ranks' rows -- one contiguous piece of G q int32 -- as 16-byte streaming stores in
+// address order, each lane gathering the four entries of its store from the tile.
+// Measured at p = 2^27-1 (18.1 GB): 3.24 ms with G = 256, 3.38 ms with G = 128, 4.35 ms with G = 64 (4.3 KB of
+// loads in flight per wave are too few); at p = 2^20+1: 0.0212, 0.0199, 0.0231 ms.  So many ranks take G = 256
+// and fewer take G = 128 (more waves to spread over the device).  The reading side alone (no stores) takes
+// 0.65 ms and the stores alone 2.6 ms (a wave streaming 27 KB: 5.5 TB/s; a store-only kernel whose workgroups
+// write one aligned 4 KB piece each reaches 6.6-7.0 TB/s, but a workgroup that short cannot keep enough loads in
+// flight: measured 4.4-5.4 ms in that shape); the whole kernel takes about their sum, reads and writes do not
+// overlap in the memory system.
+constexpr int kLookupLanes = 64;
+constexpr int kLookupBigG = 256, kLookupSmallG = 128;
+constexpr int kLookupBigMinQ = 22;                      // p > 2^21: a wave takes kLookupBigG ranks
+
+template <int Q, int G>
+__global__ __launch_bounds__(kLookupLanes) void k_send_lookup(const SkipTab tab, const slot_t *__restrict__ recvT,
+                                                              uint64_t ldT, int32_t *__restrict__ send_out,
+                                                              int8_t *__restrict__ rowsB) {
+    static_assert(G % 4 == 0 && kLookupLanes % (G / 4) == 0 && G <= 4 * kLookupLanes, "a lane takes four ranks of one slot");
+    constexpr int kQuads = G / 4;                                  // lanes that cover one slot of the group
+    constexpr int kSlotsPerLoad = kLookupLanes / kQuads;
+    constexpr int kLoads = (Q + kSlotsPerLoad - 1) / kSlotsPerLoad;
+    constexpr int kRS = G + 4;                                     // bytes per slot row of the tile (padded: banks)
+    constexpr int kStores = (G * Q + 4 * kLookupLanes - 1) / (4 * kLookupLanes);
+    __shared__ __align__(16) int8_t tile[Q * kRS];
     const uint32_t p = tab.s[Q];
-    const uint64_t first = (uint64_t)blockIdx.x * kBlock;
-    const uint64_t idx = first + threadIdx.x;
-    const bool live = idx < p;
-    int32_t *my = tile + threadIdx.x * kStride;
-    if (live) {
+    const uint64_t first = (uint64_t)blockIdx.x * G;               // < p: the grid has ceil(p / G) workgroups
+    const uint32_t lane = threadIdx.x;
+    const uint32_t j4 = (lane % kQuads) * 4u;                      // this lane's four ranks within the group
+    const uint32_t kk = lane / kQuads;
+    uint32_t got[kLoads];
 #pragma unroll
-        for (int k = 0; k < Q; ++k) {
-            uint32_t t = (uint32_t)idx + tab.s[k];
+    for (int it = 0; it < kLoads; ++it) {
+        const uint32_t k = it * kSlotsPerLoad + kk;
+        const uint32_t kc = k < (uint32_t)Q ? k : (uint32_t)Q - 1u;    // lanes past the last slot repeat it; never stored
+        const uint32_t sk = ((p - 1u) >> (Q - kc)) + 1u;           // skips[k]: the closed form of Alg. 1's halving
+        const uint64_t r = first + j4;
+        uint32_t word = 0;
+        if (r < p) {
+            uint32_t t = (uint32_t)r + sk;                         // below 2p < 2^32
             t = t >= p ? t - p : t;
-            my[k] = recvT[(uint64_t)k * ldT + t];
+            const slot_t *row = recvT + (uint64_t)kc * ldT;
+            if (t + 3u < p) {
+                __builtin_memcpy(&word, row + t, 4);
+            } else {                                               // the ranks wrap inside these four (one lane per slot)
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    uint32_t tc = t + c;
+                    tc = tc >= p ? tc - p : tc;
+                    word |= (uint32_t)(uint8_t)row[tc] << (8 * c);
+                }
+            }
         }
+        got[it] = word;
+    }
+#pragma unroll
+    for (int it = 0; it < kLoads; ++it) {
+        const uint32_t k = it * kSlotsPerLoad + kk;
+        if (k < (uint32_t)Q) *reinterpret_cast<uint32_t *>(tile + k * kRS + j4) = got[it];
     }
     __syncthreads();
-    const uint64_t rows = ((uint64_t)p - first) < (uint64_t)kBlock ? ((uint64_t)p - first) : (uint64_t)kBlock;
-    tile_to_rows<Q>(tile, (uint32_t)rows, send_out + first * Q);
-    if (rowsB) byte_rows_from_tile<Q>(tile, (uint32_t)rows, rowsB + first * kRS);
+    const uint32_t rows = ((uint64_t)p - first) < (uint64_t)G ? (uint32_t)((uint64_t)p - first) : (uint32_t)G;
+    const uint32_t n = rows * Q;                                   // entries of this group
+    int32_t *dst = send_out + first * Q;
+    const bool vec = (reinterpret_cast<uintptr_t>(dst) & 15u) == 0;
+#pragma unroll
+    for (int it = 0; it < kStores; ++it) {
+        const uint32_t e = (uint32_t)it * 4u * kLookupLanes + lane * 4u;
+        if (e < n) {
+            uint32_t R = e / Q, k = e - R * Q;                     // divisions by a constant
+            int32_t v[4];
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                const uint32_t Rc = R < (uint32_t)G ? R : (uint32_t)G - 1u;   // past the group's end: read in bounds, not stored
+                v[c] = tile[k * kRS + Rc];
+                ++k;
+                const bool wrap = k == (uint32_t)Q;
+                k = wrap ? 0u : k;
+                R += wrap ? 1u : 0u;
+            }
+            if (vec && e + 4u <= n) {
+                const v4i pack = {v[0], v[1], v[2], v[3]};
+                __builtin_nontemporal_store(pack, reinterpret_cast<v4i *>(dst + e));
+            } else {
+#pragma unroll
+                for (int c = 0; c < 4; ++c)
+                    if (e + c < n) dst[e + c] = v[c];
+            }
+        }
+    }
+    if (rowsB) {
+        // the same rows as bytes for the expansion that follows: T[k] = entry[k] - k, the first three once more
+        constexpr int kRSB = byte_row_stride(Q);
+        constexpr uint32_t kW4 = kRSB / 4;
+        uint32_t *out4 = reinterpret_cast<uint32_t *>(rowsB + first * kRSB);
+        for (uint32_t w = lane; w < rows * kW4; w += kLookupLanes) {
+            const uint32_t row = w / kW4, pos0 = 4u * (w - row * kW4);
+            uint32_t packed = 0;
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                const uint32_t pos = pos0 + c;
+                const bool slot_ok = pos < (uint32_t)(Q + 3);
+                const uint32_t slot = pos < (uint32_t)Q ? pos : (slot_ok ? pos - Q : 0u);
+                const int32_t t = slot_ok && slot < (uint32_t)Q ? (int32_t)tile[slot * kRS + row] - (int32_t)slot : 0;
+                packed |= ((uint32_t)t & 0xffu) << (8 * c);
+            }
+            out4[w] = packed;
+        }
+    }
 }
 
 // K1b: send rows of ranks [r0, r1) with no neighbour rows at hand (Alg. 5): entry i is entry i of the

@@ -274,8 +274,9 @@ int launch_sched(const SkipTab &tab, uint32_t root, uint32_t r0, uint32_t r1, in
     }
     if (send_out) {
         if (full) {
-            launch(kSendLookup, k_send_lookup<Q>, dim3(blocks), dim3(kBlock), st, tab, (const slot_t *)recvT, ldT,
-                   send_out, sendB);
+            constexpr int G = Q >= kLookupBigMinQ ? kLookupBigG : kLookupSmallG;
+            launch(kSendLookup, k_send_lookup<Q, G>, dim3((unsigned)((count + G - 1) / G)), dim3(kLookupLanes), st, tab,
+                   (const slot_t *)recvT, ldT, send_out, sendB);
         } else if (dtab) {
             if (!recv_out)                      // no receive rows asked for: the table has not been filled yet
                 launch(kDigits, k_digits<Q>, dim3((unsigned)(((uint64_t)tab.s[Q] + kBlock - 1) / kBlock)), dim3(kBlock),
