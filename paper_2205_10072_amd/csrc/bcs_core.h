@@ -294,7 +294,10 @@ BCS_HD uint32_t window_blocks(const Pol &pol, uint32_t d_lo, uint32_t d_hi) {
     const uint32_t run = below & ~127u;                        // levels 7..k-1
     const int passed = __builtin_popcount(pol.odd_mask() & run);
     const int row = k > kLowLevels ? passed : 25 + k;
-    const uint32_t small = pol.lowtab()[row * 128 + (int)(low & 127u)];
+    // the table serves tails whose highest clear digit lies below level 7; where the table sits in global memory
+    // (every lane its own shape) the read is skipped when no lane of the wave has such a tail
+    uint32_t small = 0;
+    if (Pol::kScalarSkips || BCS_WAVE_ANY((clear >> kLowLevels) == 0u)) small = pol.lowtab()[row * 128 + (int)(low & 127u)];
     const uint32_t suf = (clear >> kLowLevels) ? tail : small;
     return diff ? (node | pre | suf) : 0u;
 }

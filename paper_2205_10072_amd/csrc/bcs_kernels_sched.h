@@ -363,6 +363,7 @@ __global__ __launch_bounds__(kBatchBlock) void k_batch(int64_t count, const int3
         const int other = __shfl_xor(qmax, off, 64);
         qmax = other > qmax ? other : qmax;
     }
+    qmax = __builtin_amdgcn_readfirstlane(qmax);   // the same in every lane: a scalar, so the loops it bounds are scalar loops
     PerLane pol;
     pol.pm1 = p - 1u;
     pol.ql = q;
