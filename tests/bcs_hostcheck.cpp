@@ -162,6 +162,26 @@ int hc_recv_row_tab(int32_t p, const uint32_t *dtab, int32_t v, int last, int32_
     return 0;
 }
 
+// full receive rows of the listed virtual ranks, out[i * 32 + k]; perlane != 0: through the per-lane-p path with
+// a wave bound of min(q + 2, 31)
+int hc_recv_rows_list(int32_t p, const int32_t *v, int64_t count, int perlane, int32_t *out) {
+    if (p < 2 || !v || !out) return -1;
+    ready();
+    SkipTab t;
+    fill_skips(p, t);
+    const int q = host_q(p);
+    for (int64_t i = 0; i < count; ++i) {
+        if (v[i] < 0 || v[i] >= p) return -1;
+        if (perlane) {
+            const int wq = q + 2 < 31 ? q + 2 : 31;
+            if (hc_recv_row_perlane(p, v[i], wq - 1, wq, out + i * 32)) return -1;
+        } else {
+            g_row[q](t, (uint32_t)v[i], q - 1, out + i * 32);
+        }
+    }
+    return 0;
+}
+
 // mask of baseblocks of ranks a..b (1 <= a, b < p), uniform-p code path
 uint32_t hc_range_blocks(int32_t p, uint32_t a, uint32_t b) {
     ready();

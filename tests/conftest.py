@@ -13,6 +13,16 @@ GOLDEN = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
 
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs an MI355X (runs the HIP library through its C ABI)")
+    config.addinivalue_line("markers", "slow: CPU test of many minutes; runs only with BCS_RUN_SLOW=1 in the environment")
+
+
+def pytest_collection_modifyitems(config, items):
+    if os.environ.get("BCS_RUN_SLOW") == "1":
+        return
+    skip = pytest.mark.skip(reason="slow: set BCS_RUN_SLOW=1 to run")
+    for item in items:
+        if "slow" in item.keywords:
+            item.add_marker(skip)
 
 
 def load_table(name):

@@ -33,6 +33,7 @@ def load():
         i32p = ctypes.POINTER(ctypes.c_int32)
         L.hc_recv_row.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int, i32p]
         L.hc_recv_row_perlane.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int, ctypes.c_int, i32p]
+        L.hc_recv_rows_list.argtypes = [ctypes.c_int32, i32p, ctypes.c_int64, ctypes.c_int, i32p]
         L.hc_range_blocks.argtypes = [ctypes.c_int32, ctypes.c_uint32, ctypes.c_uint32]
         L.hc_range_blocks.restype = ctypes.c_uint32
         L.hc_recv_rows_all.argtypes = [ctypes.c_int32, i32p]
@@ -83,3 +84,14 @@ def recv_row_tab(p, dtab, v, last):
     assert load().hc_recv_row_tab(p, dtab.ctypes.data_as(ctypes.POINTER(ctypes.c_uint32)), v, last,
                                   out.ctypes.data_as(ctypes.POINTER(ctypes.c_int32))) == 0
     return out
+
+
+def recv_rows_list(p, ranks, perlane=False):
+    """Full receive rows of the listed virtual ranks: array [len(ranks)][q]."""
+    q = (p - 1).bit_length()
+    v = np.ascontiguousarray(ranks, dtype=np.int32)
+    out = np.full((len(v), 32), 12345, dtype=np.int32)
+    i32p = ctypes.POINTER(ctypes.c_int32)
+    assert load().hc_recv_rows_list(p, v.ctypes.data_as(i32p), len(v), 1 if perlane else 0, out.ctypes.data_as(i32p)) == 0
+    assert (out[:, q:] == 12345).all()
+    return out[:, :q]

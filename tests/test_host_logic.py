@@ -142,6 +142,69 @@ def test_lane_code_all_rows_every_p_to_3000(oracle):
         assert np.array_equal(hostcheck.recv_rows_all(p), recv), p
 
 
+@pytest.mark.slow
+def test_lane_code_all_rows_every_p_to_40000(oracle):
+    """The same for every rank of every p up to 40 000 (about eleven minutes on 8 cores)."""
+    for p in range(3001, 40001):
+        recv, _ = oracle.sched_range(p, want_send=False, threads=8)
+        assert np.array_equal(hostcheck.recv_rows_all(p), recv), p
+
+
+def _p_from_bits(q, shape6, low_clear_levels):
+    """p with ceil(log2 p) = q whose top seven bits of p - 1 are 1 and the six bits of shape6 (they fix skips[7]
+    and the odd levels below 7) and whose levels >= 7 in low_clear_levels are odd (level k is odd exactly when bit
+    q-1-k of p - 1 is clear)."""
+    pm1 = (1 << (q - 1)) | (shape6 << (q - 7)) | ((1 << (q - 7)) - 1)
+    for k in low_clear_levels:
+        assert 7 <= k < q
+        pm1 &= ~(1 << (q - 1 - k))
+    return pm1 + 1
+
+
+def test_lane_code_every_table_shape_and_odd_level_pattern(oracle):
+    """Structural check of the closed forms on digit masks.  What they depend on: the shape of the seven lowest
+    levels (64 values of the top bits of p - 1), which levels from 7 up are odd, and, for a window, the digits of
+    its lower end point: the top level k where the end points differ, whether digits 7..k-1 are all set (then the
+    table row `odd levels passed` is read with the seven low digits) and the low digits themselves.  For q from 8 to
+    31, every shape, and odd-level patterns none / all / single / pairs / random: ranks are built from such digit
+    patterns and shifted by skips so that the patterns become window end points of their receive rows; rows from
+    both code paths of the lane code must equal the oracle's."""
+    rng = np.random.default_rng(20221005)
+    total = 0
+    for q in (8, 9, 11, 14, 17, 21, 25, 28, 31):
+        levels = list(range(7, q))
+        patterns = [[], levels]
+        patterns += [[k] for k in levels[::max(1, len(levels) // 4)]]
+        patterns += [sorted(rng.choice(levels, size=min(2, len(levels)), replace=False).tolist()) for _ in range(2)]
+        patterns += [[k for k in levels if rng.random() < 0.5] for _ in range(3)]
+        for pi, pat in enumerate(patterns):
+            shapes = range(64) if pi < 2 else rng.choice(64, size=6, replace=False).tolist()
+            for shape6 in shapes:
+                p = _p_from_bits(q, int(shape6), pat)
+                if p > 2**31 - 1:
+                    continue
+                skips = oracle.skips(p).astype(np.int64)
+                assert len(skips) == q + 1
+                ranks = {0, 1, p - 1}
+                for k in range(7, q + 1):
+                    ones = sum(int(skips[j]) for j in range(7, k))             # digits 7..k-1 all set
+                    for L in rng.integers(0, 128, size=4).tolist() + [0, 127]:
+                        low = sum(int(skips[j]) for j in range(7) if L >> j & 1)
+                        above = sum(int(skips[j]) for j in range(k + 1, q) if rng.random() < 0.5)
+                        y1 = (above + ones + low) % p
+                        for i in (k - 1, k):
+                            if 0 <= i <= q:
+                                ranks.add(int((y1 + skips[i]) % p))
+                                ranks.add(int((y1 + skips[i] - 1) % p))
+                v = np.array(sorted(ranks), dtype=np.int32)
+                want, _, _ = oracle.sched_batch(np.full(len(v), p, np.int32), v, np.zeros(len(v), np.int32),
+                                                want_send=False, threads=8)
+                assert np.array_equal(hostcheck.recv_rows_list(p, v), want[:, :q]), (p, q, shape6, pat)
+                assert np.array_equal(hostcheck.recv_rows_list(p, v, perlane=True), want[:, :q]), (p, q, shape6, pat)
+                total += len(v)
+    assert total > 100000
+
+
 def test_lane_code_rows_from_the_digit_table(oracle):
     """The path of the whole-range kernels: one digit walk per rank into a table, every window's end points read
     from it.  Every rank of every p up to 1200 and of a few larger p."""
