@@ -276,6 +276,24 @@ int bcs_unpack_round(int32_t p, int32_t n, const int32_t *idx, const int64_t *di
                      int32_t *data, const int32_t *packed, int64_t length,
                      int64_t *offsets, void *workspace, size_t workspace_bytes, void *stream);
 
+/* The same with the plans of ALL rounds made ahead, in one launch (Alg. 9 runs its pack and unpack loops once
+ * per round; at the paper's sizes -- p = 1152, a few hundred KB per round -- a round is bound by launch latency,
+ * so the per-round work is cut to one kernel per direction).
+ * bcs_pack_plan_rounds: row j of idx_table (device, rounds x p int32: a table of bcs_allgather_tables, or any
+ * rows of block numbers) is planned into row j of
+ *   offsets_all: device, rounds x (p+1) int64: what bcs_pack_round writes to `offsets` for that round;
+ *   src_all: device, rounds x p int64: where each root's block starts in `data` (elements).
+ * bcs_pack_round_planned / bcs_unpack_round_planned: the payload of one round from its two plan rows
+ * (offsets: p+1 entries, src: p entries); arguments otherwise as bcs_pack_round / bcs_unpack_round.
+ * All three enqueue one kernel and allocate nothing.
+ * BCS_EINVAL: p < 1, n < 1, rounds < 0, a NULL array, plan arrays not 8-byte aligned, negative capacity / length. */
+int bcs_pack_plan_rounds(int32_t p, int32_t n, int64_t rounds, const int32_t *idx_table, const int64_t *displs,
+                         int64_t *offsets_all, int64_t *src_all, void *stream);
+int bcs_pack_round_planned(int32_t p, const int64_t *offsets, const int64_t *src, const int32_t *data,
+                           int32_t *packed, int64_t capacity, void *stream);
+int bcs_unpack_round_planned(int32_t p, const int64_t *offsets, const int64_t *src, int32_t *data,
+                             const int32_t *packed, int64_t length, void *stream);
+
 /* Plans of the two other collectives the paper runs on the same circulant
  * graph; host-side, O(q), all arrays are host memory with room for q entries,
  * the return value is q (or BCS_EINVAL for p < 1, r outside [0, p), NULL).

@@ -30,6 +30,7 @@ SYMBOLS = (
     "bcs_last_hip_error", "bcs_timing_begin", "bcs_timing_end", "bcs_timing_stats", "bcs_kernel_name", "bcs_valu_peak_launch",
     "bcs_allgather_workspace_bytes", "bcs_allgather_tables", "bcs_allgather_tables_ws",
     "bcs_pack_workspace_bytes", "bcs_pack_round", "bcs_unpack_round", "bcs_allgather_plan", "bcs_census_plan",
+    "bcs_pack_plan_rounds", "bcs_pack_round_planned", "bcs_unpack_round_planned",
 )
 KERNEL_COUNT = 15
 VALU_PEAK_OPS_PER_ITER = 32
@@ -95,6 +96,9 @@ def lib():
     L.bcs_pack_workspace_bytes.restype = i64
     L.bcs_pack_round.argtypes = [i32, i32, vp, vp, vp, vp, i64, vp, vp, sz, vp]
     L.bcs_unpack_round.argtypes = [i32, i32, vp, vp, vp, vp, i64, vp, vp, sz, vp]
+    L.bcs_pack_plan_rounds.argtypes = [i32, i32, i64, vp, vp, vp, vp, vp]
+    L.bcs_pack_round_planned.argtypes = [i32, vp, vp, vp, vp, i64, vp]
+    L.bcs_unpack_round_planned.argtypes = [i32, vp, vp, vp, vp, i64, vp]
     _lib = L
     return L
 
@@ -335,6 +339,33 @@ def bcs_unpack_round(n, idx, displs, data, packed, length, offsets, workspace, s
                                   _ptr(packed, max(int(length), 0), "packed"), length,
                                   _dev(offsets, torch.int64, p + 1, "offsets"), wp, wb, _stream(stream)),
            "bcs_unpack_round")
+
+
+def bcs_pack_plan_rounds(n, idx_table, displs, offsets_all, src_all, stream=None):
+    """idx_table int32[rounds][p], displs int64[p+1] -> offsets_all int64[rounds][p+1], src_all int64[rounds][p]."""
+    import torch
+    rounds, p = idx_table.shape
+    _check(lib().bcs_pack_plan_rounds(p, n, rounds, _ptr(idx_table), _dev(displs, torch.int64, p + 1, "displs"),
+                                      _dev(offsets_all, torch.int64, rounds * (p + 1), "offsets_all"),
+                                      _dev(src_all, torch.int64, rounds * p, "src_all"), _stream(stream)),
+           "bcs_pack_plan_rounds")
+
+
+def bcs_pack_round_planned(offsets, src, data, packed, stream=None):
+    """One round from its plan rows: offsets int64[p+1], src int64[p]; packed's numel is the capacity."""
+    import torch
+    p = src.numel()
+    _check(lib().bcs_pack_round_planned(p, _dev(offsets, torch.int64, p + 1, "offsets"), _dev(src, torch.int64),
+                                        _ptr(data), _ptr(packed), packed.numel(), _stream(stream)),
+           "bcs_pack_round_planned")
+
+
+def bcs_unpack_round_planned(offsets, src, data, packed, length, stream=None):
+    import torch
+    p = src.numel()
+    _check(lib().bcs_unpack_round_planned(p, _dev(offsets, torch.int64, p + 1, "offsets"), _dev(src, torch.int64),
+                                          _ptr(data), _ptr(packed, max(int(length), 0), "packed"), length,
+                                          _stream(stream)), "bcs_unpack_round_planned")
 
 
 def _host_plan(fn, what, p, r, arrays):

@@ -212,14 +212,21 @@ __global__ __launch_bounds__(kBlock) void k_pack_plan_local(uint32_t p, uint32_t
     }
 }
 
-// The whole plan in one workgroup, for the few thousand processes of the paper's runs: one launch instead
-// of three (a round is launch-latency bound at those sizes).
+// The whole plan of a round in one workgroup, for the few thousand processes of the paper's runs: one launch
+// instead of three (a round is launch-latency bound at those sizes).  A grid of several workgroups plans as many
+// rounds at once: workgroup b takes row b of an index table (rows of p entries, as bcs_allgather_tables writes
+// them) and fills row b of the offsets (p + 1 entries a row) and of the block positions (p entries a row).
 constexpr uint32_t kPlanOneMaxP = 8 * kPlanRoots;
 
-__global__ __launch_bounds__(kBlock) void k_pack_plan_one(uint32_t p, uint32_t n, const int32_t *__restrict__ idx,
-                                                          const int64_t *__restrict__ displs, PackPlan plan) {
+__global__ __launch_bounds__(kBlock) void k_pack_plan_one(uint32_t p, uint32_t n, const int32_t *__restrict__ idx_rows,
+                                                          const int64_t *__restrict__ displs, PackPlan all) {
     __shared__ int64_t wave_sum[kBlock / 64];
     __shared__ int64_t carry_s;
+    const int32_t *idx = idx_rows + (uint64_t)blockIdx.x * p;
+    PackPlan plan;
+    plan.offsets = all.offsets + (uint64_t)blockIdx.x * ((uint64_t)p + 1u);
+    plan.src = all.src + (uint64_t)blockIdx.x * p;
+    plan.totals = nullptr;
     if (threadIdx.x == 0) carry_s = 0;
     __syncthreads();
     for (uint64_t base = 0; base < p; base += kPlanRoots) {

@@ -891,54 +891,84 @@ int pack_plan(int32_t p, int32_t n, const int32_t *idx, const int64_t *displs, i
 }
 }  // namespace
 
+}  // extern "C"
+
+namespace {
+// the payload kernel of one round: PACK moves blocks into the message, !PACK the message into the blocks
+template <bool PACK>
+int launch_copy(int32_t p, int64_t limit, const int64_t *offsets, const int64_t *src, int32_t *data, int32_t *message,
+                hipStream_t st) {
+    const int aligned = (int)((((uintptr_t)message) & 15u) == 0);
+    if (limit < kCopyShort) {
+        const uint64_t blocks = ((uint64_t)limit + kBlock * 4 - 1) / (kBlock * 4);
+        launch(kPackCopy, k_pack_copy<PACK, 1>, dim3((unsigned)blocks), dim3(kBlock), st, (uint32_t)p, limit, offsets, src,
+               data, message, aligned);
+    } else {
+        const uint64_t chunk = (uint64_t)kCopyIter * kBlock * 4;
+        const uint64_t blocks = ((uint64_t)limit + chunk - 1) / chunk;
+        launch(kPackCopy, k_pack_copy<PACK, kCopyIter>, dim3((unsigned)blocks), dim3(kBlock), st, (uint32_t)p, limit,
+               offsets, src, data, message, aligned);
+    }
+    hipError_t e = hipGetLastError();
+    return e == hipSuccess ? BCS_OK : hip_fail(e);
+}
+inline bool copy_size_ok(int64_t limit) { return ((uint64_t)limit + kBlock * 4 - 1) / (kBlock * 4) <= 0x7fffffffull; }
+}  // namespace
+
+extern "C" {
+
 int bcs_pack_round(int32_t p, int32_t n, const int32_t *idx, const int64_t *displs, const int32_t *data,
                    int32_t *packed, int64_t capacity, int64_t *offsets, void *workspace, size_t workspace_bytes,
                    void *stream) {
     if (!data || capacity < 0 || (!packed && capacity > 0)) return BCS_EINVAL;
-    if (((uint64_t)capacity + kBlock * 4 - 1) / (kBlock * 4) > 0x7fffffffull) return BCS_EINVAL;
+    if (!copy_size_ok(capacity)) return BCS_EINVAL;
     PackPlan plan;
     const int rc = pack_plan(p, n, idx, displs, offsets, workspace, workspace_bytes, (hipStream_t)stream, plan);
     if (rc != BCS_OK || capacity == 0) return rc;
-    const int aligned = (int)((((uintptr_t)packed) & 15u) == 0);
-    if (capacity < kCopyShort) {
-        const uint64_t blocks = ((uint64_t)capacity + kBlock * 4 - 1) / (kBlock * 4);
-        launch(kPackCopy, k_pack_copy<true, 1>, dim3((unsigned)blocks), dim3(kBlock), (hipStream_t)stream, (uint32_t)p,
-               capacity, (const int64_t *)offsets, (const int64_t *)plan.src, const_cast<int32_t *>(data), packed,
-               aligned);
-    } else {
-        const uint64_t chunk = (uint64_t)kCopyIter * kBlock * 4;
-        const uint64_t blocks = ((uint64_t)capacity + chunk - 1) / chunk;
-        launch(kPackCopy, k_pack_copy<true, kCopyIter>, dim3((unsigned)blocks), dim3(kBlock), (hipStream_t)stream,
-               (uint32_t)p, capacity, (const int64_t *)offsets, (const int64_t *)plan.src,
-               const_cast<int32_t *>(data), packed, aligned);
-    }
-    hipError_t e = hipGetLastError();
-    return e == hipSuccess ? BCS_OK : hip_fail(e);
+    return launch_copy<true>(p, capacity, offsets, plan.src, const_cast<int32_t *>(data), packed, (hipStream_t)stream);
 }
 
 int bcs_unpack_round(int32_t p, int32_t n, const int32_t *idx, const int64_t *displs, int32_t *data,
                      const int32_t *packed, int64_t length, int64_t *offsets, void *workspace, size_t workspace_bytes,
                      void *stream) {
     if (!data || length < 0 || (!packed && length > 0)) return BCS_EINVAL;
-    if (((uint64_t)length + kBlock * 4 - 1) / (kBlock * 4) > 0x7fffffffull) return BCS_EINVAL;
+    if (!copy_size_ok(length)) return BCS_EINVAL;
     PackPlan plan;
     const int rc = pack_plan(p, n, idx, displs, offsets, workspace, workspace_bytes, (hipStream_t)stream, plan);
     if (rc != BCS_OK || length == 0) return rc;
-    const int aligned = (int)((((uintptr_t)packed) & 15u) == 0);
-    if (length < kCopyShort) {
-        const uint64_t blocks = ((uint64_t)length + kBlock * 4 - 1) / (kBlock * 4);
-        launch(kPackCopy, k_pack_copy<false, 1>, dim3((unsigned)blocks), dim3(kBlock), (hipStream_t)stream, (uint32_t)p,
-               length, (const int64_t *)offsets, (const int64_t *)plan.src, data, const_cast<int32_t *>(packed),
-               aligned);
-    } else {
-        const uint64_t chunk = (uint64_t)kCopyIter * kBlock * 4;
-        const uint64_t blocks = ((uint64_t)length + chunk - 1) / chunk;
-        launch(kPackCopy, k_pack_copy<false, kCopyIter>, dim3((unsigned)blocks), dim3(kBlock), (hipStream_t)stream,
-               (uint32_t)p, length, (const int64_t *)offsets, (const int64_t *)plan.src, data,
-               const_cast<int32_t *>(packed), aligned);
-    }
+    return launch_copy<false>(p, length, offsets, plan.src, data, const_cast<int32_t *>(packed), (hipStream_t)stream);
+}
+
+int bcs_pack_plan_rounds(int32_t p, int32_t n, int64_t rounds, const int32_t *idx_table, const int64_t *displs,
+                         int64_t *offsets_all, int64_t *src_all, void *stream) {
+    if (p < 1 || n < 1 || rounds < 0 || rounds > 0x7fffffffll || !idx_table || !displs || !offsets_all || !src_all)
+        return BCS_EINVAL;
+    if ((((uintptr_t)offsets_all) | ((uintptr_t)src_all)) & 7u) return BCS_EINVAL;
+    if (rounds == 0) return BCS_OK;
+    PackPlan all;
+    all.offsets = offsets_all;
+    all.src = src_all;
+    all.totals = nullptr;
+    launch(kPackPlan, k_pack_plan_one, dim3((unsigned)rounds), dim3(kBlock), (hipStream_t)stream, (uint32_t)p, (uint32_t)n,
+           idx_table, displs, all);
     hipError_t e = hipGetLastError();
     return e == hipSuccess ? BCS_OK : hip_fail(e);
+}
+
+int bcs_pack_round_planned(int32_t p, const int64_t *offsets, const int64_t *src, const int32_t *data, int32_t *packed,
+                           int64_t capacity, void *stream) {
+    if (p < 1 || !offsets || !src || !data || capacity < 0 || (!packed && capacity > 0)) return BCS_EINVAL;
+    if (!copy_size_ok(capacity)) return BCS_EINVAL;
+    if (capacity == 0) return BCS_OK;
+    return launch_copy<true>(p, capacity, offsets, src, const_cast<int32_t *>(data), packed, (hipStream_t)stream);
+}
+
+int bcs_unpack_round_planned(int32_t p, const int64_t *offsets, const int64_t *src, int32_t *data,
+                             const int32_t *packed, int64_t length, void *stream) {
+    if (p < 1 || !offsets || !src || !data || length < 0 || (!packed && length > 0)) return BCS_EINVAL;
+    if (!copy_size_ok(length)) return BCS_EINVAL;
+    if (length == 0) return BCS_OK;
+    return launch_copy<false>(p, length, offsets, src, data, const_cast<int32_t *>(packed), (hipStream_t)stream);
 }
 
 int bcs_valu_peak_launch(uint32_t blocks, uint32_t iters, uint32_t *sink, void *stream) {

@@ -734,6 +734,61 @@ def test_pack_and_unpack_one_round(bcs, oracle):
             assert np.array_equal(d_off.cpu().numpy(), ooff)
 
 
+def test_pack_plans_of_all_rounds_and_planned_rounds(bcs, oracle):
+    """Alg. 9's pack and unpack loops with the plans of all rounds made in one launch: every row of the plan and
+    every round's message against the oracle's pack loop, the unpacked buffers against its unpack loop.  The last
+    case has the paper's own shape (p = 1152, m = 10^8 elements, n = 1658 blocks from its block-size rule)."""
+    from paper_2205_10072_amd import synth
+    rng = np.random.default_rng(1152)
+    for p, n, m, r in [(1, 3, 10, 0), (5, 2, 40, 3), (37, 6, 5000, 11), (1000, 9, 300000, 999), (9001, 4, 90000, 77),
+                       (1152, 1658, 100000000, 0)]:
+        print("plan rounds: p=%d n=%d m=%d" % (p, n, m), flush=True)
+        sizes, displs = synth.irregular_sizes(p, m)
+        R = bcs.bcs_rounds(p, n)
+        pack_t = torch.empty((R, p), dtype=torch.int32, device="cuda")
+        unpack_t = torch.empty((R, p), dtype=torch.int32, device="cuda")
+        bcs.bcs_allgather_tables(p, n, r, pack_t, unpack_t)
+        data = rng.integers(0, 1 << 30, max(1, int(displs[-1]))).astype(np.int32)
+        d_data = torch.from_numpy(data).cuda()
+        d_displs = torch.from_numpy(displs).cuda()
+        offs = torch.full((R, p + 1), -1, dtype=torch.int64, device="cuda")
+        srcs = torch.full((R, p), -1, dtype=torch.int64, device="cuda")
+        bcs.bcs_pack_plan_rounds(n, pack_t, d_displs, offs, srcs)
+        uoffs = torch.full((R, p + 1), -1, dtype=torch.int64, device="cuda")
+        usrcs = torch.full((R, p), -1, dtype=torch.int64, device="cuda")
+        bcs.bcs_pack_plan_rounds(n, unpack_t, d_displs, uoffs, usrcs)
+        torch.cuda.synchronize()
+        h_pack, h_unpack = pack_t.cpu().numpy(), unpack_t.cpu().numpy()
+        h_offs, h_uoffs = offs.cpu().numpy(), uoffs.cpu().numpy()
+        cap = int(h_offs[:, p].max()) + 8
+        d_msg = torch.empty(cap, dtype=torch.int32, device="cuda")
+        blank = np.full_like(data, -5)
+        d_blank = torch.full((len(data),), -5, dtype=torch.int32, device="cuda")
+        rounds = range(R) if R <= 300 else sorted(set(range(0, R, 7)) | {0, 1, R - 2, R - 1})
+        for j in range(R):
+            # the plan rows of every round against the oracle's pack loop (it also gives the offsets)
+            if j in rounds or p <= 1152:
+                omsg, ooff = oracle.pack_round(n, h_pack[j], displs, data)
+                assert np.array_equal(h_offs[j], ooff), (p, n, j)
+            if j not in rounds:
+                continue
+            d_msg.fill_(-99)
+            bcs.bcs_pack_round_planned(offs[j], srcs[j], d_data, d_msg)
+            torch.cuda.synchronize()
+            got = d_msg.cpu().numpy()
+            assert np.array_equal(got[:len(omsg)], omsg) and (got[len(omsg):] == -99).all(), (p, n, j)
+            # what this process receives in round j has the lengths of its unpack row: take the data's own blocks
+            umsg, uoff = oracle.pack_round(n, h_unpack[j], displs, data)
+            assert np.array_equal(h_uoffs[j], uoff), (p, n, j)
+            oracle.unpack_round(n, h_unpack[j], displs, blank, umsg)
+            d_umsg = torch.from_numpy(umsg).cuda() if len(umsg) else torch.empty(0, dtype=torch.int32, device="cuda")
+            bcs.bcs_unpack_round_planned(uoffs[j], usrcs[j], d_blank, d_umsg, len(umsg))
+        torch.cuda.synchronize()
+        assert np.array_equal(d_blank.cpu().numpy(), blank), (p, n)
+        del pack_t, unpack_t, d_data, d_blank, offs, srcs, uoffs, usrcs, d_msg
+        torch.cuda.empty_cache()
+
+
 def test_allgather_tables_and_messages_beyond_32_bit_sizes(bcs, oracle):
     """Index tables of 2 x 4.4 G entries and a packed message of 4.1 G elements: the 64-bit paths, checked on the
     device against the defining index arithmetic (Alg. 9; Alg. 6 for the round shift) written with tensor operations."""

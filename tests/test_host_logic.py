@@ -67,6 +67,17 @@ def test_host_helpers_and_argument_checks(oracle):
     for p, n, r in [(0, 3, 0), (5, 0, 0), (5, 3, 5), (5, 3, -1)]:
         assert L.bcs_allgather_tables(p, n, r, fake, fake, None) == bcs.EINVAL
     assert L.bcs_allgather_tables(5, 3, 0, None, None, None) == bcs.EINVAL
+    assert L.bcs_pack_plan_rounds(0, 3, 4, fake, fake, fake, fake, None) == bcs.EINVAL
+    assert L.bcs_pack_plan_rounds(5, 0, 4, fake, fake, fake, fake, None) == bcs.EINVAL
+    assert L.bcs_pack_plan_rounds(5, 3, -1, fake, fake, fake, fake, None) == bcs.EINVAL
+    assert L.bcs_pack_plan_rounds(5, 3, 4, fake, fake, None, fake, None) == bcs.EINVAL
+    assert L.bcs_pack_plan_rounds(5, 3, 4, fake, fake, ctypes.c_void_p(260), fake, None) == bcs.EINVAL   # misaligned
+    assert L.bcs_pack_plan_rounds(5, 3, 0, fake, fake, fake, fake, None) == bcs.OK
+    assert L.bcs_pack_round_planned(5, fake, fake, fake, None, 8, None) == bcs.EINVAL
+    assert L.bcs_pack_round_planned(5, fake, None, fake, fake, 8, None) == bcs.EINVAL
+    assert L.bcs_pack_round_planned(5, fake, fake, fake, fake, 0, None) == bcs.OK
+    assert L.bcs_unpack_round_planned(5, fake, fake, fake, fake, -1, None) == bcs.EINVAL
+    assert L.bcs_unpack_round_planned(5, fake, fake, fake, None, 0, None) == bcs.OK
     # p = 1 and empty ranges succeed without touching the device
     assert L.bcs_sched(1, 0, 1, fake, fake, None) == bcs.OK
     assert L.bcs_sched(9, 4, 4, fake, fake, None) == bcs.OK
