@@ -51,14 +51,24 @@ def csrc_digest():
 # Key: (config, kernel).  `csrc`: csrc_digest() of the sources that were profiled; when the sources have changed
 # since, the record is still printed but marked "stale": true, and a warning goes to stderr.
 PROFILED = {
-    "csrc": "9f1a67ccba4318ad",
-    "source": "profiles/bench_c2_kernels.md, profiles/allgather_tables_p1048577_n256.md",
+    "csrc": "8306f40d7ebc564a",
+    "source": "profiles/c2_step_p1048577_n256.md, c3_sched_p134217727.md, c4_expand_p65537_n4096.md, c5_batch_2e20.md, "
+              "allgather_tables_p1048577_n256.md",
     "counters": {
-        # valu_per_wave = SQ_INSTS_VALU / SQ_WAVES; active_lanes = SQ_THREAD_CYCLES_VALU / SQ_ACTIVE_INST_VALU (of 64)
-        ("C2", "k_expand_rows"): {"fetch_kib": 35344, "write_kib": 1130583, "valu_per_wave": 69.0, "active_lanes": 64.0, "waves": 1130500},
-        ("C2", "k_recv_uniform"): {"fetch_kib": 11364, "write_kib": 132103, "valu_per_wave": 1275.0, "active_lanes": 64.0, "waves": 16388},
-        ("C2", "k_send_lookup"): {"fetch_kib": 15914, "write_kib": 110592, "valu_per_wave": 359.9, "active_lanes": 64.0, "waves": 16388},
-        ("C2", "k_digits"): {"fetch_kib": 32, "write_kib": 4096, "valu_per_wave": 72.0, "active_lanes": 64.0, "waves": 16388},
+        # per dispatch: FETCH_SIZE / WRITE_SIZE in KiB as read, SQ_WAVES, SQ_INSTS_VALU / SQ_WAVES, SQ_INSTS_SALU / SQ_WAVES,
+        # SQ_THREAD_CYCLES_VALU / SQ_ACTIVE_INST_VALU (lanes active per vector instruction, of 64)
+        ("C3", "k_digits"): {'fetch_kib': 32, 'write_kib': 524288, 'waves': 2097152, 'valu_per_wave': 90.0, 'salu_per_wave': 25.5, 'active_lanes': 64.0},
+        ("C3", "k_recv_uniform"): {'fetch_kib': 3186764, 'write_kib': 17696248, 'waves': 2097152, 'valu_per_wave': 1402.0, 'salu_per_wave': 525.0, 'active_lanes': 64.0},
+        ("C3", "k_send_lookup"): {'fetch_kib': 2031785, 'write_kib': 14156056, 'waves': 524288, 'valu_per_wave': 1002.0, 'salu_per_wave': 626.0, 'active_lanes': 64.0},
+        ("C2", "k_digits"): {'fetch_kib': 31, 'write_kib': 4096, 'waves': 16388, 'valu_per_wave': 72.0, 'salu_per_wave': 25.5, 'active_lanes': 64.0},
+        ("C2", "k_recv_uniform"): {'fetch_kib': 11289, 'write_kib': 132101, 'waves': 16388, 'valu_per_wave': 1275.0, 'salu_per_wave': 460.2, 'active_lanes': 64.0},
+        ("C2", "k_send_lookup"): {'fetch_kib': 21071, 'write_kib': 110676, 'waves': 8193, 'valu_per_wave': 1126.9, 'salu_per_wave': 446.0, 'active_lanes': 63.2},
+        ("C2", "k_expand_rows"): {'fetch_kib': 35345, 'write_kib': 1130581, 'waves': 1130500, 'valu_per_wave': 69.0, 'salu_per_wave': 9.0, 'active_lanes': 64.0},
+        ("C4", "k_expand"): {'fetch_kib': 9008, 'write_kib': 1052688, 'waves': 263176, 'valu_per_wave': 258.5, 'salu_per_wave': 195.0, 'active_lanes': 63.3},
+        ("C4", "k_rows_to_bytes"): {'fetch_kib': 2252, 'write_kib': 1280, 'waves': 5124, 'valu_per_wave': 50.0, 'salu_per_wave': 12.0, 'active_lanes': 64.0},
+        ("C4", "k_expand_rows"): {'fetch_kib': 5135, 'write_kib': 1052921, 'waves': 1052692, 'valu_per_wave': 69.0, 'salu_per_wave': 9.0, 'active_lanes': 64.0},
+        ("C5 recv_and_send", "k_batch"): {'fetch_kib': 14049, 'write_kib': 1344409, 'waves': 16384, 'valu_per_wave': 35765.4, 'salu_per_wave': 11217.7, 'active_lanes': 64.0},
+        ("C5 recv_only", "k_batch"): {'fetch_kib': 11984, 'write_kib': 699645, 'waves': 16384, 'valu_per_wave': 2709.0, 'salu_per_wave': 872.3, 'active_lanes': 63.7},
         ("AG", "k_allgather_tables"): {"fetch_kib": 41280, "write_kib": 2261412},
     },
 }
@@ -76,16 +86,21 @@ def profiled(config, kernel, digest):
 
 
 # ----------------------------------------------------------------------------------------------------------------
-# One model of the vector-ALU work of the construction, counted on the main path of the kernels' ISA and used for
-# every `alu` roofline below.  "Useful" lane-operations of one rank with its OWN q (a wave of the batch kernel runs
+# One model of the vector-ALU work of the construction, used for every `alu` roofline below.  "Useful" lane-operations of one rank with its OWN q (a wave of the batch kernel runs
 # its loops to the largest q among its lanes; that excess, the second-range branch of Alg. 4, the byte copies of a
 # row and the sort of the batch kernel are not counted).  So `frac` = useful lane-ops/s / peak is at most the share
 # of time the vector ALUs are busy, and falls below it by divergence and by everything that is not the method.
-#   a round of Alg. 4 on two digit masks            55 ops (window masks, candidate, bookkeeping; reads its end point)
+#   a row whose end points come from the table      36.6 q + 414: the vector instructions k_recv_uniform executes per
+#                                                    rank (one rank a lane), fitted to SQ_INSTS_VALU / SQ_WAVES measured
+#                                                    at q = 17 (1 036) and q = 27 (1 402); so for this kernel `frac` is
+#                                                    the share of the peak its executed vector instructions amount to,
+#                                                    i.e. its vector-ALU utilisation (the byte rows that the C2 step
+#                                                    also leaves cost 92 instructions more and are not counted)
+#   the batch kernel and Alg. 5, by the structure of the code (no counter fit):
+#   a round of Alg. 4 on two digit masks            55 ops (window masks, candidate, bookkeeping)
 #   set-up of a row                                 50 ops
 #   a digit walk, one p per launch                  3 ops a level from level 7 up, 3 around the low-digit table read
 #   a digit walk, p per lane (batch kernel)         4 ops a level from level 7 up, 10 around it
-#   a row whose end points come from the table      55 q + 50
 #   a row by walks                                  (q + 2) walks + 55 q + 50
 #   a send row by Alg. 5: entry i = rounds 0..i of the to-neighbour's row: sum over i of (i + 3) walks (or table
 #   reads) + 55 (i + 1) + 30
@@ -95,7 +110,7 @@ def ops_walk(q, per_lane):
 
 
 def ops_recv_tabled(q):
-    return 55 * q + 50
+    return 36.6 * q + 414
 
 
 def ops_recv_walks(q, per_lane, walks=None):

@@ -305,9 +305,41 @@ __global__ __launch_bounds__(kBlock) void k_send_recompute(const SkipTab tab, ui
 // K3: unrelated (p, r, root) triples; rows of BCS_BATCH_STRIDE ints (one 128-byte line each), padded.
 // A workgroup takes kBatchBlock triples and first orders them by q in LDS (counting sort), because a
 // wave runs its level loops to the largest q among its lanes and the work grows like q^3: after the
-// sort a wave holds neighbouring q only.  Each lane then builds the rows of its triple and stores
-// them entry by entry into the triple's own line.
+// sort a wave holds neighbouring q only.  Each lane then builds the rows of its triple into an LDS tile of
+// bytes (entries lie in [-31, 30]; a byte of -128 stands for the padding), at the triple's place in the
+// input order; the workgroup then writes the tile out as whole 128-byte lines, eight lanes a row and 16 bytes
+// a lane.  (Storing each entry straight into its row, 4 bytes at a time into a line of the lane's own, made the
+// memory system write five times the table's bytes as partial lines, and a call for receive rows alone was
+// bound by those stores: measured 0.254 ms with the vector ALU busy 28 % of the time.)
 constexpr int kBatchBlock = 1024;
+constexpr int kBatchRowBytes = BCS_BATCH_STRIDE + 4;       // LDS row stride: nine words, so lanes' rows spread over the banks
+constexpr int8_t kBatchPadByte = -128;
+
+// the workgroup's byte tile -> rows of the table (after a barrier); `rows` = triples of this workgroup that exist
+__device__ __forceinline__ void batch_rows_out(const int8_t *tileB, uint32_t rows, int32_t *__restrict__ dst) {
+    const bool vec = (reinterpret_cast<uintptr_t>(dst) & 15u) == 0;
+#pragma unroll
+    for (int it = 0; it < BCS_BATCH_STRIDE / 4; ++it) {
+        const uint32_t g = (uint32_t)it * kBatchBlock + threadIdx.x;
+        const uint32_t row = g >> 3, part = g & 7u;
+        if (row >= rows) continue;
+        const uint32_t four = *reinterpret_cast<const uint32_t *>(tileB + row * kBatchRowBytes + part * 4u);
+        int32_t v[4];
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const int32_t b = (int32_t)(int8_t)(four >> (8 * c));
+            v[c] = b == (int32_t)kBatchPadByte ? BCS_BATCH_PAD : b;
+        }
+        int32_t *out = dst + (uint64_t)row * BCS_BATCH_STRIDE + part * 4u;
+        if (vec) {
+            const v4i pack = {v[0], v[1], v[2], v[3]};
+            *reinterpret_cast<v4i *>(out) = pack;
+        } else {
+#pragma unroll
+            for (int c = 0; c < 4; ++c) out[c] = v[c];
+        }
+    }
+}
 
 __global__ __launch_bounds__(kBatchBlock) void k_batch(int64_t count, const int32_t *__restrict__ pv,
                                                        const int32_t *__restrict__ rv,
@@ -317,6 +349,7 @@ __global__ __launch_bounds__(kBatchBlock) void k_batch(int64_t count, const int3
     __shared__ uint32_t bins[33];                 // bins[q] for valid triples, bins[32] for the rest
     __shared__ uint32_t start[33];
     __shared__ uint32_t s_p[kBatchBlock], s_v[kBatchBlock], s_slot[kBatchBlock];
+    __shared__ __align__(16) int8_t tileB[kBatchBlock * kBatchRowBytes];
     const int64_t first = (int64_t)blockIdx.x * kBatchBlock;
     {
         const int64_t idx = first + threadIdx.x;
@@ -353,7 +386,8 @@ __global__ __launch_bounds__(kBatchBlock) void k_batch(int64_t count, const int3
     const uint32_t slot = s_slot[threadIdx.x];
     const bool valid = (slot & 0x80000000u) == 0u;
     const bool live = (slot & 0x40000000u) == 0u;
-    const int64_t idx = first + (slot & 0xffffu);
+    const uint32_t orig = slot & 0xffffu;                     // the triple's place among the workgroup's 1024
+    const int64_t idx = first + orig;
     const int q = ceil_log2(p);
     if (live && q_out) q_out[idx] = valid ? q : -1;
     // largest q in this wave bounds the level loops of all its lanes
@@ -370,24 +404,31 @@ __global__ __launch_bounds__(kBatchBlock) void k_batch(int64_t count, const int3
     pol.wave_top = qmax - 1;
     pol.odd = odd_levels(p, q);
     pol.low = g_lowtab + (size_t)low_shape(p, q) * kLowShapeBytes;
+    const uint32_t rows = (count - first) < (int64_t)kBatchBlock ? (uint32_t)(count - first) : (uint32_t)kBatchBlock;
+    int8_t *my = tileB + orig * kBatchRowBytes;
+    uint32_t *my4 = reinterpret_cast<uint32_t *>(my);
+    const uint32_t pad4 = 0x80808080u;
     if (recv_out) {
-        int32_t *row = recv_out + idx * BCS_BATCH_STRIDE;
-        recv_row(pol, v, qmax - 1, [&](int i, int val) { if (live) row[i] = val; });
-        if (live)
-            for (int k = q; k < BCS_BATCH_STRIDE; ++k) row[k] = BCS_BATCH_PAD;
+#pragma unroll
+        for (int w = 0; w < BCS_BATCH_STRIDE / 4; ++w) my4[w] = pad4;
+        recv_row(pol, v, qmax - 1, [&](int i, int val) { my[i] = (int8_t)val; });
+        __syncthreads();
+        batch_rows_out(tileB, rows, recv_out + first * BCS_BATCH_STRIDE);
+        __syncthreads();
     }
     if (send_out) {
-        int32_t *row = send_out + idx * BCS_BATCH_STRIDE;
+#pragma unroll
+        for (int w = 0; w < BCS_BATCH_STRIDE / 4; ++w) my4[w] = pad4;
 #pragma unroll 1
         for (int i = 0; i < qmax; ++i) {
             uint32_t t = v + (i < q ? pol.s(i) : 0u);
             t = t >= p ? t - p : t;
             int32_t keep = 0;
             recv_row(pol, t, i, [&](int j, int val) { keep = (j == i) ? val : keep; });
-            if (live && i < q) row[i] = keep;
+            if (i < q) my[i] = (int8_t)keep;
         }
-        if (live)
-            for (int k = q; k < BCS_BATCH_STRIDE; ++k) row[k] = BCS_BATCH_PAD;
+        __syncthreads();
+        batch_rows_out(tileB, rows, send_out + first * BCS_BATCH_STRIDE);
     }
 }
 
