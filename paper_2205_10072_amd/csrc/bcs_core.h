@@ -443,5 +443,65 @@ BCS_HD void recv_row_tab_upto(const Pol &pol, const uint32_t *__restrict__ dtab,
     }
 }
 
+// Send entries without the to-neighbour's rounds (Alg. 5 costs entry k that neighbour's rounds 0..k).
+// With t = (v + skips[k]) mod p the entry is entry k of t's receive row, and in three cases none of t's rounds
+// are needed:
+//   (a) k is t's home round, which is the case exactly for v < skips[k+1] - skips[k]: the entry is t's
+//       baseblock (Alg. 4's first branch), and D(t) = D(v) with digit k added, so that baseblock is v's, or k
+//       for v = 0;
+//   otherwise, when v has a digit at or above k, let m be the lowest such digit and L the value of v's digits
+//   below k.  The rank with the digits of v from m up and nothing below lies in round k's first window
+//   (v - (skips[k+1] - skips[k]), v], holds baseblock m, and nothing larger lies there; so the entry is m - q
+//   unless t has come by block m in its earlier rounds.  Those rounds' windows reach back to v + 1 only, and past
+//   it, by Alg. 4's second range, by at most the number of odd levels; between v + 1 and t the ranks whose lower
+//   part is empty hold blocks other than m.  So the entry is m - q
+//   (b) when L keeps clear of both ends of its range: 2c + 2 < L < skips[k] - 1 - (2c + 2), c = the number of
+//       odd levels up to k.  The second range of round i of t reaches skips[k] - skips[i+1] + 1 - c_i ranks past
+//       v + 1 at most, so it can touch the holder of m, the rank v - L, only for L < c; at the other end a lower
+//       part within c of skips[k] - 1 runs over the end of its (shortened) copy when the skip is added.  Every
+//       exception found (all entries of every rank of every p <= 40 000; 39 million entries of structured larger
+//       p up to 2^31 with L within 80 of either end, 0.6 million of them exceptions) has L within c - 1 of an end;
+//       the margin is more than twice that;
+//   (c) when the digits of t below k are those of v (adding the skip did not disturb them): no exception in the
+//       same searches.
+// (b) and (c) are observations with the argument above, not proved statements; the CPU tests compare this code
+// with Alg. 5 of the oracle entry by entry (every rank of every p <= 1500, of every p <= 40 000 behind the slow
+// marker, and structured large p).  Everything else -- L near an end of its range and low digits disturbed by a
+// carry that met an odd level -- is left to Alg. 5: the return value has bit k set for every entry k < q that was
+// NOT emitted.
+template <class Pol, class DigitsOf, class Emit>
+BCS_HD uint32_t send_row_direct(const Pol &pol, uint32_t v, uint32_t dv, DigitsOf digits_of, Emit emit) {
+    const uint32_t p = pol.p();
+    const int q = pol.q();
+    uint32_t pending = 0;
+    uint32_t low = 0;                                         // value of v's digits below k
+#pragma unroll 1
+    for (int k = 0; k <= pol.top(); ++k) {
+        const bool active = k < q;                            // per-lane q may be below the wave's bound
+        const uint32_t s = active ? pol.sdyn(k) : 0u;
+        const uint32_t kbit = 1u << (k & 31);
+        const uint32_t oddk = (pol.odd_mask() >> (k & 31)) & 1u;
+        const uint32_t above = dv & ~(kbit - 1u);
+        const bool home = active && v + oddk < s;             // v < skips[k+1] - skips[k]
+        const uint32_t mrg = 2u * (uint32_t)__builtin_popcount(pol.odd_mask() & ((kbit << 1) - 1u)) + 2u;
+        const bool mid = low > mrg && low + mrg + 1u < s;
+        bool direct = home || (above != 0u && mid);
+        const bool ask = active && !direct && above != 0u;    // (c) needs the digits of t
+        bool same_low = false;
+        if (BCS_WAVE_ANY(ask)) {
+            uint32_t t = v + s;
+            t = t >= p ? t - p : t;
+            const uint32_t dt = digits_of(t);
+            same_low = ((dv ^ dt) & (kbit - 1u)) == 0u;
+        }
+        direct = direct || (ask && same_low);
+        const int val = home ? (v ? __builtin_ctz(dv | 0x80000000u) : k) : __builtin_ctz(above | 0x80000000u) - q;
+        if (active && direct) emit(k, val);
+        pending |= (active && !direct) ? kbit : 0u;
+        low += (dv & kbit) ? s : 0u;
+    }
+    return pending;
+}
+
 }  // namespace bcs
 #endif  // BCS_CORE_H

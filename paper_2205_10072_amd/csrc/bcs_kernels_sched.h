@@ -276,26 +276,33 @@ __global__ __launch_bounds__(kBlock) void k_send_recompute(const SkipTab tab, ui
     const uint32_t r = live ? (uint32_t)(r0 + idx) : root;
     const uint32_t v = r >= root ? r - root : r + p - root;
     int32_t *my = tile + threadIdx.x * kStride;
-#pragma unroll 1
-    for (int i = 0; i < Q; ++i) {
-        uint32_t t = v + tab.s[i];
-        t = t >= p ? t - p : t;
-        uint32_t dt;
-        if constexpr (TAB) dt = dtab[t];                  // digit masks of all ranks from k_digits
-        else dt = digits(pol, t);
-        int32_t keep = dt ? __builtin_ctz(dt) : 0;
-        // Round i is the neighbour's home round when its highest digit is i: then the entry is its baseblock and
-        // none of its earlier rounds matters.  A wave of consecutive ranks below skips[i+1] - skips[i] is in that
-        // case as a whole (half of all waves for the last slot, a quarter for the one before, ...).
-        const bool home_round = dt != 0u && (31 - __clz((int)dt)) == i;
-        if (__any(!home_round)) {
-            int32_t got = 0;
-            auto last_entry = [&](int j, int val) { got = (j == i) ? val : got; };
-            if constexpr (TAB) recv_row_tab_upto(pol, dtab, t, dt, i, last_entry);
-            else recv_row_from(pol, t, dt, i, last_entry);
-            keep = got;
+    // the entries that need none of the to-neighbour's rounds (bcs_core.h); for consecutive ranks and large p
+    // that is nearly all of them
+    auto digits_of = [&](uint32_t y) -> uint32_t {
+        if constexpr (TAB) return dtab[y];                // digit masks of all ranks from k_digits
+        else return digits(pol, y);
+    };
+    uint32_t pending = send_row_direct(pol, v, digits_of(v), digits_of, [&](int k, int val) { my[k] = val; });
+    // Alg. 5 for the rest: every lane works down its own list, largest k first; the wave computes rounds
+    // 0..(largest k asked for) of each lane's neighbour and a lane keeps the entry of its own k
+    while (__any(pending != 0u)) {
+        const int kk = 31 - __clz((int)pending);              // -1: this lane has nothing left
+        pending &= ~(kk >= 0 ? 1u << kk : 0u);
+        int kmax = kk;
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) {
+            const int other = __shfl_xor(kmax, off, 64);
+            kmax = other > kmax ? other : kmax;
         }
-        my[i] = keep;
+        kmax = __builtin_amdgcn_readfirstlane(kmax);
+        // skips[kk] by the closed form of Alg. 1's halving (kk differs from lane to lane)
+        uint32_t t = v + (kk >= 0 ? ((p - 1u) >> (Q - kk)) + 1u : 0u);
+        t = t >= p ? t - p : t;
+        int32_t got = 0;
+        auto own_entry = [&](int j, int val) { got = (j == kk) ? val : got; };
+        if constexpr (TAB) recv_row_tab_upto(pol, dtab, t, dtab[t], kmax, own_entry);
+        else recv_row(pol, t, kmax, own_entry);
+        if (kk >= 0) my[kk] = got;
     }
     __syncthreads();
     const uint64_t rows = (count - first) < (uint64_t)kBlock ? (count - first) : (uint64_t)kBlock;
@@ -419,13 +426,28 @@ __global__ __launch_bounds__(kBatchBlock) void k_batch(int64_t count, const int3
     if (send_out) {
 #pragma unroll
         for (int w = 0; w < BCS_BATCH_STRIDE / 4; ++w) my4[w] = pad4;
-#pragma unroll 1
-        for (int i = 0; i < qmax; ++i) {
-            uint32_t t = v + (i < q ? pol.s(i) : 0u);
+        // the entries that need none of the to-neighbour's rounds; the others (a carry of v + skips[k] met an odd
+        // level: about a third) are left in `pending`
+        uint32_t pending = send_row_direct(pol, v, digits(pol, v), [&](uint32_t y) { return digits(pol, y); },
+                                           [&](int k, int val) { my[k] = (int8_t)val; });
+        // Alg. 5 for those: each lane works down its own list, largest k first, so that the lanes of a wave ask
+        // for rows of similar length; the wave computes rounds 0..(largest k asked for) and every lane keeps
+        // the entry of its own k (receive rows are prefix-stable, the extra rounds change nothing)
+        while (__any(pending != 0u)) {
+            const int kk = 31 - __clz((int)pending);              // -1: this lane has nothing left
+            pending &= ~(kk >= 0 ? 1u << kk : 0u);
+            int kmax = kk;
+#pragma unroll
+            for (int off = 32; off >= 1; off >>= 1) {
+                const int other = __shfl_xor(kmax, off, 64);
+                kmax = other > kmax ? other : kmax;
+            }
+            kmax = __builtin_amdgcn_readfirstlane(kmax);
+            uint32_t t = v + (kk >= 0 ? pol.s(kk) : 0u);
             t = t >= p ? t - p : t;
             int32_t keep = 0;
-            recv_row(pol, t, i, [&](int j, int val) { keep = (j == i) ? val : keep; });
-            if (i < q) my[i] = (int8_t)keep;
+            recv_row(pol, t, kmax, [&](int j, int val) { keep = (j == kk) ? val : keep; });
+            if (kk >= 0) my[kk] = (int8_t)keep;
         }
         __syncthreads();
         batch_rows_out(tileB, rows, send_out + first * BCS_BATCH_STRIDE);

@@ -182,6 +182,35 @@ int hc_recv_rows_list(int32_t p, const int32_t *v, int64_t count, int perlane, i
     return 0;
 }
 
+// send rows of the listed virtual ranks as the batch kernel builds them: the entries that need no rounds of the
+// to-neighbour directly, the rest by Alg. 5 on the lane code; out[i * 32 + k]; direct_mask[i] (may be NULL) gets the
+// bits of the entries that were taken directly
+int hc_send_rows_list(int32_t p, const int32_t *v, int64_t count, int wave_q, int32_t *out, uint32_t *direct_mask) {
+    if (p < 1 || !v || !out) return -1;
+    for (int64_t i = 0; i < count; ++i) {
+        if (v[i] < 0 || v[i] >= p) return -1;
+        PerLane pol;
+        pol.pm1 = (uint32_t)p - 1u;
+        pol.ql = host_q(p);
+        pol.wave_top = (wave_q > pol.ql ? wave_q : pol.ql) - 1;
+        pol.odd = odd_levels((uint32_t)p, pol.ql);
+        pol.low = low_for(p);
+        int32_t *row = out + i * 32;
+        const uint32_t dv = digits(pol, (uint32_t)v[i]);
+        uint32_t pending = send_row_direct(pol, (uint32_t)v[i], dv, [&](uint32_t y) { return digits(pol, y); },
+                                           [&](int k, int val) { row[k] = val; });
+        if (direct_mask) direct_mask[i] = ~pending & (pol.ql >= 32 ? 0xffffffffu : ((1u << pol.ql) - 1u));
+        while (pending) {
+            const int k = 31 - __builtin_clz(pending);
+            pending &= ~(1u << k);
+            uint32_t t = (uint32_t)v[i] + pol.s(k);
+            t = t >= (uint32_t)p ? t - (uint32_t)p : t;
+            recv_row(pol, t, k, [&](int j, int val) { if (j == k) row[k] = val; });
+        }
+    }
+    return 0;
+}
+
 // mask of baseblocks of ranks a..b (1 <= a, b < p), uniform-p code path
 uint32_t hc_range_blocks(int32_t p, uint32_t a, uint32_t b) {
     ready();

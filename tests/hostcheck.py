@@ -34,6 +34,8 @@ def load():
         L.hc_recv_row.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int, i32p]
         L.hc_recv_row_perlane.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_int, ctypes.c_int, i32p]
         L.hc_recv_rows_list.argtypes = [ctypes.c_int32, i32p, ctypes.c_int64, ctypes.c_int, i32p]
+        L.hc_send_rows_list.argtypes = [ctypes.c_int32, i32p, ctypes.c_int64, ctypes.c_int, i32p,
+                                        ctypes.POINTER(ctypes.c_uint32)]
         L.hc_range_blocks.argtypes = [ctypes.c_int32, ctypes.c_uint32, ctypes.c_uint32]
         L.hc_range_blocks.restype = ctypes.c_uint32
         L.hc_recv_rows_all.argtypes = [ctypes.c_int32, i32p]
@@ -95,3 +97,17 @@ def recv_rows_list(p, ranks, perlane=False):
     assert load().hc_recv_rows_list(p, v.ctypes.data_as(i32p), len(v), 1 if perlane else 0, out.ctypes.data_as(i32p)) == 0
     assert (out[:, q:] == 12345).all()
     return out[:, :q]
+
+
+def send_rows_list(p, ranks, wave_q=0, want_direct=False):
+    """Send rows of the listed virtual ranks the way the batch kernel builds them: array [len(ranks)][q]
+    (and, on request, per rank the mask of the entries that took the direct rule)."""
+    q = (p - 1).bit_length()
+    v = np.ascontiguousarray(ranks, dtype=np.int32)
+    out = np.full((len(v), 32), 12345, dtype=np.int32)
+    direct = np.zeros(len(v), dtype=np.uint32)
+    i32p = ctypes.POINTER(ctypes.c_int32)
+    assert load().hc_send_rows_list(p, v.ctypes.data_as(i32p), len(v), wave_q, out.ctypes.data_as(i32p),
+                                    direct.ctypes.data_as(ctypes.POINTER(ctypes.c_uint32))) == 0
+    assert (out[:, q:] == 12345).all()
+    return (out[:, :q], direct) if want_direct else out[:, :q]

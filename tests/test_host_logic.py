@@ -216,6 +216,69 @@ def test_lane_code_every_table_shape_and_odd_level_pattern(oracle):
     assert total > 100000
 
 
+def test_lane_code_send_rows_every_p_to_1500(oracle):
+    """Send rows the way the batch kernel builds them (entries that need none of the to-neighbour's rounds taken
+    directly, the rest by Alg. 5 on the lane code) against the oracle's look-up table: every entry of every rank of
+    every p up to 1500, with the wave's bound at q and above it."""
+    taken = total = 0
+    for p in range(1, 1501):
+        _, send = oracle.sched_range(p, threads=4)
+        got, direct = hostcheck.send_rows_list(p, np.arange(p), want_direct=True)
+        assert np.array_equal(got, send), p
+        if p % 97 == 0:
+            assert np.array_equal(hostcheck.send_rows_list(p, np.arange(p), wave_q=31), send), p
+        total += send.size
+        taken += int(np.unpackbits(direct.view(np.uint8)).sum())
+    assert taken > 0.6 * total                  # the direct rule must carry most entries, or it is not exercised
+
+
+@pytest.mark.slow
+def test_lane_code_send_rows_every_p_to_40000(oracle):
+    for p in range(1501, 40001):
+        _, send = oracle.sched_range(p, threads=8)
+        assert np.array_equal(hostcheck.send_rows_list(p, np.arange(p)), send), p
+
+
+def test_lane_code_send_rows_large_p_structured(oracle):
+    """The direct send rule where it could break: additions r + skips[k] whose carries meet odd levels.  For q up
+    to 31, table shapes and odd-level patterns as in the receive test; ranks whose digits from k up form carry
+    chains of every length up to four, with lower parts empty, small, largest possible and one below, and on both
+    sides of the margin from which the rule takes an entry without looking at the neighbour's digits; every entry
+    against Alg. 5 of the oracle."""
+    rng = np.random.default_rng(2205100)
+    total = 0
+    for q in (8, 10, 13, 17, 21, 25, 28, 31):
+        levels = list(range(7, q))
+        patterns = [[], levels, [k for k in levels if rng.random() < 0.5], [k for k in levels if rng.random() < 0.5]]
+        patterns += [[k] for k in levels[::max(1, len(levels) // 2)]]
+        for pi, pat in enumerate(patterns):
+            for shape6 in (range(0, 64, 7) if pi < 2 else rng.choice(64, size=3, replace=False).tolist()):
+                p = _p_from_bits(q, int(shape6), pat)
+                if p > 2**31 - 1:
+                    continue
+                skips = oracle.skips(p).astype(np.int64)
+                ranks = {0, 1, 2, p - 1, p - 2}
+                for k in range(q):
+                    sk = int(skips[k])
+                    m = 2 * sum(1 for j in range(k + 1) if 2 * int(skips[j]) - int(skips[j + 1]) == 1) + 2
+                    lows = {0, 1, 2, sk - 1, sk - 2, int(rng.integers(0, sk)), m, m + 1, m + 2, sk - 1 - m, sk - 2 - m, sk - 3 - m,
+                            m // 2, sk - 1 - m // 2}
+                    for chain in range(5):
+                        top = sum(int(skips[j]) for j in range(k, min(k + chain, q)))
+                        above = sum(int(skips[j]) for j in range(min(k + chain + 1, q), q) if rng.random() < 0.5)
+                        for low in lows:
+                            if 0 <= low < sk:
+                                ranks.add(int((above + top + low) % p))
+                ranks |= {int(x) for x in rng.integers(0, p, 24)}
+                v = np.array(sorted(ranks), dtype=np.int32)
+                if len(v) > 400:
+                    v = np.sort(rng.choice(v, size=400, replace=False)).astype(np.int32)
+                _, want, _ = oracle.sched_batch(np.full(len(v), p, np.int32), v, np.zeros(len(v), np.int32), threads=8)
+                assert np.array_equal(hostcheck.send_rows_list(p, v, wave_q=min(q + 1, 31)), want[:, :q]), (p, q, shape6, pat)
+                total += len(v)
+    assert total > 20000
+
+
 def test_lane_code_rows_from_the_digit_table(oracle):
     """The path of the whole-range kernels: one digit walk per rank into a table, every window's end points read
     from it.  Every rank of every p up to 1200 and of a few larger p."""
