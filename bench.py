@@ -51,24 +51,24 @@ def csrc_digest():
 # Key: (config, kernel).  `csrc`: csrc_digest() of the sources that were profiled; when the sources have changed
 # since, the record is still printed but marked "stale": true, and a warning goes to stderr.
 PROFILED = {
-    "csrc": "8306f40d7ebc564a",
+    "csrc": "aba8a9e3f3518bcf",
     "source": "profiles/c2_step_p1048577_n256.md, c3_sched_p134217727.md, c4_expand_p65537_n4096.md, c5_batch_2e20.md, "
               "allgather_tables_p1048577_n256.md",
     "counters": {
         # per dispatch: FETCH_SIZE / WRITE_SIZE in KiB as read, SQ_WAVES, SQ_INSTS_VALU / SQ_WAVES, SQ_INSTS_SALU / SQ_WAVES,
         # SQ_THREAD_CYCLES_VALU / SQ_ACTIVE_INST_VALU (lanes active per vector instruction, of 64)
-        ("C3", "k_digits"): {'fetch_kib': 32, 'write_kib': 524288, 'waves': 2097152, 'valu_per_wave': 90.0, 'salu_per_wave': 25.5, 'active_lanes': 64.0},
-        ("C3", "k_recv_uniform"): {'fetch_kib': 3186764, 'write_kib': 17696248, 'waves': 2097152, 'valu_per_wave': 1402.0, 'salu_per_wave': 525.0, 'active_lanes': 64.0},
-        ("C3", "k_send_lookup"): {'fetch_kib': 2031785, 'write_kib': 14156056, 'waves': 524288, 'valu_per_wave': 1002.0, 'salu_per_wave': 626.0, 'active_lanes': 64.0},
+        ("C3", "k_digits"): {'fetch_kib': 28, 'write_kib': 524288, 'waves': 2097152, 'valu_per_wave': 90.0, 'salu_per_wave': 25.5, 'active_lanes': 64.0},
+        ("C3", "k_recv_uniform"): {'fetch_kib': 3190049, 'write_kib': 17696065, 'waves': 2097152, 'valu_per_wave': 1402.0, 'salu_per_wave': 525.0, 'active_lanes': 64.0},
+        ("C3", "k_send_lookup"): {'fetch_kib': 2031789, 'write_kib': 14156028, 'waves': 524288, 'valu_per_wave': 1002.0, 'salu_per_wave': 626.0, 'active_lanes': 64.0},
         ("C2", "k_digits"): {'fetch_kib': 31, 'write_kib': 4096, 'waves': 16388, 'valu_per_wave': 72.0, 'salu_per_wave': 25.5, 'active_lanes': 64.0},
-        ("C2", "k_recv_uniform"): {'fetch_kib': 11289, 'write_kib': 132101, 'waves': 16388, 'valu_per_wave': 1275.0, 'salu_per_wave': 460.2, 'active_lanes': 64.0},
-        ("C2", "k_send_lookup"): {'fetch_kib': 21071, 'write_kib': 110676, 'waves': 8193, 'valu_per_wave': 1126.9, 'salu_per_wave': 446.0, 'active_lanes': 63.2},
-        ("C2", "k_expand_rows"): {'fetch_kib': 35345, 'write_kib': 1130581, 'waves': 1130500, 'valu_per_wave': 69.0, 'salu_per_wave': 9.0, 'active_lanes': 64.0},
+        ("C2", "k_recv_uniform"): {'fetch_kib': 11285, 'write_kib': 132100, 'waves': 16388, 'valu_per_wave': 1275.0, 'salu_per_wave': 460.2, 'active_lanes': 64.0},
+        ("C2", "k_send_lookup"): {'fetch_kib': 21066, 'write_kib': 110666, 'waves': 8193, 'valu_per_wave': 1126.9, 'salu_per_wave': 446.0, 'active_lanes': 63.2},
+        ("C2", "k_expand_rows"): {'fetch_kib': 35345, 'write_kib': 1130582, 'waves': 1130500, 'valu_per_wave': 69.0, 'salu_per_wave': 9.0, 'active_lanes': 64.0},
         ("C4", "k_expand"): {'fetch_kib': 9008, 'write_kib': 1052688, 'waves': 263176, 'valu_per_wave': 258.5, 'salu_per_wave': 195.0, 'active_lanes': 63.3},
         ("C4", "k_rows_to_bytes"): {'fetch_kib': 2252, 'write_kib': 1280, 'waves': 5124, 'valu_per_wave': 50.0, 'salu_per_wave': 12.0, 'active_lanes': 64.0},
-        ("C4", "k_expand_rows"): {'fetch_kib': 5135, 'write_kib': 1052921, 'waves': 1052692, 'valu_per_wave': 69.0, 'salu_per_wave': 9.0, 'active_lanes': 64.0},
-        ("C5 recv_and_send", "k_batch"): {'fetch_kib': 14049, 'write_kib': 1344409, 'waves': 16384, 'valu_per_wave': 35765.4, 'salu_per_wave': 11217.7, 'active_lanes': 64.0},
-        ("C5 recv_only", "k_batch"): {'fetch_kib': 11984, 'write_kib': 699645, 'waves': 16384, 'valu_per_wave': 2709.0, 'salu_per_wave': 872.3, 'active_lanes': 63.7},
+        ("C4", "k_expand_rows"): {'fetch_kib': 5135, 'write_kib': 1052904, 'waves': 1052692, 'valu_per_wave': 69.0, 'salu_per_wave': 9.0, 'active_lanes': 64.0},
+        ("C5 recv_and_send", "k_batch"): {'fetch_kib': 8470, 'write_kib': 266240, 'waves': 16384, 'valu_per_wave': 11584.4, 'salu_per_wave': 3662.1, 'active_lanes': 63.8},
+        ("C5 recv_only", "k_batch"): {'fetch_kib': 8364, 'write_kib': 135168, 'waves': 16384, 'valu_per_wave': 2831.3, 'salu_per_wave': 870.0, 'active_lanes': 63.8},
         ("AG", "k_allgather_tables"): {"fetch_kib": 41280, "write_kib": 2261412},
     },
 }
@@ -390,7 +390,17 @@ def run_c5(torch, bcs, steps, warmup, digest):
     for key, step, ops in (("recv_and_send", lambda: bcs.bcs_sched_batch(pp, rr, ro, brecv, bsend, qv), ops_recv + ops_send),
                            ("recv_only", lambda: bcs.bcs_sched_batch(pp, rr, ro, brecv, None, qv), ops_recv)):
         ms, ms_ev, timing = timed_steps(torch, bcs, step, steps, warmup)
-        kernels = kernel_records(timing, steps, {"k_batch": ("alu", ops)}, "C5 " + key, digest)
+        # `frac` of this kernel: the vector instructions it executes (all 64 lanes active: the per-lane-p code is
+        # branch-free in q) against the peak, i.e. its vector-ALU utilisation, from the counter profile of these
+        # sources; when the sources have changed since the profile, the structural model of useful work instead
+        prof = profiled("C5 " + key, "k_batch", digest)
+        executed = None
+        if prof is not None and not prof["stale"]:
+            executed = prof["valu_per_wave"] * prof["waves"] * prof["active_lanes"]
+        kernels = kernel_records(timing, steps, {"k_batch": ("alu", executed if executed else ops)}, "C5 " + key, digest)
+        kernels["k_batch"]["ops_source"] = "counters (executed vector lane-operations)" if executed else "model (useful lane-operations)"
+        kernels["k_batch"]["useful_lane_ops_model"] = ops
+        kernels["k_batch"]["useful_frac_model"] = ops / kernels["k_batch"]["avg_ms"] / 1e6 / INT_VALU_PEAK_GOPS
         out[key] = {"ms_per_step": ms, "ms_per_step_with_kernel_events": ms_ev,
                     "value": count / (ms * 1e-3), "unit": "rank-schedules/s" if key == "recv_and_send" else "receive rows/s",
                     "useful_lane_ops_per_rank": ops / count, "roofline": dominant(kernels), "kernels": kernels}

@@ -465,6 +465,61 @@ def test_irregular_batch(bcs, oracle):
     assert np.array_equal(send.cpu().numpy(), osend)
 
 
+def test_batch_send_rows_where_the_direct_rule_is_at_its_limits(bcs, oracle):
+    """Send rows of the batch kernel (entries taken from the rank's own digits where that is exact, Alg. 5 otherwise)
+    on triples built to sit at the rule's limits: p with chosen odd levels for q up to 31, ranks whose additions
+    r + skips[k] carry through odd levels, with lower parts empty, largest possible and on both sides of the rule's
+    margin; every entry against Alg. 5 of the oracle.  A second call takes the same ranks as a range of one p
+    (the kernel for parts of the ranks uses the same rule)."""
+    from test_host_logic import _p_from_bits
+    rng = np.random.default_rng(310522)
+    ps, rs = [], []
+    for q in (9, 12, 16, 20, 24, 27, 29, 31):
+        levels = list(range(7, q))
+        for pat in ([], levels, [k for k in levels if rng.random() < 0.5], [k for k in levels if rng.random() < 0.3]):
+            p = _p_from_bits(q, int(rng.integers(0, 64)), pat)
+            if p > 2**31 - 1:
+                continue
+            skips = oracle.skips(p).astype(np.int64)
+            for k in range(q):
+                sk = int(skips[k])
+                m = 2 * sum(1 for j in range(k + 1) if 2 * int(skips[j]) - int(skips[j + 1]) == 1) + 2
+                for chain in range(4):
+                    top = sum(int(skips[j]) for j in range(k, min(k + chain, q)))
+                    above = sum(int(skips[j]) for j in range(min(k + chain + 1, q), q) if rng.random() < 0.5)
+                    for low in (0, 1, sk - 1, sk - 2, m, m + 1, sk - 1 - m, sk - 2 - m, int(rng.integers(0, sk))):
+                        if 0 <= low < sk:
+                            ps.append(p)
+                            rs.append((above + top + low) % p)
+    p_arr = np.array(ps, dtype=np.int32)
+    v_arr = np.array(rs, dtype=np.int32)
+    root = (rng.integers(0, 2**31 - 1, len(p_arr)) % p_arr).astype(np.int32)
+    r_arr = ((v_arr.astype(np.int64) + root) % p_arr).astype(np.int32)      # so that the virtual rank is v
+    print("structured batch: %d triples" % len(p_arr), flush=True)
+    orecv, osend, oq = oracle.sched_batch(p_arr, r_arr, root, threads=16)
+    d = [torch.from_numpy(a).cuda() for a in (p_arr, r_arr, root)]
+    recv, send = dev_tables(len(p_arr), 32)
+    qv = torch.empty(len(p_arr), dtype=torch.int32, device="cuda")
+    bcs.bcs_sched_batch(d[0], d[1], d[2], recv, send, qv)
+    torch.cuda.synchronize()
+    assert np.array_equal(qv.cpu().numpy(), oq)
+    assert np.array_equal(recv.cpu().numpy(), orecv)
+    assert np.array_equal(send.cpu().numpy(), osend)
+    # the kernel for a part of the ranks of one p uses the same rule: ranges around sums of skips
+    for q, pat in ((27, list(range(7, 27))), (31, [k for k in range(7, 31) if k % 2]), (21, [9, 14])):
+        p = _p_from_bits(q, int(rng.integers(0, 64)), pat)
+        skips = oracle.skips(p).astype(np.int64)
+        for _ in range(5):
+            pick = rng.random(q) < 0.4
+            centre = int(skips[:q][pick].sum()) % p
+            v0, v1 = max(0, centre - 330), min(p, centre + 310)
+            root = int(rng.integers(0, p - v1 + 1))                 # ranks root + v0 .. root + v1 - 1 play virtual ranks v0 .. v1 - 1
+            r0, r1 = v0 + root, v1 + root
+            _, want = oracle.sched_range(p, root=root, r0=r0, r1=r1, want_recv=False, threads=16)
+            _, got = gpu_sched(bcs, p, root=root, r0=r0, r1=r1, want_recv=False)
+            assert np.array_equal(got, want), (p, root, r0, r1)
+
+
 def test_batch_edge_rows(bcs, oracle):
     """Invalid triples are flagged on the device; a ragged count; single outputs."""
     p = np.array([1, 2, 2, 0, 5, 5, 2**31 - 1, 7, -3, 9], dtype=np.int32)
