@@ -520,6 +520,59 @@ def test_batch_send_rows_where_the_direct_rule_is_at_its_limits(bcs, oracle):
             assert np.array_equal(got, want), (p, root, r0, r1)
 
 
+def test_send_rule_against_the_look_up_for_every_rank_of_large_p(bcs):
+    """Send rows of parts of the ranks (taken from the ranks' own digits where the rule applies, Alg. 5 otherwise)
+    against send rows of all ranks by look-up in the receive table, which is their definition (Alg. 9, second loop):
+    every rank of 40 values of p of 12 to 27 bits, random and with chosen odd levels, each under a random root and cut
+    into two ranges at a random rank.  Then p of 30 and 31 bits, whose tables do not fit: slices of 2^20 ranks
+    against entry k of the receive rows of their to-neighbours.  (The receive rows themselves are compared with the
+    oracle elsewhere in this file.)"""
+    from test_host_logic import _p_from_bits
+    rng = np.random.default_rng(20220510)
+    ps = [(1 << 20) + 1, (1 << 23) + 1, (1 << 24) + 12345, (1 << 26) - 3, (1 << 27) - 1]
+    while len(ps) < 40:
+        q = int(rng.integers(12, 27))
+        if rng.random() < 0.5:
+            ps.append(int(rng.integers(2**(q - 1) + 1, 2**q)))
+        else:
+            pr = rng.choice([0.1, 0.5, 0.9, 1.0])
+            ps.append(_p_from_bits(q, int(rng.integers(0, 64)), [k for k in range(7, q) if rng.random() < pr]))
+    for p in ps:
+        q = bcs.bcs_q(p)
+        full = torch.empty((p, q), dtype=torch.int32, device="cuda")
+        part = torch.full((p, q), 99, dtype=torch.int32, device="cuda")
+        root, cut = int(rng.integers(0, p)), int(rng.integers(1, p))
+        bcs.bcs_sched_rooted(p, root, 0, p, None, full)
+        bcs.bcs_sched_rooted(p, root, 0, cut, None, part[:cut])
+        bcs.bcs_sched_rooted(p, root, cut, p, None, part[cut:])
+        torch.cuda.synchronize()
+        assert torch.equal(full, part), (p, root, cut)
+        del full, part
+    bcs.bcs_release()
+    torch.cuda.empty_cache()
+    W = 1 << 20
+    big = [2**31 - 1, 2**30 + 1, 2**30, _p_from_bits(31, 5, [k for k in range(7, 31) if k % 3]),
+           _p_from_bits(30, 60, list(range(7, 30))), int(rng.integers(2**30 + 1, 2**31 - 1))]
+    for p in big:
+        q = bcs.bcs_q(p)
+        skips = bcs.bcs_skips(p)
+        pick = rng.random(q) < 0.4
+        centres = [int(rng.integers(0, p)), int(sum(s for s, f in zip(skips[:q], pick) if f) % p), 0, p - 1]
+        for c in centres:
+            r0 = max(0, min(c - W // 2, p - W))
+            send = torch.full((W, q), 99, dtype=torch.int32, device="cuda")
+            nb = torch.empty((W, q), dtype=torch.int32, device="cuda")
+            bcs.bcs_sched(p, r0, r0 + W, None, send)
+            for k in range(q):
+                a = (r0 + skips[k]) % p
+                if a + W <= p:
+                    bcs.bcs_sched(p, a, a + W, nb, None)
+                else:
+                    bcs.bcs_sched(p, a, p, nb[:p - a], None)
+                    bcs.bcs_sched(p, 0, a + W - p, nb[p - a:], None)
+                assert torch.equal(send[:, k], nb[:, k]), (p, r0, k)
+
+
 def test_batch_edge_rows(bcs, oracle):
     """Invalid triples are flagged on the device; a ragged count; single outputs."""
     p = np.array([1, 2, 2, 0, 5, 5, 2**31 - 1, 7, -3, 9], dtype=np.int32)
