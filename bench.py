@@ -490,6 +490,48 @@ def bench_allgather_tables(torch, bcs, args):
     return out
 
 
+def bench_partner_tables(torch, bcs, args):
+    """Alg. 7 / Alg. 8: the to- and from-process tables of all p = 2^27-1 processes (q = 27), one kernel each."""
+    p = 2**27 - 1
+    q = bcs.bcs_q(p)
+    to = torch.empty((p, q), dtype=torch.int32, device="cuda")
+    frm = torch.empty((p, q), dtype=torch.int32, device="cuda")
+
+    def step():
+        bcs.bcs_allgather_partners(p, 0, p, to, frm)
+        bcs.bcs_census_partners(p, 0, p, to, frm)
+
+    steps = max(1, min(args.steps, 100))
+    ms_per_step, _, timing = timed_steps(torch, bcs, step, steps, args.warmup)
+    ms, cnt = timing["k_partner_tables"][:2]
+    avg_ms = ms / cnt
+    nbytes = 2 * p * q * 4                                   # per launch: both tables, written once
+    out = {
+        "metric": "partner tables of the regular allgather and the census for all processes, GB/s written vs HBM peak",
+        "value": 2 * nbytes / (ms_per_step * 1e-3) / 1e9, "unit": "GB/s",
+        "n_gpus": 1, "steps": steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int32", "data": "synthetic",
+        "config": {"workload": "p=2^27-1 processes (q=27): to/from tables of Alg. 7, then of Alg. 8, 4 tables of "
+                               "p x q int32", "p": p, "q": q},
+        "roofline": {"kernel": "k_partner_tables", "bound": "hbm", "achieved": nbytes / avg_ms / 1e6,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": nbytes / avg_ms / 1e6 / HBM_PEAK_GBS,
+                     "traffic": None, "avg_ms": avg_ms},
+        "csrc": csrc_digest(),
+    }
+    if not args.no_cpu_baseline:
+        import oracle
+        sample = 1 << 16
+        t0 = time.perf_counter()
+        for r in range(sample):
+            oracle.allgather_plan(p, r)
+            oracle.census_plan(p, r)
+        el = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": sample * q * 16 / el / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
+                               "sample": "the plans of %d processes, one call per process and collective (through "
+                                         "ctypes), %.1f s" % (sample, el)}
+    return out
+
+
 PACK_P = 1152              # the paper's largest run: 36 nodes x 32 processes
 
 
@@ -631,11 +673,12 @@ def main():
                     help="timed steps of the headline configuration (C3); the other configurations time min(steps, 100)")
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--workload", choices=["configs", "allgather-tables", "pack-round"], default="configs",
+    ap.add_argument("--workload", choices=["configs", "allgather-tables", "pack-round", "partner-tables"],
+                    default="configs",
                     help="configs (default): the hot path on the baseline's configurations C2..C5, headline on C3.  "
                          "allgather-tables: the first widening, Alg. 9's pack/unpack index tables of one process, "
                          "reported as its own line.  pack-round: the second, packing and unpacking one round's message "
-                         "on irregular buffers")
+                         "on irregular buffers.  partner-tables: the to/from tables of Alg. 7 and Alg. 8 for all processes")
     ap.add_argument("--only", default="C3,C2,C4,C5",
                     help="comma-separated subset of C2,C3,C4,C5 to run (for profiler runs; the headline needs C3)")
     ap.add_argument("--graph", action="store_true",
@@ -659,6 +702,9 @@ def main():
         return
     if args.workload == "pack-round":
         print(json.dumps(bench_pack_round(torch, bcs, args)))
+        return
+    if args.workload == "partner-tables":
+        print(json.dumps(bench_partner_tables(torch, bcs, args)))
         return
     only = [c.strip().upper() for c in args.only.split(",") if c.strip()]
     for c in only:

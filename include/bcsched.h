@@ -311,6 +311,22 @@ int bcs_allgather_plan(int32_t p, int32_t r, int32_t *to, int32_t *from,
                        int32_t *count, int32_t *recv_first);
 int bcs_census_plan(int32_t p, int32_t r, int32_t *to, int32_t *from, int32_t *own);
 
+/* The partner tables of the same two collectives for the processes [r0, r1) at
+ * once, written by one kernel (HBM-bound, pure stores): what a launcher or a
+ * simulator of the whole machine needs, and the device-side form of the two
+ * plans above.  to and from are device arrays of (r1 - r0) * q int32, entry
+ * [(r - r0) * q + k]; either may be NULL.
+ * bcs_allgather_partners (Alg. 7): to = (r - skips[k] + p) mod p, from =
+ * (r + skips[k]) mod p.  bcs_census_partners (Alg. 8): the same with the
+ * distance skips[k] - 1 in the rounds where 2 skips[k] > skips[k+1].  The
+ * per-round quantities that do not depend on the process (count, recv_first,
+ * own) come from the host plans of any one process.
+ * Asynchronous on `stream`, no allocation.  BCS_EINVAL: p < 1, a range outside
+ * 0 <= r0 <= r1 <= p, both arrays NULL with entries to write (p = 1 and
+ * r0 = r1 have none). */
+int bcs_allgather_partners(int32_t p, int32_t r0, int32_t r1, int32_t *to, int32_t *from, void *stream);
+int bcs_census_partners(int32_t p, int32_t r0, int32_t r1, int32_t *to, int32_t *from, void *stream);
+
 /* Frees the per-device scratch kept by the plain bcs_sched* calls on the
  * current device (after synchronising that device).  Safe to call anytime. */
 int bcs_release(void);
@@ -323,7 +339,7 @@ int bcs_release(void);
  * 0..BCS_KERNEL_COUNT-1, the summed duration in milliseconds and the number
  * of timed launches into host arrays of BCS_KERNEL_COUNT entries.  Not
  * thread-safe; meant for one measuring thread. */
-#define BCS_KERNEL_COUNT         15
+#define BCS_KERNEL_COUNT         16
 #define BCS_TIMING_MAX_LAUNCHES  4096
 int bcs_timing_begin(void);
 int bcs_timing_end(double *ms_sum_host, int64_t *launches_host);

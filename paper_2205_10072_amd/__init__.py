@@ -31,8 +31,9 @@ SYMBOLS = (
     "bcs_allgather_workspace_bytes", "bcs_allgather_tables", "bcs_allgather_tables_ws",
     "bcs_pack_workspace_bytes", "bcs_pack_round", "bcs_unpack_round", "bcs_allgather_plan", "bcs_census_plan",
     "bcs_pack_plan_rounds", "bcs_pack_round_planned", "bcs_unpack_round_planned",
+    "bcs_allgather_partners", "bcs_census_partners",
 )
-KERNEL_COUNT = 15
+KERNEL_COUNT = 16
 VALU_PEAK_OPS_PER_ITER = 32
 
 _lib = None
@@ -92,6 +93,8 @@ def lib():
     L.bcs_allgather_tables_ws.argtypes = [i32, i32, i32, vp, vp, vp, sz, vp]
     L.bcs_allgather_plan.argtypes = [i32, i32, vp, vp, vp, vp]
     L.bcs_census_plan.argtypes = [i32, i32, vp, vp, vp]
+    L.bcs_allgather_partners.argtypes = [i32, i32, i32, vp, vp, vp]
+    L.bcs_census_partners.argtypes = [i32, i32, i32, vp, vp, vp]
     L.bcs_pack_workspace_bytes.argtypes = [i32]
     L.bcs_pack_workspace_bytes.restype = i64
     L.bcs_pack_round.argtypes = [i32, i32, vp, vp, vp, vp, i64, vp, vp, sz, vp]
@@ -383,3 +386,18 @@ def bcs_allgather_plan(p, r):
 def bcs_census_plan(p, r):
     """Alg. 8: lists (to, from, own) of q entries."""
     return _host_plan(lib().bcs_census_plan, "bcs_census_plan", p, r, 3)
+
+
+def _partners(fn, what, p, r0, r1, to, frm, stream):
+    need = _rows(r0, r1) * bcs_q(p) if p >= 1 else 0
+    _check(fn(p, r0, r1, _ptr(to, need, what + ": to"), _ptr(frm, need, what + ": from"), _stream(stream)), what)
+
+
+def bcs_allgather_partners(p, r0, r1, to, frm, stream=None):
+    """Alg. 7's to- and from-processes of the processes [r0, r1): int32 device tables [(r - r0) * q + k]."""
+    _partners(lib().bcs_allgather_partners, "bcs_allgather_partners", p, r0, r1, to, frm, stream)
+
+
+def bcs_census_partners(p, r0, r1, to, frm, stream=None):
+    """Alg. 8's to- and from-processes of the processes [r0, r1): int32 device tables [(r - r0) * q + k]."""
+    _partners(lib().bcs_census_partners, "bcs_census_partners", p, r0, r1, to, frm, stream)

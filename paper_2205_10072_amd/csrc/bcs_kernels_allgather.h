@@ -388,6 +388,45 @@ __global__ __launch_bounds__(kBlock) void k_pack_copy(uint32_t p, int64_t limit,
     }
 }
 
+// ----------------------------------------------------------------------------------------------
+// Partner tables of the regular allgather (Alg. 7) and of the census (Alg. 8) for a range of processes:
+// to[(r - r0) q + k] = (r - dist_k + p) mod p, from[(r - r0) q + k] = (r + dist_k) mod p, where dist_k = skips[k]
+// for Alg. 7 and skips[k] minus one at the odd levels (2 skips[k] > skips[k+1]) for Alg. 8.  Pure stores: a
+// workgroup writes one 4 KB piece of each table (a lane 16 bytes of each), the shape in which store-only kernels
+// come closest to the HBM's rate on this GPU.  The skips come from Alg. 1's halving in closed form,
+// skips[k] = ((p-1) >> (q-k)) + 1, and level k is odd when bit q-1-k of p-1 is clear.
+// ----------------------------------------------------------------------------------------------
+template <bool VEC>
+__global__ __launch_bounds__(kBlock) void k_partner_tables(uint32_t p, uint32_t q, uint32_t census, uint32_t r0,
+                                                           uint64_t total, int32_t *__restrict__ to,
+                                                           int32_t *__restrict__ from) {
+    const uint64_t e0 = ((uint64_t)blockIdx.x * kBlock + threadIdx.x) * 4;
+    if (e0 >= total) return;
+    const uint64_t row = e0 / q;
+    uint32_t k = (uint32_t)(e0 - row * q);
+    uint32_t r = r0 + (uint32_t)row;
+    const uint32_t pm1 = p - 1u;
+    v4i vt, vf;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+        const uint32_t odd = census & ~(pm1 >> (q - 1u - k)) & 1u;
+        const uint32_t dist = (pm1 >> (q - k)) + 1u - odd;           // k < q <= 31: shifts of 1..31
+        vt[c] = (int32_t)(r >= dist ? r - dist : r + (p - dist));
+        const uint32_t f = r + dist;                                  // < 2^32: r, dist < 2^31
+        vf[c] = (int32_t)(f >= p ? f - p : f);
+        if (++k == q) { k = 0; ++r; }                                 // entries past the end are never stored
+    }
+    if (VEC && e0 + 4 <= total) {
+        if (to) __builtin_nontemporal_store(vt, reinterpret_cast<v4i *>(to + e0));
+        if (from) __builtin_nontemporal_store(vf, reinterpret_cast<v4i *>(from + e0));
+    } else {
+        for (int c = 0; c < 4 && e0 + c < total; ++c) {
+            if (to) to[e0 + c] = vt[c];
+            if (from) from[e0 + c] = vf[c];
+        }
+    }
+}
+
 }  // namespace
 
 #endif  // BCS_KERNELS_ALLGATHER_H

@@ -29,13 +29,13 @@ inline int hip_fail(hipError_t e) {
 // given a start and a stop event from a fixed pool, so its duration is the device's own.
 enum KernelId {
     kRecv = 0, kSendLookup, kSendRecompute, kBatch, kExpand, kFill, kValuPeak, kAllgather, kPackPlan, kPackCopy,
-    kRecvExpand, kSendExpand, kExpandRows, kRowsToBytes, kDigits, kKernelCount
+    kRecvExpand, kSendExpand, kExpandRows, kRowsToBytes, kDigits, kPartnerTables, kKernelCount
 };
 static_assert(kKernelCount == BCS_KERNEL_COUNT, "header and kernel list disagree");
 const char *const kKernelNames[kKernelCount] = {"k_recv_uniform", "k_send_lookup", "k_send_recompute", "k_batch",
                                                 "k_expand",       "k_fill",        "k_valu_peak",   "k_allgather_tables",
                                                 "k_pack_plan",    "k_pack_copy",   "k_recv_expand", "k_send_expand",
-                                                "k_expand_rows",  "k_rows_to_bytes", "k_digits"};
+                                                "k_expand_rows",  "k_rows_to_bytes", "k_digits",     "k_partner_tables"};
 struct Timing {
     bool on = false;
     int used = 0;
@@ -859,6 +859,38 @@ int bcs_census_plan(int32_t p, int32_t r, int32_t *to, int32_t *from, int32_t *o
         own[k] = odd ? 0 : 1;
     }
     return q;
+}
+
+}  // extern "C"
+
+namespace {
+int partner_tables(int32_t p, int32_t r0, int32_t r1, uint32_t census, int32_t *to, int32_t *from, void *stream) {
+    if (p < 1 || r0 < 0 || r0 > r1 || r1 > p) return BCS_EINVAL;
+    const int q = host_q(p);
+    const uint64_t total = (uint64_t)(r1 - r0) * (uint64_t)q;
+    if (total == 0) return BCS_OK;                                          // p = 1 or an empty range
+    if (!to && !from) return BCS_EINVAL;
+    const uint64_t blocks = (total + kBlock * 4 - 1) / (kBlock * 4);       // at most 2^31 * 31 / 1024
+    const bool vec = ((((uintptr_t)to) | ((uintptr_t)from)) & 15u) == 0;
+    if (vec)
+        launch(kPartnerTables, k_partner_tables<true>, dim3((unsigned)blocks), dim3(kBlock), (hipStream_t)stream,
+               (uint32_t)p, (uint32_t)q, census, (uint32_t)r0, total, to, from);
+    else
+        launch(kPartnerTables, k_partner_tables<false>, dim3((unsigned)blocks), dim3(kBlock), (hipStream_t)stream,
+               (uint32_t)p, (uint32_t)q, census, (uint32_t)r0, total, to, from);
+    hipError_t e = hipGetLastError();
+    return e == hipSuccess ? BCS_OK : hip_fail(e);
+}
+}  // namespace
+
+extern "C" {
+
+int bcs_allgather_partners(int32_t p, int32_t r0, int32_t r1, int32_t *to, int32_t *from, void *stream) {
+    return partner_tables(p, r0, r1, 0u, to, from, stream);
+}
+
+int bcs_census_partners(int32_t p, int32_t r0, int32_t r1, int32_t *to, int32_t *from, void *stream) {
+    return partner_tables(p, r0, r1, 1u, to, from, stream);
 }
 
 int64_t bcs_pack_workspace_bytes(int32_t p) {

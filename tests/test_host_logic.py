@@ -78,6 +78,12 @@ def test_host_helpers_and_argument_checks(oracle):
     assert L.bcs_pack_round_planned(5, fake, fake, fake, fake, 0, None) == bcs.OK
     assert L.bcs_unpack_round_planned(5, fake, fake, fake, fake, -1, None) == bcs.EINVAL
     assert L.bcs_unpack_round_planned(5, fake, fake, fake, None, 0, None) == bcs.OK
+    for fn in (L.bcs_allgather_partners, L.bcs_census_partners):
+        for p, r0, r1 in [(0, 0, 0), (10, 3, 2), (10, 0, 11), (10, -1, 4)]:
+            assert fn(p, r0, r1, fake, fake, None) == bcs.EINVAL
+        assert fn(10, 0, 4, None, None, None) == bcs.EINVAL
+        assert fn(1, 0, 1, None, None, None) == bcs.OK               # q = 0: no entries
+        assert fn(10, 4, 4, fake, None, None) == bcs.OK
     # p = 1 and empty ranges succeed without touching the device
     assert L.bcs_sched(1, 0, 1, fake, fake, None) == bcs.OK
     assert L.bcs_sched(9, 4, 4, fake, fake, None) == bcs.OK
