@@ -313,15 +313,15 @@ BCS_HD uint32_t window_blocks(const Pol &pol, uint32_t d_lo, uint32_t d_hi) {
 // One round of Alg. 4 on the digit masks of the window's end points: d_hi for v - skips[i], d_lo for
 // v - skips[i+1] (each with the lap digit when the subtraction did not wrap).  B is the set of blocks the rank
 // has, c the number of odd levels up to i; digits_of(y) gives the digit mask of a rank y < p.
-template <class Pol, class DigitsOf, class Emit>
-BCS_HD void recv_round(const Pol &pol, uint32_t v, int i, uint32_t s_n, uint32_t d_lo, uint32_t d_hi, int home,
-                       int own, uint32_t &B, uint32_t &c, DigitsOf digits_of, Emit emit) {
+template <class Pol, class DigitsOf>
+BCS_HD int recv_round_value(const Pol &pol, uint32_t v, int i, uint32_t s_n, uint32_t d_lo, uint32_t d_hi, int home,
+                            int own, uint32_t B, DigitsOf digits_of) {
     const uint32_t p = pol.p();
     const int q = pol.q();
     const uint32_t lap = 1u << (q & 31);
     const bool active = i < q;                            // per-lane q may be below the wave's bound
     const bool is_home = (i == home);
-    c += (pol.odd_mask() >> i) & 1u;
+    const uint32_t c = (uint32_t)__builtin_popcount(pol.odd_mask() & ((2u << (i & 31)) - 1u));
     uint32_t U = window_blocks(pol, d_lo, d_hi) & ~lap & ~B;
     const bool need2 = active && !is_home && U == 0u;
     if (BCS_WAVE_ANY(need2)) {
@@ -336,10 +336,56 @@ BCS_HD void recv_round(const Pol &pol, uint32_t v, int i, uint32_t s_n, uint32_t
         U = need2 ? U2 : U;
     }
     const int blk = 31 - BCS_CLZ(U);                      // largest candidate
+    return is_home ? own : blk - q;
+}
+
+// The same round for callers that keep B themselves: the new block joins B, the entry goes to emit.
+template <class Pol, class DigitsOf, class Emit>
+BCS_HD void recv_round(const Pol &pol, uint32_t v, int i, uint32_t s_n, uint32_t d_lo, uint32_t d_hi, int home,
+                       int own, uint32_t &B, DigitsOf digits_of, Emit emit) {
+    const int q = pol.q();
+    const int val = recv_round_value(pol, v, i, s_n, d_lo, d_hi, home, own, B, digits_of);
+    const bool active = i < q;
     // one emit for both kinds of round, so that a wave with lanes of both kinds does not run it twice
-    const bool take = active && !is_home;
-    B |= take ? (1u << (blk & 31)) : 0u;
-    if (active) emit(i, is_home ? own : blk - q);
+    B |= (active && val < 0) ? (1u << ((val + q) & 31)) : 0u;
+    if (active) emit(i, val);
+}
+
+// Rounds that need no window (one p per launch).  With D(v) the digit mask of the rank and low the value of its
+// digits below i, round i's entry is
+//   - the rank's baseblock when i is its highest digit (Alg. 4's first branch);
+//   - (next digit of v above i) - q when digit i is set: v - skips[i] then has the digits of v without digit i
+//     and is the case "adding the skip leaves the low digits alone" of send_row_direct below, seen from the
+//     receiving side;
+//   - i - q when digit i is clear and low keeps clear of the ends of its range: taking skips[i] from v borrows
+//     from the next digit j above (the lap digit when there is none), which sets digits i..j-1 and lowers the low
+//     part by the number o of odd levels in [i, j); this is case (b) of send_row_direct with the low part low - o,
+//     and the test here allows for every o from 0 to the number of odd levels from i up.
+// Like (b) and (c) there these are observations checked against the oracle (every rank of every p the CPU tests
+// run this code on, and the full-size configurations on the GPU), not proved statements.  Low rounds rarely
+// agree across the 64 ranks of a wave, so the test starts at round kDigitRoundsFrom.
+constexpr int kDigitRoundsFrom = 6;
+constexpr int kTabAhead = 10;                           // recv_row_tab reads the end points of rounds below this ahead
+
+// dl = D(v) with the lap digit (so that there always is a digit above round i); returns whether the entry could
+// be taken from the digits and leaves it in val, its block (the lap digit's index q for the home round, which
+// Alg. 4's set B never holds) in blk.  Written with masks instead of conditions: one straight run of vector ops.
+template <class Pol>
+BCS_HD bool round_from_digits(const Pol &pol, uint32_t dl, int i, uint32_t s_i, uint32_t low, int home, int own,
+                              int &val, int &blk) {
+    const int q = pol.q();
+    const uint32_t odd = pol.odd_mask();
+    const int mrg = 2 * __builtin_popcount(odd & ((2u << (i & 31)) - 1u)) + 2;
+    const int c1 = mrg + __builtin_popcount(odd >> (i & 31));          // low must exceed this ...
+    const int c2 = (int)s_i - mrg - 1;                                  // ... and stay below this
+    const uint32_t width = c2 > c1 + 1 ? (uint32_t)(c2 - c1 - 1) : 0u;
+    const uint32_t m = 0u - ((dl >> (i & 31)) & 1u);                    // all ones when digit i is set
+    const uint32_t above = (dl >> (i & 31)) >> 1;                       // never 0: the lap digit
+    const uint32_t next = (uint32_t)(__builtin_ctz(above) + i + 1);
+    blk = (int)((m & next) | (~m & (uint32_t)i));
+    val = i == home ? own : blk - q;
+    const uint32_t x = (low - (uint32_t)c1 - 1u) & ~m;
+    return m != 0u || x < width;
 }
 
 template <class Pol, class Emit>
@@ -359,29 +405,52 @@ BCS_HD void recv_row_from(const Pol &pol, uint32_t v, uint32_t dv, int last, Emi
     const int home = 31 - BCS_CLZ(dv);                    // -1 for the root
     const int own = dv ? __builtin_ctz(dv) : 0;
     uint32_t B = v ? (1u << own) : 0u;
+    // Digits of v - skips[n] with the lap digit.  When skips[n] is part of v's greedy sum, taking it out leaves the
+    // greedy sum of v - skips[n] (the ranks below it were below skips[n] before and still are), and for n = q the
+    // end point is v itself: no walk.  The high digits of consecutive ranks agree, so whole waves take this path.
+    // (Lanes with unrelated p never agree on it, so the per-lane policy does not ask.)
+    auto end_digits = [&](int n, uint32_t s) -> uint32_t {
+        const bool ahead = v >= s;
+        const uint32_t y = ahead ? v - s : v + p - s;
+        if constexpr (Pol::kScalarSkips) {
+            const uint32_t nbit = 1u << (n & 31);
+            const bool direct = (n == q) || (dv & nbit) != 0u;
+            uint32_t d = (n == q) ? dv : ((dv & ~nbit) | lap);
+            if (BCS_WAVE_ANY(!direct)) d = digits(pol, y) | (ahead ? lap : 0u);
+            return d;
+        } else {
+            return digits(pol, y) | (ahead ? lap : 0u);
+        }
+    };
     uint32_t s_i = pol.sdyn(0);
-    uint32_t d_hi = digits(pol, v >= s_i ? v - s_i : v + p - s_i) | (v >= s_i ? lap : 0u);
-    uint32_t c = 0;
+    uint32_t d_hi = 0;
+    bool have_hi = false;                                 // wave-uniform: d_hi holds the digits of v - skips[i]
+    uint32_t low = 0;                                     // value of v's digits below round i
 #pragma unroll 1
     for (int i = 0; i <= last; ++i) {
         const uint32_t s_n = pol.sdyn(i + 1);
-        const bool ahead = v >= s_n;
-        const uint32_t y = ahead ? v - s_n : v + p - s_n;
-        // When skips[i+1] is part of v's greedy sum, taking it out leaves the greedy sum of v - skips[i+1] (the
-        // ranks below it were below skips[i+1] before and still are), and in the last round the end point is v
-        // itself: no walk.  The high digits of consecutive ranks agree, so whole waves take this path.
-        // (Lanes with unrelated p never agree on it, so the per-lane policy does not ask.)
-        uint32_t d_lo;
-        if constexpr (Pol::kScalarSkips) {
-            const uint32_t nbit = 1u << ((i + 1) & 31);
-            const bool direct = (i + 1 == q) || (dv & nbit) != 0u;
-            d_lo = (i + 1 == q) ? dv : ((dv & ~nbit) | lap);
-            if (BCS_WAVE_ANY(!direct)) d_lo = digits(pol, y) | (ahead ? lap : 0u);
+        int val = 0;
+        bool easy = false;
+        int blk = 0;
+        if constexpr (Pol::kScalarSkips)
+            easy = i >= kDigitRoundsFrom && round_from_digits(pol, dv | lap, i, s_i, low, home, own, val, blk);
+        if (BCS_WAVE_ANY(!easy)) {
+            if (!have_hi) d_hi = end_digits(i, s_i);
+            const uint32_t d_lo = end_digits(i + 1, s_n);
+            const int w = recv_round_value(pol, v, i, s_n, d_lo, d_hi, home, own, B,
+                                           [&](uint32_t r) { return digits(pol, r); });
+            val = easy ? val : w;
+            blk = easy ? blk : (w < 0 ? w + q : q);       // the home round adds nothing: the lap digit's bit
+            d_hi = d_lo;
+            have_hi = true;
         } else {
-            d_lo = digits(pol, y) | (ahead ? lap : 0u);
+            have_hi = false;
         }
-        recv_round(pol, v, i, s_n, d_lo, d_hi, home, own, B, c, [&](uint32_t r) { return digits(pol, r); }, emit);
-        d_hi = d_lo;
+        const bool active = i < q;                        // per-lane q may be below the wave's bound
+        B |= active ? (1u << (blk & 31)) : 0u;
+        if (active) emit(i, val);
+        low += (dv >> (i & 31)) & 1u ? s_i : 0u;
+        s_i = s_n;
     }
 }
 
@@ -395,21 +464,38 @@ BCS_HD void recv_row_tab(const Pol &pol, const uint32_t *__restrict__ dtab, uint
     constexpr int kQ = Pol::kTopLevel + 1;
     const uint32_t p = pol.p();
     const uint32_t lap = 1u << (kQ & 31);
-    uint32_t d[kQ + 1];                                  // d[n]: digits of v - skips[n] with the lap digit
-#pragma unroll
-    for (int n = 0; n <= kQ; ++n) {
+    // d(n): digits of v - skips[n] with the lap digit.  Those of the low rounds, which always need their windows,
+    // are read ahead; the others only by the few waves that need a window in a high round.
+    constexpr int kAhead = kQ < kTabAhead ? kQ : kTabAhead;
+    auto end_point = [&](int n) -> uint32_t {
         const uint32_t s = pol.s(n);
         const bool ahead = v >= s;
-        d[n] = dtab[ahead ? v - s : v + p - s] | (ahead ? lap : 0u);
-    }
-    const uint32_t dv = d[kQ];                           // skips[q] = p: the rank itself, no lap
+        return dtab[ahead ? v - s : v + p - s] | (ahead ? lap : 0u);
+    };
+    uint32_t d[kAhead + 1];
+#pragma unroll
+    for (int n = 0; n <= kAhead; ++n) d[n] = end_point(n);
+    const uint32_t dv = dtab[v];                         // skips[q] = p: the rank itself, no lap
     const int home = 31 - BCS_CLZ(dv);
     const int own = dv ? __builtin_ctz(dv) : 0;
     uint32_t B = v ? (1u << own) : 0u;
-    uint32_t c = 0;
+    uint32_t low = 0;                                    // value of v's digits below round i
 #pragma unroll
-    for (int i = 0; i < kQ; ++i)
-        recv_round(pol, v, i, pol.s(i + 1), d[i + 1], d[i], home, own, B, c, [&](uint32_t r) { return dtab[r]; }, emit);
+    for (int i = 0; i < kQ; ++i) {
+        int val = 0, blk = 0;
+        const bool easy = i >= kDigitRoundsFrom && round_from_digits(pol, dv | lap, i, pol.s(i), low, home, own, val, blk);
+        if (BCS_WAVE_ANY(!easy)) {
+            const uint32_t d_hi = i <= kAhead ? d[i <= kAhead ? i : 0] : end_point(i);
+            const uint32_t d_lo = i + 1 == kQ ? dv : (i + 1 <= kAhead ? d[i + 1 <= kAhead ? i + 1 : 0] : end_point(i + 1));
+            const int w = recv_round_value(pol, v, i, pol.s(i + 1), d_lo, d_hi, home, own, B,
+                                           [&](uint32_t r) { return dtab[r]; });
+            val = easy ? val : w;
+            blk = easy ? blk : (w < 0 ? w + kQ : kQ);    // the home round adds nothing: the lap digit's bit
+        }
+        B |= 1u << (blk & 31);
+        emit(i, val);
+        low += (0u - ((dv >> i) & 1u)) & pol.s(i);
+    }
 }
 
 // Rounds 0..last of the same row, for Alg. 5's neighbours (last varies, so the rounds stay a loop): the read for
@@ -431,12 +517,11 @@ BCS_HD void recv_row_tab_upto(const Pol &pol, const uint32_t *__restrict__ dtab,
     const int home = 31 - BCS_CLZ(dv);
     const int own = dv ? __builtin_ctz(dv) : 0;
     uint32_t B = v ? (1u << own) : 0u;
-    uint32_t c = 0;
 #pragma unroll 1
     for (int i = 0; i <= last; ++i) {
         const uint32_t s_next = pol.sdyn(i + 2 <= q ? i + 2 : q);
         const uint32_t d_next = end_point(s_next);
-        recv_round(pol, v, i, s_n, d_lo, d_hi, home, own, B, c, [&](uint32_t r) { return dtab[r]; }, emit);
+        recv_round(pol, v, i, s_n, d_lo, d_hi, home, own, B, [&](uint32_t r) { return dtab[r]; }, emit);
         d_hi = d_lo;
         d_lo = d_next;
         s_n = s_next;

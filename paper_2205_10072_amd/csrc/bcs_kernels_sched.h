@@ -57,7 +57,7 @@ __device__ __forceinline__ void tile_to_rows(const int32_t *tile, uint32_t rows,
         if ((reinterpret_cast<uintptr_t>(dst) & 15u) == 0) {
             const uint32_t n4 = n >> 2;
             for (uint32_t g = threadIdx.x; g < n4; g += kBlock)
-                reinterpret_cast<v4i *>(dst)[g] = reinterpret_cast<const v4i *>(tile)[g];
+                __builtin_nontemporal_store(reinterpret_cast<const v4i *>(tile)[g], reinterpret_cast<v4i *>(dst) + g);
             const uint32_t e = (n4 << 2) + threadIdx.x;
             if (e < n) dst[e] = tile[e];
             return;
@@ -92,6 +92,7 @@ __global__ __launch_bounds__(kBlock) void k_digits(const SkipTab tab, uint32_t *
     if (y < p) dtab[y] = d;
 }
 
+constexpr uint64_t kSlotTableCached = 128ull << 20;   // slot-major tables up to this size are written for the caches
 template <int Q, bool BYTES, bool TAB = false>
 __global__ __launch_bounds__(kBlock) void k_recv_uniform(const SkipTab tab, uint32_t root, uint32_t r0, uint32_t r1,
                                                          int32_t *__restrict__ recv_out,
@@ -102,6 +103,9 @@ __global__ __launch_bounds__(kBlock) void k_recv_uniform(const SkipTab tab, uint
     constexpr int kRS = byte_row_stride(Q);
     __shared__ __align__(16) int32_t tile[kBlock * kStride];
     __shared__ __align__(16) int8_t tileB[BYTES ? kBlock * kRS : 16];   // only the variant that leaves byte rows pays for it
+    // the tile's part of the slot-major table, slot by slot; the variant with byte rows (tables that the caches
+    // hold) has no room for it beside them and stores the entries one by one
+    __shared__ __align__(16) slot_t tileT[BYTES ? 16 : Q * kBlock];
     __shared__ uint32_t lowtab[kLowShapeBytes / 4];
     Uniform<Q> pol;
 #pragma unroll
@@ -115,20 +119,40 @@ __global__ __launch_bounds__(kBlock) void k_recv_uniform(const SkipTab tab, uint
     const uint64_t idx = first + threadIdx.x;
     const uint64_t count = (uint64_t)r1 - r0;
     const bool live = idx < count;
-    const uint32_t r = live ? (uint32_t)(r0 + idx) : root;       // idle lanes replay the root (cheap, valid)
+    const uint32_t r = live ? (uint32_t)(r0 + idx) : root;
     const uint32_t v = r >= root ? r - root : r + p - root;
     int32_t *my = tile + threadIdx.x * kStride;
     int8_t *myB = tileB + (BYTES ? threadIdx.x * kRS : 0);
     auto emit = [&](int i, int val) {
         my[i] = val;
-        if (recvT && live) recvT[(uint64_t)i * ldT + idx] = (slot_t)val;
-        if constexpr (BYTES) myB[i] = (int8_t)(val - i);
+        if constexpr (BYTES) {
+            if (recvT) recvT[(uint64_t)i * ldT + idx] = (slot_t)val;
+            myB[i] = (int8_t)(val - i);
+        } else {
+            if (recvT) tileT[i * kBlock + threadIdx.x] = (slot_t)val;
+        }
     };
-    if constexpr (TAB) recv_row_tab(pol, dtab, v, emit);
-    else recv_row(pol, v, Q - 1, emit);
-    if (!recv_out) return;
+    if (live) {                                                  // lanes past the end sit the row out
+        if constexpr (TAB) recv_row_tab(pol, dtab, v, emit);
+        else recv_row(pol, v, Q - 1, emit);
+    }
     if constexpr (BYTES) byte_row_finish<Q>(myB);
     __syncthreads();
+    if (!BYTES && recvT) {
+        // Each slot's kBlock bytes are one aligned piece of the table (its rows are padded to a multiple of
+        // kBlock, so the last tile writes its idle lanes' bytes into the padding): 16 bytes a lane.
+        static_assert(kBlock % 16 == 0, "16-byte pieces");
+        // A table that the caches hold is left there for the look-up that follows; a larger one is streamed out.
+        const bool stream_out = ldT * Q > kSlotTableCached;
+        for (int g = threadIdx.x; g < Q * (kBlock / 16); g += kBlock) {
+            const int k = g / (kBlock / 16), part = g % (kBlock / 16);
+            const v4i piece = *reinterpret_cast<const v4i *>(tileT + k * kBlock + part * 16);
+            v4i *dst = reinterpret_cast<v4i *>(recvT + (uint64_t)k * ldT + first + part * 16);
+            if (stream_out) __builtin_nontemporal_store(piece, dst);
+            else *dst = piece;
+        }
+    }
+    if (!recv_out) return;
     const uint64_t rows = (count - first) < (uint64_t)kBlock ? (count - first) : (uint64_t)kBlock;
     tile_to_rows<Q>(tile, (uint32_t)rows, recv_out + first * Q);
     if constexpr (BYTES) byte_rows_out<Q>(tileB, (uint32_t)rows, rowsB + first * kRS);
