@@ -321,11 +321,12 @@ BCS_HD int recv_round_value(const Pol &pol, uint32_t v, int i, uint32_t s_n, uin
     const uint32_t lap = 1u << (q & 31);
     const bool active = i < q;                            // per-lane q may be below the wave's bound
     const bool is_home = (i == home);
-    const uint32_t c = (uint32_t)__builtin_popcount(pol.odd_mask() & ((2u << (i & 31)) - 1u));
     uint32_t U = window_blocks(pol, d_lo, d_hi) & ~lap & ~B;
     const bool need2 = active && !is_home && U == 0u;
     if (BCS_WAVE_ANY(need2)) {
-        // the c ranks that end where the first range begins; one more lap if that runs below 0
+        // the c ranks that end where the first range begins (c = the number of odd levels up to i); one more lap
+        // if that runs below 0
+        const uint32_t c = (uint32_t)__builtin_popcount(pol.odd_mask() & ((2u << (i & 31)) - 1u));
         const uint32_t Y = v + p - s_n;
         const bool under = Y < c;
         const uint32_t Z = under ? Y + p - c : Y - c;

@@ -69,6 +69,26 @@ __device__ __forceinline__ void tile_to_rows(const int32_t *tile, uint32_t rows,
     }
 }
 
+
+// Rows of a workgroup's LDS tile of bytes (rank-major, Q bytes a rank, so the tile is the table's piece with one byte
+// an entry) to their place in the rank-major int32 table: a lane reads four bytes, widens them and writes 16 bytes.
+template <int Q>
+__device__ __forceinline__ void byte_tile_to_rows(const int8_t *tile, uint32_t rows, int32_t *__restrict__ dst) {
+    const uint32_t n = rows * Q;
+    if ((reinterpret_cast<uintptr_t>(dst) & 15u) == 0) {
+        const uint32_t n4 = n >> 2;
+        for (uint32_t g = threadIdx.x; g < n4; g += kBlock) {
+            const int32_t w = reinterpret_cast<const int32_t *>(tile)[g];
+            const v4i pack = {(int32_t)(int8_t)w, (int32_t)(int8_t)(w >> 8), (int32_t)(int8_t)(w >> 16), w >> 24};
+            __builtin_nontemporal_store(pack, reinterpret_cast<v4i *>(dst) + g);
+        }
+        const uint32_t e = (n4 << 2) + threadIdx.x;
+        if (e < n) dst[e] = tile[e];
+        return;
+    }
+    for (uint32_t e = threadIdx.x; e < n; e += kBlock) dst[e] = tile[e];
+}
+
 // ----------------------------------------------------------------------------------------------
 // K1: receive rows of ranks [r0, r1), uniform p.  Lane = rank.  Rows are staged in LDS (odd stride,
 // conflict-free) and leave as contiguous dwords; optionally each entry is also stored slot-major
@@ -99,9 +119,8 @@ __global__ __launch_bounds__(kBlock) void k_recv_uniform(const SkipTab tab, uint
                                                          slot_t *__restrict__ recvT, uint64_t ldT,
                                                          int8_t *__restrict__ rowsB,
                                                          const uint32_t *__restrict__ dtab) {
-    constexpr int kStride = Q | 1;
     constexpr int kRS = byte_row_stride(Q);
-    __shared__ __align__(16) int32_t tile[kBlock * kStride];
+    __shared__ __align__(16) int8_t tile[kBlock * Q + 16];
     __shared__ __align__(16) int8_t tileB[BYTES ? kBlock * kRS : 16];   // only the variant that leaves byte rows pays for it
     // the tile's part of the slot-major table, slot by slot; the variant with byte rows (tables that the caches
     // hold) has no room for it beside them and stores the entries one by one
@@ -121,10 +140,10 @@ __global__ __launch_bounds__(kBlock) void k_recv_uniform(const SkipTab tab, uint
     const bool live = idx < count;
     const uint32_t r = live ? (uint32_t)(r0 + idx) : root;
     const uint32_t v = r >= root ? r - root : r + p - root;
-    int32_t *my = tile + threadIdx.x * kStride;
+    int8_t *my = tile + threadIdx.x * Q;
     int8_t *myB = tileB + (BYTES ? threadIdx.x * kRS : 0);
     auto emit = [&](int i, int val) {
-        my[i] = val;
+        my[i] = (int8_t)val;
         if constexpr (BYTES) {
             if (recvT) recvT[(uint64_t)i * ldT + idx] = (slot_t)val;
             myB[i] = (int8_t)(val - i);
@@ -154,7 +173,7 @@ __global__ __launch_bounds__(kBlock) void k_recv_uniform(const SkipTab tab, uint
     }
     if (!recv_out) return;
     const uint64_t rows = (count - first) < (uint64_t)kBlock ? (count - first) : (uint64_t)kBlock;
-    tile_to_rows<Q>(tile, (uint32_t)rows, recv_out + first * Q);
+    byte_tile_to_rows<Q>(tile, (uint32_t)rows, recv_out + first * Q);
     if constexpr (BYTES) byte_rows_out<Q>(tileB, (uint32_t)rows, rowsB + first * kRS);
 }
 
@@ -282,8 +301,7 @@ template <int Q, bool TAB>
 __global__ __launch_bounds__(kBlock) void k_send_recompute(const SkipTab tab, uint32_t root, uint32_t r0, uint32_t r1,
                                                            int32_t *__restrict__ send_out,
                                                            const uint32_t *__restrict__ dtab) {
-    constexpr int kStride = Q | 1;
-    __shared__ __align__(16) int32_t tile[kBlock * kStride];
+    __shared__ __align__(16) int8_t tile[kBlock * Q + 16];   // one byte an entry, laid out like the table
     __shared__ uint32_t lowtab[kLowShapeBytes / 4];
     Uniform<Q> pol;
 #pragma unroll
@@ -299,14 +317,14 @@ __global__ __launch_bounds__(kBlock) void k_send_recompute(const SkipTab tab, ui
     const bool live = idx < count;
     const uint32_t r = live ? (uint32_t)(r0 + idx) : root;
     const uint32_t v = r >= root ? r - root : r + p - root;
-    int32_t *my = tile + threadIdx.x * kStride;
+    int8_t *my = tile + threadIdx.x * Q;
     // the entries that need none of the to-neighbour's rounds (bcs_core.h); for consecutive ranks and large p
     // that is nearly all of them
     auto digits_of = [&](uint32_t y) -> uint32_t {
         if constexpr (TAB) return dtab[y];                // digit masks of all ranks from k_digits
         else return digits(pol, y);
     };
-    uint32_t pending = send_row_direct(pol, v, digits_of(v), digits_of, [&](int k, int val) { my[k] = val; });
+    uint32_t pending = send_row_direct(pol, v, digits_of(v), digits_of, [&](int k, int val) { my[k] = (int8_t)val; });
     // Alg. 5 for the rest: every lane works down its own list, largest k first; the wave computes rounds
     // 0..(largest k asked for) of each lane's neighbour and a lane keeps the entry of its own k
     while (__any(pending != 0u)) {
@@ -326,11 +344,11 @@ __global__ __launch_bounds__(kBlock) void k_send_recompute(const SkipTab tab, ui
         auto own_entry = [&](int j, int val) { got = (j == kk) ? val : got; };
         if constexpr (TAB) recv_row_tab_upto(pol, dtab, t, dtab[t], kmax, own_entry);
         else recv_row(pol, t, kmax, own_entry);
-        if (kk >= 0) my[kk] = got;
+        if (kk >= 0) my[kk] = (int8_t)got;
     }
     __syncthreads();
     const uint64_t rows = (count - first) < (uint64_t)kBlock ? (count - first) : (uint64_t)kBlock;
-    tile_to_rows<Q>(tile, (uint32_t)rows, send_out + first * Q);
+    byte_tile_to_rows<Q>(tile, (uint32_t)rows, send_out + first * Q);
 }
 
 // K3: unrelated (p, r, root) triples; rows of BCS_BATCH_STRIDE ints (one 128-byte line each), padded.
