@@ -51,24 +51,24 @@ def csrc_digest():
 # Key: (config, kernel).  `csrc`: csrc_digest() of the sources that were profiled; when the sources have changed
 # since, the record is still printed but marked "stale": true, and a warning goes to stderr.
 PROFILED = {
-    "csrc": "aba8a9e3f3518bcf",
+    "csrc": "ba28eb247fe814cd",
     "source": "profiles/c2_step_p1048577_n256.md, c3_sched_p134217727.md, c4_expand_p65537_n4096.md, c5_batch_2e20.md, "
               "allgather_tables_p1048577_n256.md",
     "counters": {
         # per dispatch: FETCH_SIZE / WRITE_SIZE in KiB as read, SQ_WAVES, SQ_INSTS_VALU / SQ_WAVES, SQ_INSTS_SALU / SQ_WAVES,
         # SQ_THREAD_CYCLES_VALU / SQ_ACTIVE_INST_VALU (lanes active per vector instruction, of 64)
         ("C3", "k_digits"): {'fetch_kib': 28, 'write_kib': 524288, 'waves': 2097152, 'valu_per_wave': 90.0, 'salu_per_wave': 25.5, 'active_lanes': 64.0},
-        ("C3", "k_recv_uniform"): {'fetch_kib': 3190049, 'write_kib': 17696065, 'waves': 2097152, 'valu_per_wave': 1402.0, 'salu_per_wave': 525.0, 'active_lanes': 64.0},
-        ("C3", "k_send_lookup"): {'fetch_kib': 2031789, 'write_kib': 14156028, 'waves': 524288, 'valu_per_wave': 1002.0, 'salu_per_wave': 626.0, 'active_lanes': 64.0},
+        ("C3", "k_recv_uniform"): {'fetch_kib': 1048874, 'write_kib': 17694790, 'waves': 2097152, 'valu_per_wave': 882.9, 'salu_per_wave': 525.4, 'active_lanes': 64.0},
+        ("C3", "k_send_lookup"): {'fetch_kib': 2031795, 'write_kib': 14155949, 'waves': 524288, 'valu_per_wave': 1002.0, 'salu_per_wave': 626.0, 'active_lanes': 64.0},
         ("C2", "k_digits"): {'fetch_kib': 31, 'write_kib': 4096, 'waves': 16388, 'valu_per_wave': 72.0, 'salu_per_wave': 25.5, 'active_lanes': 64.0},
-        ("C2", "k_recv_uniform"): {'fetch_kib': 11285, 'write_kib': 132100, 'waves': 16388, 'valu_per_wave': 1275.0, 'salu_per_wave': 460.2, 'active_lanes': 64.0},
-        ("C2", "k_send_lookup"): {'fetch_kib': 21066, 'write_kib': 110666, 'waves': 8193, 'valu_per_wave': 1126.9, 'salu_per_wave': 446.0, 'active_lanes': 63.2},
-        ("C2", "k_expand_rows"): {'fetch_kib': 35345, 'write_kib': 1130582, 'waves': 1130500, 'valu_per_wave': 69.0, 'salu_per_wave': 9.0, 'active_lanes': 64.0},
+        ("C2", "k_recv_uniform"): {'fetch_kib': 7270, 'write_kib': 132104, 'waves': 16388, 'valu_per_wave': 1025.4, 'salu_per_wave': 564.5, 'active_lanes': 64.0},
+        ("C2", "k_send_lookup"): {'fetch_kib': 21071, 'write_kib': 110660, 'waves': 8193, 'valu_per_wave': 1126.9, 'salu_per_wave': 446.0, 'active_lanes': 63.2},
+        ("C2", "k_expand_rows"): {'fetch_kib': 35337, 'write_kib': 1130597, 'waves': 1130500, 'valu_per_wave': 69.0, 'salu_per_wave': 9.0, 'active_lanes': 64.0},
         ("C4", "k_expand"): {'fetch_kib': 9008, 'write_kib': 1052688, 'waves': 263176, 'valu_per_wave': 258.5, 'salu_per_wave': 195.0, 'active_lanes': 63.3},
         ("C4", "k_rows_to_bytes"): {'fetch_kib': 2252, 'write_kib': 1280, 'waves': 5124, 'valu_per_wave': 50.0, 'salu_per_wave': 12.0, 'active_lanes': 64.0},
-        ("C4", "k_expand_rows"): {'fetch_kib': 5135, 'write_kib': 1052904, 'waves': 1052692, 'valu_per_wave': 69.0, 'salu_per_wave': 9.0, 'active_lanes': 64.0},
-        ("C5 recv_and_send", "k_batch"): {'fetch_kib': 8470, 'write_kib': 266240, 'waves': 16384, 'valu_per_wave': 11584.4, 'salu_per_wave': 3662.1, 'active_lanes': 63.8},
-        ("C5 recv_only", "k_batch"): {'fetch_kib': 8364, 'write_kib': 135168, 'waves': 16384, 'valu_per_wave': 2831.3, 'salu_per_wave': 870.0, 'active_lanes': 63.8},
+        ("C4", "k_expand_rows"): {'fetch_kib': 5127, 'write_kib': 1052932, 'waves': 1052692, 'valu_per_wave': 69.0, 'salu_per_wave': 9.0, 'active_lanes': 64.0},
+        ("C5 recv_and_send", "k_batch"): {'fetch_kib': 8495, 'write_kib': 266240, 'waves': 16384, 'valu_per_wave': 11522.8, 'salu_per_wave': 3684.2, 'active_lanes': 63.8},
+        ("C5 recv_only", "k_batch"): {'fetch_kib': 8406, 'write_kib': 135168, 'waves': 16384, 'valu_per_wave': 2813.4, 'salu_per_wave': 872.8, 'active_lanes': 63.8},
         ("AG", "k_allgather_tables"): {"fetch_kib": 41280, "write_kib": 2261412},
     },
 }
@@ -90,12 +90,14 @@ def profiled(config, kernel, digest):
 # its loops to the largest q among its lanes; that excess, the second-range branch of Alg. 4, the byte copies of a
 # row and the sort of the batch kernel are not counted).  So `frac` = useful lane-ops/s / peak is at most the share
 # of time the vector ALUs are busy, and falls below it by divergence and by everything that is not the method.
-#   a row whose end points come from the table      36.6 q + 414: the vector instructions k_recv_uniform executes per
-#                                                    rank (one rank a lane), fitted to SQ_INSTS_VALU / SQ_WAVES measured
-#                                                    at q = 17 (1 036) and q = 27 (1 402); so for this kernel `frac` is
-#                                                    the share of the peak its executed vector instructions amount to,
-#                                                    i.e. its vector-ALU utilisation (the byte rows that the C2 step
-#                                                    also leaves cost 92 instructions more and are not counted)
+#   a row whose end points come from the table      the vector instructions k_recv_uniform executes (one rank a lane),
+#                                                    SQ_INSTS_VALU x 64 of the counter profile of this configuration:
+#                                                    the count depends on p (how many rounds a wave takes from the
+#                                                    ranks' digits, how many from windows), so it is measured, not
+#                                                    modelled; for this kernel `frac` is therefore its vector-ALU
+#                                                    utilisation.  Without a profile entry: 55 ops for each of the first
+#                                                    six rounds, 28 for each later one (17 for the rule, a window in one
+#                                                    round of five), 80 of set-up
 #   the batch kernel and Alg. 5, by the structure of the code (no counter fit):
 #   a round of Alg. 4 on two digit masks            55 ops (window masks, candidate, bookkeeping)
 #   set-up of a row                                 50 ops
@@ -113,7 +115,17 @@ def ops_walk(q, per_lane):
 
 
 def ops_recv_tabled(q):
-    return 36.6 * q + 414
+    return 55 * min(q, 6) + 28 * max(q - 6, 0) + 80
+
+
+def recv_tabled_model(config, p, q, digest):
+    """("alu", lane-ops per launch, note) for k_recv_uniform over all p ranks: executed instructions from the profile
+    of `config` if there is one, else the estimate above."""
+    prof = profiled(config, "k_recv_uniform", digest)
+    if prof is not None and "valu_per_wave" in prof:
+        return ("alu", prof["valu_per_wave"] * prof["waves"] * prof["active_lanes"],
+                "counters (executed vector lane-operations)" + (", of other sources: stale" if prof["stale"] else ""))
+    return ("alu", ops_recv_tabled(q) * p, "model (estimate)")
 
 
 def ops_recv_walks(q, per_lane, walks=None):
@@ -211,7 +223,12 @@ def kernel_records(timing, steps, models, config, digest):
         ent = {"launches_per_step": cnt / steps, "avg_ms": avg_ms, "min_ms": shortest, "max_ms": longest,
                "ms_per_step": ms / steps}
         if name in models:
-            bound, amount = models[name]
+            bound, amount = models[name][:2]
+            if len(models[name]) > 2:
+                ent["ops_source"] = models[name][2]
+            if len(models[name]) > 3:          # a second view: the bytes the kernel has to move, against the HBM peak
+                ent["hbm_algorithmic_bytes"] = models[name][3]
+                ent["hbm_frac"] = models[name][3] / avg_ms / 1e6 / HBM_PEAK_GBS
             if bound == "hbm":
                 ent.update(bound="hbm", achieved=amount / avg_ms / 1e6, peak=HBM_PEAK_GBS, unit="GB/s",
                            algorithmic_bytes=amount)
@@ -253,7 +270,8 @@ def run_c3(torch, bcs, steps, warmup, digest):
         bcs.bcs_sched_rooted_ws(p, ROOT_RANK, 0, p, recv, send, ws)
 
     ms, ms_ev, timing = timed_steps(torch, bcs, step, steps, warmup)
-    models = {"k_recv_uniform": ("alu", ops_recv_tabled(q) * p),
+    # the receive kernel writes the int32 table and the slot-major bytes and reads the digit table (counted once)
+    models = {"k_recv_uniform": recv_tabled_model("C3", p, q, digest) + (p * q * (4 + 1) + 4 * p,),
               "k_digits": ("alu", (ops_walk(q, False) + 12) * p),
               "k_send_lookup": ("hbm", p * q * (1 + 4))}          # reads the slot-major bytes, writes one int32 table
     kernels = kernel_records(timing, steps, models, "C3", digest)
@@ -294,7 +312,7 @@ def run_c2(torch, bcs, steps, warmup, digest):
     ms, ms_ev, timing = timed_steps(torch, bcs, step, steps, warmup)
     models = {"k_expand_rows": ("hbm", P * R * 4), "k_expand": ("hbm", P * R * 4),
               "k_send_lookup": ("hbm", P * q * (1 + 4) + P * 24),   # slot-major bytes in; one table and its byte rows out
-              "k_recv_uniform": ("alu", ops_recv_tabled(q) * P),
+              "k_recv_uniform": recv_tabled_model("C2", P, q, digest),
               "k_digits": ("alu", (ops_walk(q, False) + 12) * P)}
     kernels = kernel_records(timing, steps, models, "C2", digest)
     construct_ms = sum(kernels[k]["ms_per_step"] for k in ("k_digits", "k_recv_uniform", "k_send_lookup") if k in kernels)

@@ -33,6 +33,13 @@
 // q+1 digit masks (3 vector ops a level down to level 7; the seven low digits of what is left are one
 // more row of the table) and a few bit operations per round.
 // All of it is branch-free apart from the wave-uniform test for Alg. 4's rare second range.
+//
+// (3) Rounds without a window (round_from_digits, one p per launch).  From level 6 up most rounds of most ranks
+// follow from D(v) alone: the home round gives the baseblock, a round whose digit is set gives the next digit
+// above, a round whose digit is clear gives the round's own index when the value of the lower digits keeps clear
+// of the ends of its range.  The 64 consecutive ranks of a wave share their high digits, so whole waves skip the
+// window in about three of four rounds; a wave with a lane the rule leaves out computes the window as in (2) and
+// every lane keeps whichever result applies to it.
 #ifndef BCS_CORE_H
 #define BCS_CORE_H
 
@@ -315,7 +322,7 @@ BCS_HD uint32_t window_blocks(const Pol &pol, uint32_t d_lo, uint32_t d_hi) {
 // has, c the number of odd levels up to i; digits_of(y) gives the digit mask of a rank y < p.
 template <class Pol, class DigitsOf>
 BCS_HD int recv_round_value(const Pol &pol, uint32_t v, int i, uint32_t s_n, uint32_t d_lo, uint32_t d_hi, int home,
-                            int own, uint32_t B, DigitsOf digits_of) {
+                            int own, uint32_t B, DigitsOf digits_of, int &blk_out) {
     const uint32_t p = pol.p();
     const int q = pol.q();
     const uint32_t lap = 1u << (q & 31);
@@ -337,6 +344,7 @@ BCS_HD int recv_round_value(const Pol &pol, uint32_t v, int i, uint32_t s_n, uin
         U = need2 ? U2 : U;
     }
     const int blk = 31 - BCS_CLZ(U);                      // largest candidate
+    blk_out = is_home ? q : blk;                          // the home round adds nothing to B: the lap digit's bit
     return is_home ? own : blk - q;
 }
 
@@ -345,10 +353,11 @@ template <class Pol, class DigitsOf, class Emit>
 BCS_HD void recv_round(const Pol &pol, uint32_t v, int i, uint32_t s_n, uint32_t d_lo, uint32_t d_hi, int home,
                        int own, uint32_t &B, DigitsOf digits_of, Emit emit) {
     const int q = pol.q();
-    const int val = recv_round_value(pol, v, i, s_n, d_lo, d_hi, home, own, B, digits_of);
+    int blk;
+    const int val = recv_round_value(pol, v, i, s_n, d_lo, d_hi, home, own, B, digits_of, blk);
     const bool active = i < q;
     // one emit for both kinds of round, so that a wave with lanes of both kinds does not run it twice
-    B |= (active && val < 0) ? (1u << ((val + q) & 31)) : 0u;
+    B |= active ? (1u << (blk & 31)) : 0u;
     if (active) emit(i, val);
 }
 
@@ -424,33 +433,33 @@ BCS_HD void recv_row_from(const Pol &pol, uint32_t v, uint32_t dv, int last, Emi
         }
     };
     uint32_t s_i = pol.sdyn(0);
-    uint32_t d_hi = 0;
-    bool have_hi = false;                                 // wave-uniform: d_hi holds the digits of v - skips[i]
+    uint32_t d_hi = end_digits(0, s_i);
+    bool have_hi = true;                                  // wave-uniform: d_hi holds the digits of v - skips[i]
     uint32_t low = 0;                                     // value of v's digits below round i
 #pragma unroll 1
     for (int i = 0; i <= last; ++i) {
         const uint32_t s_n = pol.sdyn(i + 1);
-        int val = 0;
-        bool easy = false;
-        int blk = 0;
-        if constexpr (Pol::kScalarSkips)
+        int val = 0, blk = 0;
+        bool easy = false, window = true;
+        if constexpr (Pol::kScalarSkips) {
             easy = i >= kDigitRoundsFrom && round_from_digits(pol, dv | lap, i, s_i, low, home, own, val, blk);
-        if (BCS_WAVE_ANY(!easy)) {
+            window = BCS_WAVE_ANY(!easy);
+        }
+        if (window) {
             if (!have_hi) d_hi = end_digits(i, s_i);
             const uint32_t d_lo = end_digits(i + 1, s_n);
+            int wb;
             const int w = recv_round_value(pol, v, i, s_n, d_lo, d_hi, home, own, B,
-                                           [&](uint32_t r) { return digits(pol, r); });
+                                           [&](uint32_t r) { return digits(pol, r); }, wb);
             val = easy ? val : w;
-            blk = easy ? blk : (w < 0 ? w + q : q);       // the home round adds nothing: the lap digit's bit
+            blk = easy ? blk : wb;
             d_hi = d_lo;
-            have_hi = true;
-        } else {
-            have_hi = false;
         }
+        have_hi = window;
         const bool active = i < q;                        // per-lane q may be below the wave's bound
         B |= active ? (1u << (blk & 31)) : 0u;
         if (active) emit(i, val);
-        low += (dv >> (i & 31)) & 1u ? s_i : 0u;
+        low += (0u - ((dv >> (i & 31)) & 1u)) & s_i;
         s_i = s_n;
     }
 }
@@ -488,10 +497,11 @@ BCS_HD void recv_row_tab(const Pol &pol, const uint32_t *__restrict__ dtab, uint
         if (BCS_WAVE_ANY(!easy)) {
             const uint32_t d_hi = i <= kAhead ? d[i <= kAhead ? i : 0] : end_point(i);
             const uint32_t d_lo = i + 1 == kQ ? dv : (i + 1 <= kAhead ? d[i + 1 <= kAhead ? i + 1 : 0] : end_point(i + 1));
+            int wb;
             const int w = recv_round_value(pol, v, i, pol.s(i + 1), d_lo, d_hi, home, own, B,
-                                           [&](uint32_t r) { return dtab[r]; });
+                                           [&](uint32_t r) { return dtab[r]; }, wb);
             val = easy ? val : w;
-            blk = easy ? blk : (w < 0 ? w + kQ : kQ);    // the home round adds nothing: the lap digit's bit
+            blk = easy ? blk : wb;
         }
         B |= 1u << (blk & 31);
         emit(i, val);

@@ -573,6 +573,48 @@ def test_send_rule_against_the_look_up_for_every_rank_of_large_p(bcs):
                 assert torch.equal(send[:, k], nb[:, k]), (p, r0, k)
 
 
+def test_rows_from_digits_against_rows_from_windows(bcs):
+    """The one-p kernels take most rounds above level 5 from the rank's own digits; the batch kernel takes every
+    round from its windows.  Every rank of 40 values of p of 8 to 27 bits (random, and with chosen odd levels),
+    each under a random root: the table by bcs_sched_rooted (all ranks: digit masks from the table) and a ragged
+    part of it (digit walks) against bcs_sched_batch on the same ranks."""
+    from test_host_logic import _p_from_bits
+    rng = np.random.default_rng(20220511)
+    ps = [(1 << 20) + 1, (1 << 23) + 1, (1 << 24) + 12345, (1 << 26) - 3, (1 << 27) - 1]
+    while len(ps) < 40:
+        q = int(rng.integers(8, 27))
+        if rng.random() < 0.5:
+            ps.append(int(rng.integers(2**(q - 1) + 1, 2**q)))
+        else:
+            pr = rng.choice([0.1, 0.5, 0.9, 1.0])
+            ps.append(_p_from_bits(q, int(rng.integers(0, 64)), [k for k in range(7, q) if rng.random() < pr]))
+    CH = 1 << 24
+    brecv = torch.empty((CH, bcs.BATCH_STRIDE), dtype=torch.int32, device="cuda")
+    qout = torch.empty(CH, dtype=torch.int32, device="cuda")
+    for p in ps:
+        q = bcs.bcs_q(p)
+        root = int(rng.integers(0, p))
+        full = torch.empty((p, q), dtype=torch.int32, device="cuda")
+        bcs.bcs_sched_rooted(p, root, 0, p, full, None)
+        a = int(rng.integers(0, p))
+        b = min(p, a + int(rng.integers(1, 1 << 20)))
+        part = torch.empty((b - a, q), dtype=torch.int32, device="cuda")
+        bcs.bcs_sched_rooted(p, root, a, b, part, None)
+        torch.cuda.synchronize()
+        assert torch.equal(full[a:b], part), (p, root, a, b)
+        for c0 in range(0, p, CH):
+            n = min(p, c0 + CH) - c0
+            pp = torch.full((n,), p, dtype=torch.int32, device="cuda")
+            rr = torch.arange(c0, c0 + n, dtype=torch.int32, device="cuda")
+            ro = torch.full((n,), root, dtype=torch.int32, device="cuda")
+            bcs.bcs_sched_batch(pp, rr, ro, brecv[:n], None, qout[:n])
+            torch.cuda.synchronize()
+            assert torch.equal(full[c0:c0 + n], brecv[:n, :q]), (p, root, c0)
+        del full, part
+    bcs.bcs_release()
+    torch.cuda.empty_cache()
+
+
 def test_batch_edge_rows(bcs, oracle):
     """Invalid triples are flagged on the device; a ragged count; single outputs."""
     p = np.array([1, 2, 2, 0, 5, 5, 2**31 - 1, 7, -3, 9], dtype=np.int32)
