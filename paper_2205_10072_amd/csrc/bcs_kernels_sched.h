@@ -297,12 +297,87 @@ __global__ __launch_bounds__(kLookupLanes) void k_send_lookup(const SkipTab tab,
 
 // K1b: send rows of ranks [r0, r1) with no neighbour rows at hand (Alg. 5): entry i is entry i of the
 // receive schedule of the to-neighbour, which costs that neighbour's rounds 0..i.
+// Work lists for send entries left to Alg. 5 (k_send_recompute, k_batch).  Each lane working down its own entries
+// makes a wave run as many turns as its unluckiest lane has entries, each turn as far as the largest k any lane asked
+// for; so the entries named by the lanes' masks (bit k of lane L: entry (L, k)) are made one list of the workgroup,
+// ranked by k and then by lane, and handed out one entry a lane: neighbouring places hold entries of the same k (and,
+// in the batch kernel, whose lanes are in the order of q, of neighbouring q), and a wave's loops run about as far as
+// each of its lanes needs.  Entry (L, k) goes to place
+// kstart[k] + (entries for k in earlier waves) + (earlier lanes of L's wave with bit k), found with ballots.  The
+// list is filled and handed out QUEUE entries at a time (QUEUE a multiple of BLOCK, the workgroup's lanes), one entry a lane: fn(has, who, k) runs in every lane of
+// every wave that has an entry.  All lanes of the workgroup must call this (it synchronises them).
+template <int BLOCK, int QUEUE, class Fn>
+__device__ __forceinline__ void work_list(uint32_t mask, uint32_t (*wcnt)[32], uint32_t *kstart, uint16_t *queue, Fn fn) {
+    static_assert(QUEUE % BLOCK == 0 && BLOCK % 64 == 0 && BLOCK <= 2048, "whole waves; a lane index and k share 16 bits");
+    const int wave = threadIdx.x >> 6;
+    // the k for which any lane of this wave has an entry (wave-uniform): the loops below visit only these
+    uint32_t any_k = mask;
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) any_k |= (uint32_t)__shfl_xor((int)any_k, off, 64);
+    any_k = __builtin_amdgcn_readfirstlane(any_k);
+    __syncthreads();                                        // earlier users of wcnt / kstart / queue are done
+    {
+        uint32_t mine = 0;                                  // lane k of a wave: the wave's entries for k
+        for (uint32_t m = any_k; m != 0u; m &= m - 1u) {
+            const int k = __builtin_ctz(m);
+            const uint32_t c = (uint32_t)__popcll(__ballot((mask >> k) & 1u));
+            mine = (threadIdx.x & 63u) == (uint32_t)k ? c : mine;
+        }
+        if ((threadIdx.x & 63u) < 32u) wcnt[wave][threadIdx.x & 63u] = mine;
+    }
+    __syncthreads();
+    if (threadIdx.x < 32) {                                 // entries for k = threadIdx.x: running count over the waves
+        uint32_t acc = 0;
+        for (int w = 0; w < BLOCK / 64; ++w) {
+            const uint32_t c = wcnt[w][threadIdx.x];
+            wcnt[w][threadIdx.x] = acc;
+            acc += c;
+        }
+        kstart[threadIdx.x] = acc;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        uint32_t acc = 0;
+        for (int k = 0; k < 32; ++k) {
+            const uint32_t c = kstart[k];
+            kstart[k] = acc;
+            acc += c;
+        }
+        kstart[32] = acc;
+    }
+    __syncthreads();
+    const uint32_t total = kstart[32];
+    for (uint32_t base = 0; base < total; base += QUEUE) {
+        for (uint32_t m = any_k; m != 0u; m &= m - 1u) {
+            const int k = __builtin_ctz(m);
+            const uint64_t bal = __ballot((mask >> k) & 1u);
+            const uint32_t before = __builtin_amdgcn_mbcnt_hi((uint32_t)(bal >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)bal, 0u));
+            const uint32_t place = kstart[k] + wcnt[wave][k] + before - base;
+            if (((mask >> k) & 1u) && place < (uint32_t)QUEUE) queue[place] = (uint16_t)((threadIdx.x << 5) | (uint32_t)k);
+        }
+        __syncthreads();
+        const uint32_t n = total - base < (uint32_t)QUEUE ? total - base : (uint32_t)QUEUE;
+        for (uint32_t e0 = 0; e0 < n; e0 += BLOCK) {   // workgroup-uniform
+            if (e0 + (threadIdx.x & ~63u) >= n) continue;    // a wave with no entry left (wave-uniform)
+            const uint32_t e = e0 + threadIdx.x;
+            const bool has = e < n;
+            const uint32_t entry = has ? queue[e] : 0u;
+            fn(has, entry >> 5, has ? (int)(entry & 31u) : -1);
+        }
+        __syncthreads();                                    // the next part of the list overwrites the queue
+    }
+}
+
+constexpr int kRecomputeQueue = 4 * kBlock;                // entries of k_send_recompute's work list held at a time
+
 template <int Q, bool TAB>
 __global__ __launch_bounds__(kBlock) void k_send_recompute(const SkipTab tab, uint32_t root, uint32_t r0, uint32_t r1,
                                                            int32_t *__restrict__ send_out,
                                                            const uint32_t *__restrict__ dtab) {
     __shared__ __align__(16) int8_t tile[kBlock * Q + 16];   // one byte an entry, laid out like the table
     __shared__ uint32_t lowtab[kLowShapeBytes / 4];
+    __shared__ uint32_t wcnt[kBlock / 64][32], kstart[33];    // the work list of the entries left to Alg. 5
+    __shared__ uint16_t queue[kRecomputeQueue];
     Uniform<Q> pol;
 #pragma unroll
     for (int k = 0; k <= Q; ++k) pol.S[k] = tab.s[k];
@@ -325,11 +400,10 @@ __global__ __launch_bounds__(kBlock) void k_send_recompute(const SkipTab tab, ui
         else return digits(pol, y);
     };
     uint32_t pending = send_row_direct(pol, v, digits_of(v), digits_of, [&](int k, int val) { my[k] = (int8_t)val; });
-    // Alg. 5 for the rest: every lane works down its own list, largest k first; the wave computes rounds
-    // 0..(largest k asked for) of each lane's neighbour and a lane keeps the entry of its own k
-    while (__any(pending != 0u)) {
-        const int kk = 31 - __clz((int)pending);              // -1: this lane has nothing left
-        pending &= ~(kk >= 0 ? 1u << kk : 0u);
+    pending = live ? pending : 0u;                            // lanes past the end replay the root and ask for nothing
+    // Alg. 5 for the rest, as a work list of the workgroup: a lane takes one entry (of any rank of the tile), the
+    // wave computes rounds 0..(its largest k) of each lane's to-neighbour and a lane keeps the entry of its own k
+    work_list<kBlock, kRecomputeQueue>(pending, wcnt, kstart, queue, [&](bool has, uint32_t who, int kk) {
         int kmax = kk;
 #pragma unroll
         for (int off = 32; off >= 1; off >>= 1) {
@@ -337,15 +411,19 @@ __global__ __launch_bounds__(kBlock) void k_send_recompute(const SkipTab tab, ui
             kmax = other > kmax ? other : kmax;
         }
         kmax = __builtin_amdgcn_readfirstlane(kmax);
+        // the rank the entry belongs to: the tile's ranks are consecutive
+        const uint64_t idx2 = first + (has ? who : threadIdx.x);
+        const uint32_t r2 = idx2 < count ? (uint32_t)(r0 + idx2) : root;
+        const uint32_t v2 = r2 >= root ? r2 - root : r2 + p - root;
         // skips[kk] by the closed form of Alg. 1's halving (kk differs from lane to lane)
-        uint32_t t = v + (kk >= 0 ? ((p - 1u) >> (Q - kk)) + 1u : 0u);
+        uint32_t t = v2 + (kk >= 0 ? ((p - 1u) >> (Q - kk)) + 1u : 0u);
         t = t >= p ? t - p : t;
         int32_t got = 0;
         auto own_entry = [&](int j, int val) { got = (j == kk) ? val : got; };
         if constexpr (TAB) recv_row_tab_upto(pol, dtab, t, dtab[t], kmax, own_entry);
         else recv_row(pol, t, kmax, own_entry);
-        if (kk >= 0) my[kk] = (int8_t)got;
-    }
+        if (has) tile[who * Q + kk] = (int8_t)got;
+    });
     __syncthreads();
     const uint64_t rows = (count - first) < (uint64_t)kBlock ? (count - first) : (uint64_t)kBlock;
     byte_tile_to_rows<Q>(tile, (uint32_t)rows, send_out + first * Q);
@@ -363,6 +441,7 @@ __global__ __launch_bounds__(kBlock) void k_send_recompute(const SkipTab tab, ui
 constexpr int kBatchBlock = 1024;
 constexpr int kBatchRowBytes = BCS_BATCH_STRIDE + 4;       // LDS row stride: nine words, so lanes' rows spread over the banks
 constexpr int8_t kBatchPadByte = -128;
+constexpr int kQueue = 4 * kBatchBlock;                    // entries of the Alg. 5 work list held at a time
 
 // the workgroup's byte tile -> rows of the table (after a barrier); `rows` = triples of this workgroup that exist
 __device__ __forceinline__ void batch_rows_out(const int8_t *tileB, uint32_t rows, int32_t *__restrict__ dst) {
@@ -390,6 +469,39 @@ __device__ __forceinline__ void batch_rows_out(const int8_t *tileB, uint32_t row
     }
 }
 
+// One entry of a work list of the batch kernel, as the lane that works on it sees it: the triple `who` of the
+// workgroup (its p and rank from the sorted arrays), the entry's k, the to-neighbour t = (v + skips[k]) mod p, and
+// a policy whose level loops run as far as the wave's largest q; kmax is the wave's largest k.  Lanes without an
+// entry (has = false, kk = -1) stand in with p = 1.
+struct BatchLane {
+    PerLane pol;
+    uint32_t t, orig;
+    int kmax;
+};
+__device__ __forceinline__ BatchLane batch_lane(bool has, uint32_t who, int kk, const uint32_t *s_p, const uint32_t *s_v,
+                                                const uint32_t *s_slot) {
+    BatchLane e;
+    const uint32_t p = has ? s_p[who] : 1u, v = has ? s_v[who] : 0u;
+    e.orig = s_slot[who] & 0xffffu;
+    const int q = ceil_log2(p);
+    int kmax = kk, qtop = q;
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+        const int ok = __shfl_xor(kmax, off, 64), oq = __shfl_xor(qtop, off, 64);
+        kmax = ok > kmax ? ok : kmax;
+        qtop = oq > qtop ? oq : qtop;
+    }
+    e.kmax = __builtin_amdgcn_readfirstlane(kmax);
+    e.pol.pm1 = p - 1u;
+    e.pol.ql = q;
+    e.pol.wave_top = __builtin_amdgcn_readfirstlane(qtop) - 1;
+    e.pol.odd = odd_levels(p, q);
+    e.pol.low = g_lowtab + (size_t)low_shape(p, q) * kLowShapeBytes;
+    const uint32_t t = v + (kk >= 0 ? e.pol.s(kk) : 0u);
+    e.t = t >= p ? t - p : t;
+    return e;
+}
+
 __global__ __launch_bounds__(kBatchBlock) void k_batch(int64_t count, const int32_t *__restrict__ pv,
                                                        const int32_t *__restrict__ rv,
                                                        const int32_t *__restrict__ rootv,
@@ -399,6 +511,9 @@ __global__ __launch_bounds__(kBatchBlock) void k_batch(int64_t count, const int3
     __shared__ uint32_t start[33];
     __shared__ uint32_t s_p[kBatchBlock], s_v[kBatchBlock], s_slot[kBatchBlock];
     __shared__ __align__(16) int8_t tileB[kBatchBlock * kBatchRowBytes];
+    __shared__ uint32_t wcnt[kBatchBlock / 64][32];            // send entries left to Alg. 5: per wave and k, then their offsets
+    __shared__ uint32_t kstart[33];
+    __shared__ uint16_t queue[kQueue];                         // the work list: (lane << 5) | k
     const int64_t first = (int64_t)blockIdx.x * kBatchBlock;
     {
         const int64_t idx = first + threadIdx.x;
@@ -468,29 +583,21 @@ __global__ __launch_bounds__(kBatchBlock) void k_batch(int64_t count, const int3
     if (send_out) {
 #pragma unroll
         for (int w = 0; w < BCS_BATCH_STRIDE / 4; ++w) my4[w] = pad4;
-        // the entries that need none of the to-neighbour's rounds; the others (a carry of v + skips[k] met an odd
-        // level: about a third) are left in `pending`
-        uint32_t pending = send_row_direct(pol, v, digits(pol, v), [&](uint32_t y) { return digits(pol, y); },
-                                           [&](int k, int val) { my[k] = (int8_t)val; });
-        // Alg. 5 for those: each lane works down its own list, largest k first, so that the lanes of a wave ask
-        // for rows of similar length; the wave computes rounds 0..(largest k asked for) and every lane keeps
-        // the entry of its own k (receive rows are prefix-stable, the extra rounds change nothing)
-        while (__any(pending != 0u)) {
-            const int kk = 31 - __clz((int)pending);              // -1: this lane has nothing left
-            pending &= ~(kk >= 0 ? 1u << kk : 0u);
-            int kmax = kk;
-#pragma unroll
-            for (int off = 32; off >= 1; off >>= 1) {
-                const int other = __shfl_xor(kmax, off, 64);
-                kmax = other > kmax ? other : kmax;
-            }
-            kmax = __builtin_amdgcn_readfirstlane(kmax);
-            uint32_t t = v + (kk >= 0 ? pol.s(kk) : 0u);
-            t = t >= p ? t - p : t;
+        // the entries that need none of the to-neighbour's rounds (send_row_direct); the others are left in `pending`
+        const uint32_t pending = send_row_direct(pol, v, digits(pol, v), [&](uint32_t y) { return digits(pol, y); },
+                                                 [&](int k, int val) { my[k] = (int8_t)val; });
+        // Those are worked off as one list of the whole workgroup, one entry a lane.  (Each lane working down its
+        // own entries made a wave run as many turns as its unluckiest lane has entries, each turn as far as the
+        // largest k any lane asked for: five times the lane-operations the entries themselves need, by a count on
+        // the C5 triples, where a triple leaves 1.8 entries on average, nearly all below level 8.)
+        // Alg. 5 for the rest: rounds 0..k of the to-neighbour's receive row, of which entry k is kept (a wave
+        // computes as many rounds as its largest k; receive rows are prefix-stable, the extra rounds change nothing)
+        work_list<kBatchBlock, kQueue>(pending, wcnt, kstart, queue, [&](bool has, uint32_t who, int kk) {
+            const BatchLane e = batch_lane(has, who, kk, s_p, s_v, s_slot);
             int32_t keep = 0;
-            recv_row(pol, t, kmax, [&](int j, int val) { keep = (j == kk) ? val : keep; });
-            if (kk >= 0) my[kk] = (int8_t)keep;
-        }
+            recv_row(e.pol, e.t, e.kmax, [&](int j, int val) { keep = (j == kk) ? val : keep; });
+            if (has) tileB[e.orig * kBatchRowBytes + kk] = (int8_t)keep;
+        });
         __syncthreads();
         batch_rows_out(tileB, rows, send_out + first * BCS_BATCH_STRIDE);
     }
