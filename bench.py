@@ -51,24 +51,24 @@ def csrc_digest():
 # Key: (config, kernel).  `csrc`: csrc_digest() of the sources that were profiled; when the sources have changed
 # since, the record is still printed but marked "stale": true, and a warning goes to stderr.
 PROFILED = {
-    "csrc": "ba28eb247fe814cd",
+    "csrc": "f33fb0306a61c98a",
     "source": "profiles/c2_step_p1048577_n256.md, c3_sched_p134217727.md, c4_expand_p65537_n4096.md, c5_batch_2e20.md, "
               "allgather_tables_p1048577_n256.md",
     "counters": {
         # per dispatch: FETCH_SIZE / WRITE_SIZE in KiB as read, SQ_WAVES, SQ_INSTS_VALU / SQ_WAVES, SQ_INSTS_SALU / SQ_WAVES,
         # SQ_THREAD_CYCLES_VALU / SQ_ACTIVE_INST_VALU (lanes active per vector instruction, of 64)
-        ("C3", "k_digits"): {'fetch_kib': 28, 'write_kib': 524288, 'waves': 2097152, 'valu_per_wave': 90.0, 'salu_per_wave': 25.5, 'active_lanes': 64.0},
-        ("C3", "k_recv_uniform"): {'fetch_kib': 1048874, 'write_kib': 17694790, 'waves': 2097152, 'valu_per_wave': 882.9, 'salu_per_wave': 525.4, 'active_lanes': 64.0},
-        ("C3", "k_send_lookup"): {'fetch_kib': 2031795, 'write_kib': 14155949, 'waves': 524288, 'valu_per_wave': 1002.0, 'salu_per_wave': 626.0, 'active_lanes': 64.0},
+        ("C3", "k_digits"): {'fetch_kib': 34, 'write_kib': 524288, 'waves': 2097152, 'valu_per_wave': 90.0, 'salu_per_wave': 25.5, 'active_lanes': 64.0},
+        ("C3", "k_recv_uniform"): {'fetch_kib': 1048884, 'write_kib': 17694812, 'waves': 2097152, 'valu_per_wave': 882.9, 'salu_per_wave': 525.4, 'active_lanes': 64.0},
+        ("C3", "k_send_lookup"): {'fetch_kib': 2031794, 'write_kib': 14155945, 'waves': 524288, 'valu_per_wave': 1002.0, 'salu_per_wave': 626.0, 'active_lanes': 64.0},
         ("C2", "k_digits"): {'fetch_kib': 31, 'write_kib': 4096, 'waves': 16388, 'valu_per_wave': 72.0, 'salu_per_wave': 25.5, 'active_lanes': 64.0},
-        ("C2", "k_recv_uniform"): {'fetch_kib': 7270, 'write_kib': 132104, 'waves': 16388, 'valu_per_wave': 1025.4, 'salu_per_wave': 564.5, 'active_lanes': 64.0},
-        ("C2", "k_send_lookup"): {'fetch_kib': 21071, 'write_kib': 110660, 'waves': 8193, 'valu_per_wave': 1126.9, 'salu_per_wave': 446.0, 'active_lanes': 63.2},
-        ("C2", "k_expand_rows"): {'fetch_kib': 35337, 'write_kib': 1130597, 'waves': 1130500, 'valu_per_wave': 69.0, 'salu_per_wave': 9.0, 'active_lanes': 64.0},
-        ("C4", "k_expand"): {'fetch_kib': 9008, 'write_kib': 1052688, 'waves': 263176, 'valu_per_wave': 258.5, 'salu_per_wave': 195.0, 'active_lanes': 63.3},
+        ("C2", "k_recv_uniform"): {'fetch_kib': 7266, 'write_kib': 132108, 'waves': 16388, 'valu_per_wave': 1025.4, 'salu_per_wave': 564.5, 'active_lanes': 64.0},
+        ("C2", "k_send_lookup"): {'fetch_kib': 21066, 'write_kib': 110661, 'waves': 8193, 'valu_per_wave': 1126.9, 'salu_per_wave': 446.0, 'active_lanes': 63.2},
+        ("C2", "k_expand_rows"): {'fetch_kib': 35345, 'write_kib': 1130589, 'waves': 1130500, 'valu_per_wave': 69.0, 'salu_per_wave': 9.0, 'active_lanes': 64.0},
+        ("C4", "k_expand"): {'fetch_kib': 9007, 'write_kib': 1052688, 'waves': 263176, 'valu_per_wave': 258.5, 'salu_per_wave': 195.0, 'active_lanes': 63.3},
         ("C4", "k_rows_to_bytes"): {'fetch_kib': 2252, 'write_kib': 1280, 'waves': 5124, 'valu_per_wave': 50.0, 'salu_per_wave': 12.0, 'active_lanes': 64.0},
-        ("C4", "k_expand_rows"): {'fetch_kib': 5127, 'write_kib': 1052932, 'waves': 1052692, 'valu_per_wave': 69.0, 'salu_per_wave': 9.0, 'active_lanes': 64.0},
-        ("C5 recv_and_send", "k_batch"): {'fetch_kib': 8495, 'write_kib': 266240, 'waves': 16384, 'valu_per_wave': 11522.8, 'salu_per_wave': 3684.2, 'active_lanes': 63.8},
-        ("C5 recv_only", "k_batch"): {'fetch_kib': 8406, 'write_kib': 135168, 'waves': 16384, 'valu_per_wave': 2813.4, 'salu_per_wave': 872.8, 'active_lanes': 63.8},
+        ("C4", "k_expand_rows"): {'fetch_kib': 5135, 'write_kib': 1052908, 'waves': 1052692, 'valu_per_wave': 69.0, 'salu_per_wave': 9.0, 'active_lanes': 64.0},
+        ("C5 recv_and_send", "k_batch"): {'fetch_kib': 9269, 'write_kib': 266240, 'waves': 16384, 'valu_per_wave': 6627.1, 'salu_per_wave': 2415.6, 'active_lanes': 63.5},
+        ("C5 recv_only", "k_batch"): {'fetch_kib': 8404, 'write_kib': 135168, 'waves': 16384, 'valu_per_wave': 2813.4, 'salu_per_wave': 872.8, 'active_lanes': 63.8},
         ("AG", "k_allgather_tables"): {"fetch_kib": 41280, "write_kib": 2261412},
     },
 }
@@ -107,8 +107,9 @@ def profiled(config, kernel, digest):
 #   a send row by Alg. 5: entry i = rounds 0..i of the to-neighbour's row: sum over i of (i + 3) walks (or table
 #   reads) + 55 (i + 1) + 30
 #   a send row as the batch kernel builds it: 30 ops an entry for the rule that takes an entry from the rank's own
-#   digits, Alg. 5 for the entries below level 8 (where the rule's margin leaves no room); the rarer entries above
-#   that fall back to Alg. 5 are not counted
+#   digits, one digit walk a round for its case (c), and Alg. 5 for the entries the rule leaves: 0.23 an entry below
+#   level 8 (1.8 a triple at C5, counted on the host build of the lane code), each the neighbour's rounds 0..k with
+#   k + 3 walks, plus 40 ops to fetch the entry from the workgroup's list
 # ----------------------------------------------------------------------------------------------------------------
 def ops_walk(q, per_lane):
     return (4 * max(q - 7, 0) + 10) if per_lane else (3 * max(q - 7, 0) + 3)
@@ -141,10 +142,11 @@ def ops_send_alg5(q, per_lane, tabled=False):
 
 
 def ops_send_direct(q, per_lane):
-    total = 30 * q
-    for i in range(min(q, 8)):
-        total += (i + 3) * ops_walk(q, per_lane) + 55 * (i + 1) + 30
-    return total
+    w = ops_walk(q, per_lane)
+    low = min(q, 8)
+    entries = 0.23 * low                       # entries left to Alg. 5
+    rounds = low / 2.0 + 0.5                   # their average k + 1
+    return 30 * q + q * w + entries * (rounds * (55 + w) + 3 * w + 40)
 
 
 def measure_valu_peak(torch, bcs):

@@ -520,6 +520,38 @@ def test_batch_send_rows_where_the_direct_rule_is_at_its_limits(bcs, oracle):
             assert np.array_equal(got, want), (p, root, r0, r1)
 
 
+def test_batch_with_more_left_over_send_entries_than_the_work_list_holds(bcs, oracle):
+    """The batch kernel works the send entries that need Alg. 5 off as a list of the workgroup, 4096 entries at a
+    time.  Triples picked (with the host build of the same lane code) so that every workgroup of 1024 has more than
+    that: ranks of p = 2^16+1 and 2^20+1 with seven or more such entries each."""
+    import hostcheck
+    rng = np.random.default_rng(77)
+    ps, vs = [], []
+    for p, span in ((2**16 + 1, 2**16 + 1), (2**20 + 1, 300000)):
+        q = (p - 1).bit_length()
+        ranks = np.arange(span, dtype=np.int32)
+        _, direct = hostcheck.send_rows_list(p, ranks, want_direct=True)
+        left = q - np.array([bin(int(x) & ((1 << q) - 1)).count("1") for x in direct])
+        many = ranks[left >= 7]
+        assert len(many) >= 2048
+        pick = rng.choice(many, 2048, replace=False)
+        assert left[pick].reshape(2, 1024).sum(axis=1).min() > 4096 + 1024     # more than one filling of the list
+        ps += [p] * 2048
+        vs += pick.tolist()
+    p_arr = np.array(ps, dtype=np.int32)
+    v_arr = np.array(vs, dtype=np.int64)
+    root = (rng.integers(0, 2**31 - 1, len(p_arr)) % p_arr).astype(np.int32)
+    r_arr = ((v_arr + root) % p_arr).astype(np.int32)
+    orecv, osend, oq = oracle.sched_batch(p_arr, r_arr, root, threads=16)
+    d = [torch.from_numpy(a).cuda() for a in (p_arr, r_arr, root)]
+    recv, send = dev_tables(len(p_arr), 32)
+    qv = torch.empty(len(p_arr), dtype=torch.int32, device="cuda")
+    bcs.bcs_sched_batch(d[0], d[1], d[2], recv, send, qv)
+    torch.cuda.synchronize()
+    assert np.array_equal(recv.cpu().numpy(), orecv)
+    assert np.array_equal(send.cpu().numpy(), osend)
+
+
 def test_send_rule_against_the_look_up_for_every_rank_of_large_p(bcs):
     """Send rows of parts of the ranks (taken from the ranks' own digits where the rule applies, Alg. 5 otherwise)
     against send rows of all ranks by look-up in the receive table, which is their definition (Alg. 9, second loop):
