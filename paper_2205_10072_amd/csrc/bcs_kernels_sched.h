@@ -47,29 +47,6 @@ __device__ __forceinline__ void byte_rows_out(const int8_t *tileB, uint32_t rows
     if (e < n4) reinterpret_cast<int32_t *>(dst)[e] = reinterpret_cast<const int32_t *>(tileB)[e];
 }
 
-// Rows of a workgroup's LDS tile (row stride Q | 1) to their place in a rank-major table.  For odd Q the tile is
-// already laid out like the table, so it leaves as 16-byte pieces with no index arithmetic.
-template <int Q>
-__device__ __forceinline__ void tile_to_rows(const int32_t *tile, uint32_t rows, int32_t *__restrict__ dst) {
-    constexpr int kStride = Q | 1;
-    const uint32_t n = rows * Q;
-    if constexpr (kStride == Q) {
-        if ((reinterpret_cast<uintptr_t>(dst) & 15u) == 0) {
-            const uint32_t n4 = n >> 2;
-            for (uint32_t g = threadIdx.x; g < n4; g += kBlock)
-                __builtin_nontemporal_store(reinterpret_cast<const v4i *>(tile)[g], reinterpret_cast<v4i *>(dst) + g);
-            const uint32_t e = (n4 << 2) + threadIdx.x;
-            if (e < n) dst[e] = tile[e];
-            return;
-        }
-    }
-    for (uint32_t e = threadIdx.x; e < n; e += kBlock) {
-        const uint32_t row = e / Q, col = e - row * Q;
-        dst[e] = tile[row * kStride + col];
-    }
-}
-
-
 // Rows of a workgroup's LDS tile of bytes (rank-major, Q bytes a rank, so the tile is the table's piece with one byte
 // an entry) to their place in the rank-major int32 table: a lane reads four bytes, widens them and writes 16 bytes.
 template <int Q>
