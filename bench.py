@@ -552,6 +552,50 @@ def bench_partner_tables(torch, bcs, args):
     return out
 
 
+def bench_shard(torch, bcs, args):
+    """One GPU's share of C3 when the ranks are spread over eight GPUs with no exchange: ranks [0, p/8) of p = 2^27-1,
+    receive rows and send rows without the other ranks' receive rows (entries from the ranks' own digits where the
+    rule allows, Alg. 5 for the rest)."""
+    p = P_C3
+    q = bcs.bcs_q(p)
+    r0, r1 = 0, (p + 7) // 8
+    rows = r1 - r0
+    recv = torch.empty((rows, q), dtype=torch.int32, device="cuda")
+    send = torch.empty((rows, q), dtype=torch.int32, device="cuda")
+    ws = torch.empty(max(1, bcs.bcs_sched_workspace_bytes(p, r0, r1)), dtype=torch.uint8, device="cuda")
+
+    def step():
+        bcs.bcs_sched_rooted_ws(p, ROOT_RANK, r0, r1, recv, send, ws)
+
+    steps = max(1, min(args.steps, 100))
+    ms, ms_ev, timing = timed_steps(torch, bcs, step, steps, args.warmup)
+    kernels = {k: {"avg_ms": v[0] / v[1], "launches_per_step": v[1] / steps} for k, v in timing.items()}
+    name = max(kernels, key=lambda k: kernels[k]["avg_ms"] * kernels[k]["launches_per_step"])
+    out = {
+        "metric": "rank-schedules constructed/s on one GPU's share of the ranks, no rows of other ranks",
+        "value": rows / (ms * 1e-3), "unit": "rank-schedules/s",
+        "n_gpus": 1, "steps": steps, "warmup": args.warmup, "ms_per_step": ms,
+        "ms_per_step_with_kernel_events": ms_ev,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int32", "data": "synthetic",
+        "config": {"workload": "ranks [0, p/8) of p=2^27-1 (q=27): the digit masks of all ranks, receive rows of the share, "
+                               "send rows of the share without the other ranks", "p": p, "q": q, "ranks": rows},
+        "roofline": {"kernel": name, "bound": "alu", "achieved": None, "peak": INT_VALU_PEAK_GOPS, "unit": "Gop/s",
+                     "frac": None, "traffic": None, "avg_ms": kernels[name]["avg_ms"],
+                     "note": "no counter profile of this workload: times only"},
+        "kernels_ms": {k: v["avg_ms"] for k, v in kernels.items()},
+        "csrc": csrc_digest(),
+    }
+    if not args.no_cpu_baseline:
+        import oracle
+        sample, threads = 1 << 22, cpu_threads()
+        t0 = time.perf_counter()
+        oracle.sched_range(p, root=ROOT_RANK, r0=r0, r1=r0 + sample, threads=threads)
+        el = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": sample / el, "unit": "rank-schedules/s", "cores": threads, "kind": "oracle",
+                               "sample": "the first 2^22 ranks of the share: recv by Alg. 4, send by Alg. 5, %.1f s" % el}
+    return out
+
+
 PACK_P = 1152              # the paper's largest run: 36 nodes x 32 processes
 
 
@@ -693,12 +737,12 @@ def main():
                     help="timed steps of the headline configuration (C3); the other configurations time min(steps, 100)")
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--workload", choices=["configs", "allgather-tables", "pack-round", "partner-tables"],
+    ap.add_argument("--workload", choices=["configs", "allgather-tables", "pack-round", "partner-tables", "shard"],
                     default="configs",
                     help="configs (default): the hot path on the baseline's configurations C2..C5, headline on C3.  "
                          "allgather-tables: the first widening, Alg. 9's pack/unpack index tables of one process, "
                          "reported as its own line.  pack-round: the second, packing and unpacking one round's message "
-                         "on irregular buffers.  partner-tables: the to/from tables of Alg. 7 and Alg. 8 for all processes")
+                         "on irregular buffers.  partner-tables: the to/from tables of Alg. 7 and Alg. 8 for all processes.  shard: one GPU's share of C3 (an eighth of the ranks) built without the other ranks")
     ap.add_argument("--only", default="C3,C2,C4,C5",
                     help="comma-separated subset of C2,C3,C4,C5 to run (for profiler runs; the headline needs C3)")
     ap.add_argument("--graph", action="store_true",
@@ -725,6 +769,9 @@ def main():
         return
     if args.workload == "partner-tables":
         print(json.dumps(bench_partner_tables(torch, bcs, args)))
+        return
+    if args.workload == "shard":
+        print(json.dumps(bench_shard(torch, bcs, args)))
         return
     only = [c.strip().upper() for c in args.only.split(",") if c.strip()]
     for c in only:
