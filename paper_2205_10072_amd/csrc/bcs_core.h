@@ -371,9 +371,11 @@ BCS_HD void recv_round(const Pol &pol, uint32_t v, int i, uint32_t s_n, uint32_t
 //     from the next digit j above (the lap digit when there is none), which sets digits i..j-1 and lowers the low
 //     part by the number o of odd levels in [i, j); this is case (b) of send_row_direct with the low part low - o,
 //     and the test here allows for every o from 0 to the number of odd levels from i up.
-// Like (b) and (c) there these are observations checked against the oracle (every rank of every p the CPU tests
-// run this code on, and the full-size configurations on the GPU), not proved statements.  Low rounds rarely
-// agree across the 64 ranks of a wave, so the test starts at round kDigitRoundsFrom.
+// Like (b) and (c) there these are observations, not proved statements: checked against the oracle (every rank of
+// every p the CPU tests run this code on, the full-size configurations on the GPU) and, on the GPU, against rows
+// taken from windows throughout (the batch kernel) for every rank of every p up to 2^22 and for slices of tens of
+// thousands of larger p.  Low rounds rarely agree across the 64 ranks of a wave, so the test starts at round
+// kDigitRoundsFrom.
 constexpr int kDigitRoundsFrom = 6;
 constexpr int kTabAhead = 10;                           // recv_row_tab reads the end points of rounds below this ahead
 

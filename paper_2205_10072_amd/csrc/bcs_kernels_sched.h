@@ -67,9 +67,10 @@ __device__ __forceinline__ void byte_tile_to_rows(const int8_t *tile, uint32_t r
 }
 
 // ----------------------------------------------------------------------------------------------
-// K1: receive rows of ranks [r0, r1), uniform p.  Lane = rank.  Rows are staged in LDS (odd stride,
-// conflict-free) and leave as contiguous dwords; optionally each entry is also stored slot-major
-// (recvT[k][r - r0]) for the send look-up that follows.
+// K1: receive rows of ranks [r0, r1), uniform p.  Lane = rank.  Rows are staged in LDS as bytes, laid out like
+// the table, and leave widened to int32 in 16-byte pieces; optionally the entries are also kept slot-major
+// (recvT[k][r - r0], one byte each) for the send look-up that follows, staged the same way and written as one
+// aligned 256-byte piece a slot.  Bytes instead of int32 in LDS is what lets eight workgroups share a compute unit.
 // ----------------------------------------------------------------------------------------------
 // K0: the digit mask of every rank (one walk each), for launches over all ranks: every end point of every
 // window of Alg. 4 is some rank, so K1 then reads its digit masks instead of walking (q+2 walks a row otherwise).
