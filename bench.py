@@ -712,9 +712,30 @@ def bench_pack_round(torch, bcs, args):
         planned_round_rows()
     torch.cuda.synchronize()
     planned_us = (time.perf_counter() - t0) * 1e6 / steps
+    # the same rounds recorded into one HIP graph (consecutive rounds, each with its own plan rows): inside a graph
+    # the kernels follow each other without the few microseconds that separate two launches of a stream
+    g_rounds = min(256, R - j)
+    g_rows = [(offs[j + i], srcs[j + i]) for i in range(g_rounds)]
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            for o, s in g_rows:
+                bcs.bcs_pack_round_planned(o, s, c["data"], c["msg"])
+                bcs.bcs_unpack_round_planned(o, s, c["data"], c["msg"], c["length"])
+    torch.cuda.synchronize()
+    graph.replay()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(10):
+        graph.replay()
+    torch.cuda.synchronize()
+    graph_us = (time.perf_counter() - t0) * 1e6 / (10 * g_rounds)
+    del graph
     out["paper_shaped"]["planned"] = {"plan_all_rounds_ms": plan_ms[0] / plan_ms[1], "plan_first_call_ms": plan_first_ms,
                                       "rounds": R, "plan_bytes": int(offs.numel() + srcs.numel()) * 8,
-                                      "pack_plus_unpack_us": planned_us}
+                                      "pack_plus_unpack_us": planned_us,
+                                      "pack_plus_unpack_us_in_hip_graph": graph_us, "graph_rounds": g_rounds}
     del pack_t, unpack_t, offs, srcs
     if not args.no_cpu_baseline:
         import oracle
