@@ -361,21 +361,29 @@ BCS_HD void recv_round(const Pol &pol, uint32_t v, int i, uint32_t s_n, uint32_t
     if (active) emit(i, val);
 }
 
-// Rounds that need no window (one p per launch).  With D(v) the digit mask of the rank and low the value of its
-// digits below i, round i's entry is
+// Rounds that need no window (one p per launch).  With D(v) the digit mask of the rank, low the value of its
+// digits below i and c the number of odd levels below i, round i's entry is
 //   - the rank's baseblock when i is its highest digit (Alg. 4's first branch);
-//   - (next digit of v above i) - q when digit i is set: v - skips[i] then has the digits of v without digit i
-//     and is the case "adding the skip leaves the low digits alone" of send_row_direct below, seen from the
-//     receiving side;
+//   - (next digit j of v above i) - q when digit i is set and low >= c.  The rank w = v - skips[i] - low has the
+//     digits of v above i and nothing below (taking digits out of a greedy sum leaves a greedy sum), so its
+//     baseblock is j; low < skips[i+1] - skips[i] puts it into the round's first window, whose other end has digit
+//     j clear, so j is the window's largest block; and v cannot have come by block j before: its own baseblock
+//     is at or below i, the earlier rounds' windows lie above v - skips[i] except for round i-1's second range,
+//     which reaches fewer than c ranks below it (and w lies low ranks below), and the next rank with baseblock j
+//     is more than 2 skips[i] above w;
 //   - i - q when digit i is clear and low keeps clear of the ends of its range: taking skips[i] from v borrows
 //     from the next digit j above (the lap digit when there is none), which sets digits i..j-1 and lowers the low
-//     part by the number o of odd levels in [i, j); this is case (b) of send_row_direct with the low part low - o,
-//     and the test here allows for every o from 0 to the number of odd levels from i up.
-// Like (b) and (c) there these are observations, not proved statements: checked against the oracle (every rank of
-// every p the CPU tests run this code on, the full-size configurations on the GPU) and, on the GPU, against rows
-// taken from windows throughout (the batch kernel) for every rank of every p up to 2^22 and for slices of tens of
-// thousands of larger p.  Low rounds rarely agree across the 64 ranks of a wave, so the test starts at round
-// kDigitRoundsFrom.
+//     part by the number o of odd levels in [i, j) (skips[j] - skips[i] = sum of skips[i..j-1] minus o).  With
+//     low' = low - o >= 0: the rank w = v - skips[i] - low' has lowest digit i and lies in the first window when
+//     low' < skips[i+1] - skips[i]; every other rank of the window shares the digits above i and has a lower
+//     lowest digit; and block i is new: v's baseblock is not i, the earlier rounds reach down to
+//     v - skips[i] - c + 1 only, which misses w when low' >= c, and the next rank with lowest digit i lies
+//     skips[i+1] - (odd levels in [i+1, j)) above w, past v.  The test allows for every o from 0 to the number of
+//     odd levels from i up and keeps twice the margin this needs (it is case (b) of send_row_direct below).
+// Both are also checked against the oracle (every rank of every p the CPU tests run this code on, the full-size
+// configurations on the GPU) and, on the GPU, against rows taken from windows throughout (the batch kernel) for
+// every rank of every p up to 2^22 and for slices of tens of thousands of larger p.  Low rounds rarely agree
+// across the 64 ranks of a wave, so the test starts at round kDigitRoundsFrom.
 constexpr int kDigitRoundsFrom = 6;
 constexpr int kTabAhead = 10;                           // recv_row_tab reads the end points of rounds below this ahead
 
@@ -397,7 +405,8 @@ BCS_HD bool round_from_digits(const Pol &pol, uint32_t dl, int i, uint32_t s_i, 
     blk = (int)((m & next) | (~m & (uint32_t)i));
     val = i == home ? own : blk - q;
     const uint32_t x = (low - (uint32_t)c1 - 1u) & ~m;
-    return m != 0u || x < width;
+    const uint32_t cbelow = (uint32_t)__builtin_popcount(odd & ((1u << (i & 31)) - 1u));   // odd levels below i
+    return (m != 0u && low >= cbelow) || x < width;
 }
 
 template <class Pol, class Emit>
