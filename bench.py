@@ -51,24 +51,24 @@ def csrc_digest():
 # Key: (config, kernel).  `csrc`: csrc_digest() of the sources that were profiled; when the sources have changed
 # since, the record is still printed but marked "stale": true, and a warning goes to stderr.
 PROFILED = {
-    "csrc": "1ccf6309b3007b19",
+    "csrc": "f7b790bceae31f3a",
     "source": "profiles/c2_step_p1048577_n256.md, c3_sched_p134217727.md, c4_expand_p65537_n4096.md, c5_batch_2e20.md, "
               "allgather_tables_p1048577_n256.md",
     "counters": {
         # per dispatch: FETCH_SIZE / WRITE_SIZE in KiB as read, SQ_WAVES, SQ_INSTS_VALU / SQ_WAVES, SQ_INSTS_SALU / SQ_WAVES,
         # SQ_THREAD_CYCLES_VALU / SQ_ACTIVE_INST_VALU (lanes active per vector instruction, of 64)
         ("C3", "k_digits"): {'fetch_kib': 28, 'write_kib': 524288, 'waves': 2097152, 'valu_per_wave': 90.0, 'salu_per_wave': 25.5, 'active_lanes': 64.0},
-        ("C3", "k_recv_uniform"): {'fetch_kib': 1048887, 'write_kib': 17694846, 'waves': 2097152, 'valu_per_wave': 915.4, 'salu_per_wave': 470.4, 'active_lanes': 63.9},
-        ("C3", "k_send_lookup"): {'fetch_kib': 2031793, 'write_kib': 14155968, 'waves': 524288, 'valu_per_wave': 1002.0, 'salu_per_wave': 626.0, 'active_lanes': 64.0},
+        ("C3", "k_recv_uniform"): {'fetch_kib': 1048881, 'write_kib': 17694827, 'waves': 2097152, 'valu_per_wave': 915.4, 'salu_per_wave': 470.4, 'active_lanes': 63.9},
+        ("C3", "k_send_lookup"): {'fetch_kib': 2031794, 'write_kib': 14155972, 'waves': 524288, 'valu_per_wave': 1002.0, 'salu_per_wave': 626.0, 'active_lanes': 64.0},
         ("C2", "k_digits"): {'fetch_kib': 31, 'write_kib': 4096, 'waves': 16388, 'valu_per_wave': 72.0, 'salu_per_wave': 25.5, 'active_lanes': 64.0},
-        ("C2", "k_recv_uniform"): {'fetch_kib': 7275, 'write_kib': 132109, 'waves': 16388, 'valu_per_wave': 1055.4, 'salu_per_wave': 546.5, 'active_lanes': 63.7},
-        ("C2", "k_send_lookup"): {'fetch_kib': 21069, 'write_kib': 110660, 'waves': 8193, 'valu_per_wave': 1126.9, 'salu_per_wave': 446.0, 'active_lanes': 63.2},
-        ("C2", "k_expand_rows"): {'fetch_kib': 35345, 'write_kib': 1130592, 'waves': 1130500, 'valu_per_wave': 69.0, 'salu_per_wave': 9.0, 'active_lanes': 64.0},
+        ("C2", "k_recv_uniform"): {'fetch_kib': 7278, 'write_kib': 132104, 'waves': 16388, 'valu_per_wave': 1055.4, 'salu_per_wave': 546.5, 'active_lanes': 63.7},
+        ("C2", "k_send_lookup"): {'fetch_kib': 21069, 'write_kib': 110656, 'waves': 8193, 'valu_per_wave': 1126.9, 'salu_per_wave': 446.0, 'active_lanes': 63.2},
+        ("C2", "k_expand_rows"): {'fetch_kib': 35345, 'write_kib': 1130584, 'waves': 1130500, 'valu_per_wave': 69.0, 'salu_per_wave': 9.0, 'active_lanes': 64.0},
         ("C4", "k_expand"): {'fetch_kib': 9004, 'write_kib': 1052688, 'waves': 263176, 'valu_per_wave': 258.5, 'salu_per_wave': 195.0, 'active_lanes': 63.3},
         ("C4", "k_rows_to_bytes"): {'fetch_kib': 2252, 'write_kib': 1280, 'waves': 5124, 'valu_per_wave': 50.0, 'salu_per_wave': 12.0, 'active_lanes': 64.0},
-        ("C4", "k_expand_rows"): {'fetch_kib': 5135, 'write_kib': 1052926, 'waves': 1052692, 'valu_per_wave': 69.0, 'salu_per_wave': 9.0, 'active_lanes': 64.0},
-        ("C5 recv_and_send", "k_batch"): {'fetch_kib': 9274, 'write_kib': 266240, 'waves': 16384, 'valu_per_wave': 6627.2, 'salu_per_wave': 2415.7, 'active_lanes': 63.5},
-        ("C5 recv_only", "k_batch"): {'fetch_kib': 8412, 'write_kib': 135168, 'waves': 16384, 'valu_per_wave': 2813.4, 'salu_per_wave': 872.8, 'active_lanes': 63.8},
+        ("C4", "k_expand_rows"): {'fetch_kib': 5135, 'write_kib': 1052924, 'waves': 1052692, 'valu_per_wave': 69.0, 'salu_per_wave': 9.0, 'active_lanes': 64.0},
+        ("C5 recv_and_send", "k_batch"): {'fetch_kib': 9272, 'write_kib': 266240, 'waves': 16384, 'valu_per_wave': 6627.2, 'salu_per_wave': 2415.7, 'active_lanes': 63.5},
+        ("C5 recv_only", "k_batch"): {'fetch_kib': 8406, 'write_kib': 135168, 'waves': 16384, 'valu_per_wave': 2813.4, 'salu_per_wave': 872.8, 'active_lanes': 63.8},
         ("AG", "k_allgather_tables"): {"fetch_kib": 41280, "write_kib": 2261412},
     },
 }

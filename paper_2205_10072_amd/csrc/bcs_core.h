@@ -571,8 +571,10 @@ BCS_HD void recv_row_tab_upto(const Pol &pol, const uint32_t *__restrict__ dtab,
 //       the margin is more than twice that;
 //   (c) when the digits of t below k are those of v (adding the skip did not disturb them): no exception in the
 //       same searches.
-// (b) and (c) are observations with the argument above, not proved statements; the CPU tests compare this code
-// with Alg. 5 of the oracle entry by entry (every rank of every p <= 1500, of every p <= 40 000 behind the slow
+// (b) is what round_from_digits argues for receive rounds, read from the sender (digit k of v clear: t has digit k
+// set and the same low part; set: the addition carries, t has digit k clear and the low part L plus the odd levels
+// the carry passes); (c) goes beyond it and is an observation, not a proved statement.  The CPU tests compare this
+// code with Alg. 5 of the oracle entry by entry (every rank of every p <= 1500, of every p <= 40 000 behind the slow
 // marker, and structured large p).  Everything else -- L near an end of its range and low digits disturbed by a
 // carry that met an odd level -- is left to Alg. 5: the return value has bit k set for every entry k < q that was
 // NOT emitted.
