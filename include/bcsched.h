@@ -150,7 +150,9 @@ int bcs_sched_rooted_static(int32_t p, int32_t root, int32_t r0, int32_t r1,
  *   recv_out, send_out: device, count x BCS_BATCH_STRIDE int32; row i holds
  *   q_i = ceil(log2 p[i]) entries, the rest BCS_BATCH_PAD.  Either may be NULL.
  *   q_out: device, count int32, may be NULL.
- * Send rows are recomputed per Alg. 5 (no other rank of that graph is there).
+ * Send rows need no other rank of that graph: an entry is taken from the rank's
+ * own greedy digits where that gives Alg. 5's value, and recomputed per Alg. 5
+ * (the to-neighbour's rounds up to it) otherwise; the results are Alg. 5's.
  * Triples are validated on the device: a row with p < 1 or r, root outside
  * [0, p) gets q_out = -1 and all-PAD rows; host-side errors are BCS_EINVAL for
  * count < 0, a NULL input array, or all outputs NULL. */
